@@ -1,0 +1,168 @@
+/*
+ * piperag.h - C ABI of the MI355X IVF-PQ retrieval library.
+ *
+ * The library implements the retrieval step of retrieval-augmented generation as
+ * the paper states it: a query vector goes in, the k closest database entries
+ * (ids and distances) come out (Section 2, "Database construction").  The index
+ * is IVF-PQ (Section 3.2, S3): the database is clustered into nlist inverted
+ * lists, each vector is stored as a product-quantisation code of M bytes
+ * (Section 3.1, O3; Appendix "Detailed Evaluation Setup", Software), and a query
+ * scans the nprobe lists whose centres are closest to it.  nprobe is the knob
+ * the paper's performance model tunes; piperag_latency_profile measures the
+ * nprobe -> latency relation that model is fitted on.
+ *
+ * Conventions
+ *   - Every function returns PIPERAG_OK (0) or a negative error code and never
+ *     throws or aborts; piperag_last_error() gives a thread-local message.
+ *   - Pointers named *_dev are device (HBM) memory owned by the caller, row-major,
+ *     contiguous, 16-byte aligned.  Pointers named *_host are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls that take a stream enqueue their work on it; unless stated otherwise
+ *     they return without waiting, and results are valid once the caller has
+ *     synchronised that stream.  The search calls allocate nothing.
+ *   - Distance is squared L2 (no square root).  The PQ code quantises the raw
+ *     vector (not its residual to the list centre), 8 bits per sub-quantiser.
+ *   - An index must not be searched from two streams at once: the search
+ *     workspace belongs to the index.
+ */
+#ifndef PIPERAG_H
+#define PIPERAG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIPERAG_OK 0
+#define PIPERAG_ERR_ARG (-1)   /* null pointer, size out of range, wrong state */
+#define PIPERAG_ERR_OOM (-2)   /* device or host allocation failed */
+#define PIPERAG_ERR_HIP (-3)   /* a HIP runtime call failed */
+#define PIPERAG_ERR_FILE (-4)  /* unreadable, truncated or malformed index file */
+#define PIPERAG_ERR_LIMIT (-5) /* nq / nprobe / k / ntotal beyond the limits given at creation */
+
+typedef struct piperag_index piperag_index; /* opaque; owns its device memory and search workspace */
+
+typedef struct piperag_params {
+    int32_t d;          /* vector dimension, multiple of M */
+    int32_t nlist;      /* number of inverted lists (coarse centres), 1 .. 2^20 */
+    int32_t M;          /* sub-quantisers = bytes per code, 1 .. 128 */
+    int32_t nbits;      /* bits per sub-quantiser; must be 8 */
+    int64_t ntotal;     /* create: capacity in vectors (add fails beyond it); load: ignored */
+    int32_t max_nq;     /* largest query batch a search call may pass (>= 1) */
+    int32_t max_nprobe; /* largest nprobe (1 .. min(nlist, 1024)) */
+    int32_t max_k;      /* largest k (1 .. 1024) */
+} piperag_params;
+
+/* ---- index life cycle ------------------------------------------------------------------- */
+
+/* Reads an index file (layout below) into HBM and makes it searchable.  Only max_nq, max_nprobe and
+ * max_k of `limits` are used.  File, little-endian: 64-byte header = "PRAGIVF1", u32 version (1), u32 d,
+ * u32 nlist, u32 M, u32 nbits (8), u32 0, u64 ntotal, zero padding; then centres f32 [nlist*d]; codebooks
+ * f32 [M*256*(d/M)]; list lengths i64 [nlist]; codes u8 [ntotal*M], list after list; ids i64 [ntotal] in
+ * the same order.  On success *out owns everything; free with piperag_ivf_free. */
+int piperag_ivf_load(const char *path, const piperag_params *limits, piperag_index **out);
+
+/* Creates an empty index from trained parameters (Section 3.2, S3: the clustering into nlist lists; the
+ * product quantiser of Section 3.1, O3).  centroids_host: f32 [nlist*d]; pq_codebook_host: f32
+ * [M*256*(d/M)], sub-quantiser-major.  Both are copied. */
+int piperag_ivf_create(const piperag_params *params, const float *centroids_host, const float *pq_codebook_host,
+                       piperag_index **out);
+
+/* Database construction (Section 2; Appendix, Software: each vector becomes a list number and M code
+ * bytes): encodes n vectors x_dev f32 [n*d] on the GPU and appends them.  list(x) = nearest centre,
+ * code[m] = nearest of the 256 centres of sub-quantiser m to the m-th slice of x; on equal distances the
+ * lower index.  ids_dev: i64 [n] or NULL for consecutive ids continuing from the number already added.
+ * Enqueues on `stream`; x_dev and ids_dev must stay valid until the stream has passed the call. */
+int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream);
+
+/* Appends n already-encoded vectors: lists_dev i32 [n] (each in 0..nlist-1, checked), codes_dev u8 [n*M],
+ * ids_dev i64 [n] or NULL.  Synchronises `stream` (for the check). */
+int piperag_ivf_add_encoded(piperag_index *index, const int32_t *lists_dev, const uint8_t *codes_dev,
+                            const int64_t *ids_dev, int64_t n, void *stream);
+
+/* Groups everything added so far into inverted lists (inside a list: order of addition) and builds the
+ * scan layout.  Synchronises `stream`; allocates.  Afterwards the index is searchable and closed to adds. */
+int piperag_ivf_finalize(piperag_index *index, void *stream);
+
+/* Writes a finalized index in the file layout of piperag_ivf_load. */
+int piperag_ivf_save(const piperag_index *index, const char *path);
+
+void piperag_ivf_free(piperag_index *index);
+
+/* ---- search ----------------------------------------------------------------------------- */
+
+/* Batched IVF-PQ search (Section 3.2, S3: nprobe of the nlist lists are selected and the vectors inside
+ * them are compared with the query; Section 2: the k closest are returned).
+ *   queries_dev f32 [nq*d];  out_dist_dev f32 [nq*k];  out_ids_dev i64 [nq*k].
+ * Per query: ascending by (distance, id); distance = sum over m of the squared distance between the
+ * query's m-th slice and the centre the code selects; when the probed lists hold fewer than k vectors
+ * the remaining slots are id -1, distance +inf.  1 <= nq <= max_nq, 1 <= nprobe <= min(nlist,
+ * max_nprobe), 1 <= k <= max_k, else PIPERAG_ERR_LIMIT / PIPERAG_ERR_ARG.  nq == 0 is a no-op. */
+int piperag_ivfpq_search(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
+                         int32_t k, float *out_dist_dev, int64_t *out_ids_dev, void *stream);
+
+/* The performance model's retrieval side (Section 3.2, S3: search latency is modelled by linear
+ * regression on nprobe): runs the search above for each nprobes_host[i] (`reps` timed repetitions after
+ * two warm-up runs, HIP events on `stream`), writes the median latency in milliseconds to
+ * out_p50_ms_host[i] and the least-squares line latency = fit[0] + fit[1]*nprobe to out_fit_host[2].
+ * Synchronises `stream`.  Scratch outputs for the searches are taken from the index workspace. */
+int piperag_latency_profile(const piperag_index *index, const float *queries_dev, int32_t nq,
+                            const int32_t *nprobes_host, int32_t n_nprobes, int32_t k, int32_t reps,
+                            float *out_p50_ms_host, float *out_fit_host, void *stream);
+
+/* ---- stage taps (each step of the search path by itself, for checking) ------------------- */
+
+/* Coarse quantiser (the index-scan term of the latency model, Section 3.2, S3): the nprobe closest
+ * centres per query ordered by (distance, list).  out_lists_dev i32 [nq*nprobe]; out_dist_dev f32
+ * [nq*nprobe] or NULL. */
+int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
+                       int32_t *out_lists_dev, float *out_dist_dev, void *stream);
+
+/* Per-query lookup tables: out_lut_dev f32 [nq*M*256], entry [q][m][j] = squared distance between the
+ * m-th slice of query q and centre j of sub-quantiser m. */
+int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_t nq, float *out_lut_dev,
+                    void *stream);
+
+/* Search with the probe lists given by the caller instead of the coarse quantiser: probes_dev i32
+ * [nq*nprobe]; an entry outside 0..nlist-1, or equal to an earlier entry of the same query, is skipped. */
+int piperag_ivfpq_search_probes(const piperag_index *index, const float *queries_dev, int32_t nq,
+                                const int32_t *probes_dev, int32_t nprobe, int32_t k, float *out_dist_dev,
+                                int64_t *out_ids_dev, void *stream);
+
+/* Encoder by itself (no append): out_lists_dev i32 [n], out_codes_dev u8 [n*M]; either may be NULL. */
+int piperag_ivf_encode(const piperag_index *index, const float *x_dev, int64_t n, int32_t *out_lists_dev,
+                       uint8_t *out_codes_dev, void *stream);
+
+/* Copies one inverted list to the host in canonical form (row i = the M code bytes of its i-th vector).
+ * *len_out receives the length; codes_host (u8 [len*M]) and ids_host (i64 [len]) may be NULL to query
+ * the length only.  Synchronous. */
+int piperag_ivf_get_list(const piperag_index *index, int32_t list, int64_t *len_out, uint8_t *codes_host,
+                         int64_t *ids_host);
+
+/* Lengths of all lists: out_host i64 [nlist].  Synchronous. */
+int piperag_ivf_list_lengths(const piperag_index *index, int64_t *out_host);
+
+/* Work done by the most recent search call on this index (valid after its stream has been
+ * synchronised): vectors compared and their code bytes (vectors * M). */
+int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, int64_t *scanned_code_bytes);
+
+/* Per-stage timing of the retrieval latency model's terms (Section 3.2, S3: index scan + vector scan).
+ * When enabled, every search call records HIP events around its stages on its stream;
+ * piperag_stage_times synchronises on them and writes the most recent call's milliseconds:
+ * [0] coarse distances, [1] top-nprobe selection and scan plan, [2] lookup-table build, [3] list scan
+ * with k-selection, [4] merge and id gather.  Stages [0]+[1] are the index-scan term, [2]..[4] the
+ * vector-scan term. */
+#define PIPERAG_NSTAGES 5
+int piperag_set_stage_timing(piperag_index *index, int enable);
+int piperag_stage_times(const piperag_index *index, float *out_ms_host /* [PIPERAG_NSTAGES] */);
+
+/* Number of vectors in the index. */
+int64_t piperag_ivf_ntotal(const piperag_index *index);
+
+const char *piperag_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPERAG_H */

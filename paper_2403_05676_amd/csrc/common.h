@@ -1,0 +1,91 @@
+// Internal definitions shared by the translation units of libpiperag (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#pragma GCC visibility push(default)
+#include "../../include/piperag.h"
+#pragma GCC visibility pop
+
+namespace piperag {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kBlockVecs = 64;     // vectors per code block (one per lane)
+constexpr int kKsub = 256;         // centres per sub-quantiser (8-bit codes)
+constexpr int kMaxK = 1024;
+constexpr int kMaxNprobe = 1024;
+constexpr int kScanThreads = 256;  // 4 waves per scan workgroup
+constexpr int kScanWaves = kScanThreads / kWave;
+constexpr int kQueueCap = 128;     // per-wave candidate queue (flushed when more than 64 are pending)
+constexpr int kTargetScanWGs = 2048;
+constexpr int kMaxSegments = 1024;
+constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
+
+void set_error(const char *fmt, ...);
+
+#define PR_CHECK_HIP(expr)                                                                     \
+    do {                                                                                       \
+        hipError_t e__ = (expr);                                                               \
+        if (e__ != hipSuccess) {                                                               \
+            piperag::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+            return e__ == hipErrorOutOfMemory ? PIPERAG_ERR_OOM : PIPERAG_ERR_HIP;             \
+        }                                                                                      \
+    } while (0)
+
+#define PR_REQUIRE(cond, code, ...)          \
+    do {                                     \
+        if (!(cond)) {                       \
+            piperag::set_error(__VA_ARGS__); \
+            return (code);                   \
+        }                                    \
+    } while (0)
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+}  // namespace piperag
+
+// The index object.  Code storage ("scan layout"): vectors are grouped list after list into blocks of 64
+// slots (a list starts on a block boundary; unused slots of its last block have id -1 and zero codes).
+// With Mp = M rounded up to a multiple of 16, block b occupies bytes [b*64*Mp, (b+1)*64*Mp) laid out as
+// [chunk c < Mp/16][lane < 64][16 bytes]; byte t = 16*c + u of lane l is code byte (l + t) mod Mp of the
+// vector in slot 64*b + l (zero when that index is >= M).  One 16-byte load per lane per chunk is thus a
+// contiguous 1 KiB wavefront access, and at step t the 64 lanes look up 64 different sub-quantisers.
+struct piperag_index {
+    piperag_params p;
+    int dsub, Mp, device;
+    // trained parameters (device)
+    float *centroids;  // [nlist*d]
+    float *pq;         // [M*256*dsub]
+    // staging area, filled by add / add_encoded until finalize
+    int64_t cap, nadded;
+    int32_t *st_list;   // [cap]
+    uint8_t *st_codes;  // [cap*M] canonical rows
+    int64_t *st_ids;    // [cap]
+    bool finalized;
+    // scan layout (after finalize)
+    int64_t ntotal, nblocks;
+    uint8_t *codes;     // [nblocks*64*Mp]
+    int64_t *ids;       // [nblocks*64]
+    int32_t *list_blk;  // [nlist+1] first block of each list
+    int32_t *list_len;  // [nlist]
+    // search workspace
+    float *ws_D;          // [max_nq*nlist]
+    int32_t *ws_probe;    // [max_nq*max_nprobe]
+    float *ws_probe_d;    // [max_nq*max_nprobe]
+    int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
+    int64_t *ws_scanned;  // [max_nq]
+    float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
+    uint64_t *ws_part;    // [(kTargetScanWGs+max_nq)*max_k] per-workgroup partial results
+    float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
+    int64_t *ws_out_i;    // [max_nq*max_k]
+    int *flag;            // [1] device flag for argument checks
+    int32_t last_nq;
+    // stage timing
+    bool timing;
+    hipEvent_t ev[PIPERAG_NSTAGES + 1];
+    bool ev_valid;
+};

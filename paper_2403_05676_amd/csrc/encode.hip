@@ -1,0 +1,204 @@
+// Database construction on the GPU (Section 2, "Database construction"; Appendix "Detailed Evaluation
+// Setup", Software: every vector is assigned to one of nlist inverted lists and quantised into M code
+// bytes).  list(x) = argmin_j ||x - centre_j||^2, code[m] = argmin_j ||x_m - pq[m][j]||^2, both in the
+// direct (difference) form in fp32, lowest index on equal values.
+#include "common.h"
+
+using namespace piperag;
+
+namespace piperag {
+int check_can_add(piperag_index *ix, int64_t n);
+int append_ids(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStream_t st);
+}  // namespace piperag
+
+namespace {
+
+constexpr int TM = 64, TN = 64, TK = 16, LDT = 68;   // tile of rows x centres x coordinates; padded LDS stride
+
+// Nearest-centre assignment.  One workgroup = 64 rows of x against all centres, 64 at a time; each thread
+// accumulates a 4x4 patch of squared differences from coordinate-major LDS tiles.
+__global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x, int64_t n, int d,
+                                                     const float *__restrict__ cent, int nlist,
+                                                     int32_t *__restrict__ out_idx) {
+    __shared__ __align__(16) float xs[TK * LDT];
+    __shared__ __align__(16) float cs[TK * LDT];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int64_t row0 = (int64_t)blockIdx.x * TM;
+    const int lr = tid >> 2, lk = (tid & 3) * 4;          // this thread loads 4 coordinates of row lr of each tile
+    const bool vec4 = (d & 3) == 0;
+
+    float best_d[4];
+    int best_j[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { best_d[i] = __builtin_inff(); best_j[i] = 0; }
+
+    for (int j0 = 0; j0 < nlist; j0 += TN) {
+        float acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) acc[i][jj] = 0.f;
+
+        for (int k0 = 0; k0 < d; k0 += TK) {
+            float xv[4] = {0.f, 0.f, 0.f, 0.f}, cv[4] = {0.f, 0.f, 0.f, 0.f};
+            const int64_t xr = row0 + lr;
+            const int cr = j0 + lr;
+            const int kk = k0 + lk;
+            if (vec4) {
+                if (xr < n && kk < d) {
+                    const float4 v = *reinterpret_cast<const float4 *>(x + xr * d + kk);
+                    xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w;
+                }
+                if (cr < nlist && kk < d) {
+                    const float4 v = *reinterpret_cast<const float4 *>(cent + (size_t)cr * d + kk);
+                    cv[0] = v.x; cv[1] = v.y; cv[2] = v.z; cv[3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (xr < n && kk + i < d) xv[i] = x[xr * d + kk + i];
+                    if (cr < nlist && kk + i < d) cv[i] = cent[(size_t)cr * d + kk + i];
+                }
+            }
+            __syncthreads();                      // previous tile fully consumed
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                xs[(lk + i) * LDT + lr] = xv[i];
+                cs[(lk + i) * LDT + lr] = cv[i];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < TK; ++k) {
+                const float4 a = *reinterpret_cast<const float4 *>(&xs[k * LDT + ty * 4]);
+                const float4 b = *reinterpret_cast<const float4 *>(&cs[k * LDT + tx * 4]);
+                const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float diff = av[i] - bv[jj];
+                        acc[i][jj] += diff * diff;
+                    }
+            }
+        }
+        // argmin over this tile's 64 centres for each of the thread's 4 rows, then over the 16 threads of the row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float bd = __builtin_inff();
+            int bj = 0x7FFFFFFF;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int j = j0 + tx * 4 + jj;
+                if (j < nlist && acc[i][jj] < bd) { bd = acc[i][jj]; bj = j; }
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                const float od = __shfl_xor(bd, off, 64);
+                const int oj = __shfl_xor(bj, off, 64);
+                if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+            }
+            if (bd < best_d[i]) { best_d[i] = bd; best_j[i] = bj; }
+        }
+    }
+    if (tx == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t r = row0 + ty * 4 + i;
+            if (r < n) out_idx[r] = best_j[i];
+        }
+    }
+}
+
+// PQ encoding.  One workgroup = 256 rows; for each sub-quantiser the 256 centres and the rows' slices are
+// staged in LDS and every thread scans the centres for its row.  Codes are collected in LDS and written
+// out as one contiguous run.
+__global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict__ x, int64_t n, int d,
+                                                        const float *__restrict__ pq, int M, int dsub,
+                                                        uint8_t *__restrict__ out_codes) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *cs = reinterpret_cast<float *>(smem);              // [256][dsub]
+    float *xs = cs + kKsub * dsub;                             // [dsub][256]
+    uint8_t *code_s = reinterpret_cast<uint8_t *>(xs + dsub * 256);   // [256][M]
+    const int tid = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.x * 256;
+    const int rows = (int)min<int64_t>(256, n - row0);
+    for (int m = 0; m < M; ++m) {
+        __syncthreads();
+        for (int i = tid; i < kKsub * dsub; i += 256) cs[i] = pq[(size_t)m * kKsub * dsub + i];
+        for (int e = tid; e < 256 * dsub; e += 256) {
+            const int r = e / dsub, t = e - r * dsub;
+            xs[t * 256 + r] = r < rows ? x[(row0 + r) * d + m * dsub + t] : 0.f;
+        }
+        __syncthreads();
+        float best = __builtin_inff();
+        int bj = 0;
+        for (int j = 0; j < kKsub; ++j) {
+            float acc = 0.f;
+            for (int t = 0; t < dsub; ++t) {
+                const float diff = xs[t * 256 + tid] - cs[j * dsub + t];
+                acc += diff * diff;
+            }
+            if (acc < best) { best = acc; bj = j; }
+        }
+        code_s[tid * M + m] = (uint8_t)bj;
+    }
+    __syncthreads();
+    uint8_t *dst = out_codes + (size_t)row0 * M;
+    for (int i = tid; i < rows * M; i += 256) dst[i] = code_s[i];
+}
+
+int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
+    const piperag_params &p = ix->p;
+    PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
+    constexpr int64_t kSlice = 1 << 22;              // rows per launch
+    for (int64_t a = 0; a < n; a += kSlice) {
+        const int64_t cnt = n - a < kSlice ? n - a : kSlice;
+        if (out_lists)
+            hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * p.d, cnt, p.d,
+                               ix->centroids, p.nlist, out_lists + a);
+        if (out_codes) {
+            const size_t lds = sizeof(float) * 2 * kKsub * ix->dsub + (size_t)256 * p.M;
+            static size_t configured = 0;
+            if (lds > configured) {
+                PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&pq_encode_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                configured = lds;
+            }
+            hipLaunchKernelGGL(pq_encode_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), lds, st, x + a * p.d, cnt, p.d,
+                               ix->pq, p.M, ix->dsub, out_codes + (size_t)a * p.M);
+        }
+    }
+    PR_CHECK_HIP(hipGetLastError());
+    return PIPERAG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int piperag_ivf_encode(const piperag_index *index, const float *x_dev, int64_t n, int32_t *out_lists_dev,
+                       uint8_t *out_codes_dev, void *stream) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    PR_REQUIRE(n >= 0, PIPERAG_ERR_ARG, "n = %lld is negative", (long long)n);
+    if (n == 0) return PIPERAG_OK;
+    PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
+    PR_CHECK_HIP(hipSetDevice(index->device));
+    return encode_impl(index, x_dev, n, out_lists_dev, out_codes_dev, (hipStream_t)stream);
+}
+
+int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream) {
+    int rc = check_can_add(index, n);
+    if (rc != PIPERAG_OK || n == 0) return rc;
+    PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    PR_CHECK_HIP(hipSetDevice(index->device));
+    rc = encode_impl(index, x_dev, n, index->st_list + index->nadded, index->st_codes + (size_t)index->nadded * index->p.M, st);
+    if (rc != PIPERAG_OK) return rc;
+    rc = append_ids(index, n, ids_dev, st);
+    if (rc != PIPERAG_OK) return rc;
+    index->nadded += n;
+    PR_CHECK_HIP(hipGetLastError());
+    return PIPERAG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,305 @@
+"""GPU parity: every step of the HIP path against the CPU oracle on the same seeded inputs, through the
+C ABI (paper_2403_05676_amd.binding -> libpiperag.so)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import parity
+from workload import gen
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def P():
+    import paper_2403_05676_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_problem(N, d, nlist, M, seed, ncomp=16, sigma=0.3, iters=4, nq=16, zipf=0.0):
+    cfg = gen.WorkloadConfig(f"t{seed}", seed, ncomp, zipf, sigma, N, d, nlist, M, min(N, 20000), nq, 1, 1)
+    x = gen.database(cfg)
+    q = gen.queries(cfg, nq)
+    S = min(N, 20000)
+    ci = gen.draw_distinct_rows(S, nlist, seed)
+    pi = [gen.draw_distinct_rows(S, 256, seed + 1 + m) for m in range(M)]
+    coarse, pq = oracle.train(x[:S], nlist, M, ci, pi, iters=iters)
+    return cfg, x, q, coarse, pq
+
+
+def gpu_index_from_oracle(pkg, oidx: oracle.Index, **limits):
+    """Library index holding exactly the oracle's lists (so that search parity does not depend on encoding ties)."""
+    ix = pkg.Index.ivf_create(oidx.coarse, oidx.pq, oidx.ntotal, **limits)
+    lists = np.repeat(np.arange(oidx.nlist, dtype=np.int32), np.diff(oidx.list_off))
+    ix.ivf_add_encoded(dev(lists), dev(oidx.codes), dev(oidx.ids))
+    ix.ivf_finalize()
+    return ix
+
+
+def run_search_parity(pkg, ix, oidx, q, nprobe, k):
+    qd = dev(q)
+    gl, gdist = ix.ivf_coarse(qd, nprobe)
+    torch.cuda.synchronize()
+    gl, gdist = gl.cpu().numpy(), gdist.cpu().numpy()
+    ex_p = parity.check_probes(gl, gdist, q, oidx.coarse, nprobe)
+    od, oi = ix.ivfpq_search(qd, nprobe, k)
+    torch.cuda.synchronize()
+    od, oi = od.cpu().numpy(), oi.cpu().numpy()
+    ex_k, max_rel = parity.check_topk(od, oi, oidx, q, gl, k)
+    scanned, nbytes = ix.search_stats()
+    assert scanned == int(np.diff(oidx.list_off)[gl].sum())
+    assert nbytes == scanned * oidx.M
+    return ex_p, ex_k, max_rel
+
+
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def cfg0():
+    cfg = gen.CONFIGS["cfg0"]
+    x = gen.database(cfg)
+    q = gen.queries(cfg)
+    ci = gen.draw_distinct_rows(cfg.train_sample, cfg.nlist, cfg.seed)
+    pi = [gen.draw_distinct_rows(cfg.train_sample, 256, cfg.seed + 1 + m) for m in range(cfg.M)]
+    coarse, pq = oracle.train(x, cfg.nlist, cfg.M, ci, pi, iters=cfg.kmeans_iters)
+    oidx = oracle.make_index(x, coarse, pq)
+    return cfg, x, q, oidx
+
+
+def test_cfg0_lut_and_coarse_taps(cfg0):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = gpu_index_from_oracle(pkg, oidx)
+    qd = dev(q)
+    lut = ix.ivf_lut(qd)
+    torch.cuda.synchronize()
+    ref = oracle.lut(q, oidx.pq)
+    assert np.all(parity.close(lut.cpu().numpy(), ref))
+    gl, gd = ix.ivf_coarse(qd, cfg.nprobe)
+    torch.cuda.synchronize()
+    parity.check_probes(gl.cpu().numpy(), gd.cpu().numpy(), q, oidx.coarse, cfg.nprobe)
+    gl, gd = ix.ivf_coarse(qd, cfg.nlist)            # full ordering of all lists
+    torch.cuda.synchronize()
+    parity.check_probes(gl.cpu().numpy(), gd.cpu().numpy(), q, oidx.coarse, cfg.nlist)
+
+
+def test_cfg0_search_matches_oracle(cfg0):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = gpu_index_from_oracle(pkg, oidx)
+    ex_p, ex_k, max_rel = run_search_parity(pkg, ix, oidx, q, cfg.nprobe, cfg.k)
+    print(f"cfg0: probe ties {ex_p}, top-k ties {ex_k}, max rel dist err {max_rel:.2e}")
+    assert max_rel < 1e-4
+    for nprobe, k in [(1, 1), (3, 100), (cfg.nlist, 10), (17, 128)]:
+        run_search_parity(pkg, ix, oidx, q, nprobe, k)
+    # single query, and a batch that is not a multiple of anything
+    run_search_parity(pkg, ix, oidx, q[:1], 8, 10)
+    run_search_parity(pkg, ix, oidx, q[:7], 8, 10)
+
+
+def test_cfg0_gpu_encode_bit_exact_and_index_structure(cfg0):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = pkg.Index.ivf_create(oidx.coarse, oidx.pq, cfg.N)
+    xd = dev(x)
+    gl, gc = ix.ivf_encode(xd)
+    torch.cuda.synchronize()
+    nl, nc = parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), x, oidx.coarse, oidx.pq)
+    print(f"cfg0 encode: {nl} list and {nc} code-byte differences at ties, of {cfg.N} x {cfg.M}")
+    assert nl <= cfg.N // 1000 and nc <= cfg.N * cfg.M // 1000
+    # add in two uneven batches, then read every list back
+    ix.ivf_add(xd[:40000])
+    ix.ivf_add(xd[40000:])
+    ix.ivf_finalize()
+    assert ix.ivf_ntotal() == cfg.N
+    lens = ix.ivf_list_lengths()
+    assert lens.sum() == cfg.N
+    glists = gl.cpu().numpy()
+    gcodes = gc.cpu().numpy()
+    seen = np.zeros(cfg.N, dtype=bool)
+    for l in range(cfg.nlist):
+        codes, ids = ix.ivf_get_list(l)
+        assert len(ids) == lens[l]
+        assert np.all(np.diff(ids) > 0)                       # order of addition = ascending id
+        assert np.all(glists[ids] == l)                      # every vector sits in the list the encoder chose
+        assert np.array_equal(codes, gcodes[ids])
+        seen[ids] = True
+    assert seen.all()
+    # the oracle searching the GPU-built index gives what the GPU search gives
+    off = np.zeros(cfg.nlist + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    parts = [ix.ivf_get_list(l) for l in range(cfg.nlist)]
+    gidx = oracle.Index(oidx.coarse, oidx.pq, off, np.concatenate([p[0] for p in parts]),
+                        np.concatenate([p[1] for p in parts]))
+    run_search_parity(pkg, ix, gidx, q, cfg.nprobe, cfg.k)
+
+
+def test_index_file_roundtrip(cfg0, tmp_path):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    path = str(tmp_path / "cfg0.ivfpq")
+    oracle.write_index_file(oidx, path)
+    ix = pkg.Index.ivf_load(path, max_nq=64, max_nprobe=64, max_k=32)
+    assert (ix.d, ix.nlist, ix.M) == (cfg.d, cfg.nlist, cfg.M)
+    run_search_parity(pkg, ix, oidx, q, cfg.nprobe, cfg.k)
+    out = str(tmp_path / "saved.ivfpq")
+    ix.ivf_save(out)
+    assert open(out, "rb").read() == open(path, "rb").read()
+    # truncated and corrupt files are rejected with an error code, not a crash
+    raw = open(path, "rb").read()
+    for bad in (raw[:40], raw[:len(raw) // 2], b"XXXXXXXX" + raw[8:]):
+        p2 = str(tmp_path / "bad.ivfpq")
+        open(p2, "wb").write(bad)
+        with pytest.raises(pkg.PiperagError) as e:
+            pkg.Index.ivf_load(p2)
+        assert e.value.code == -4
+
+
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,d,nlist,M,nprobe,k", [
+    (5000, 32, 20, 1, 5, 10),        # one sub-quantiser
+    (5000, 32, 20, 4, 20, 7),        # nprobe = nlist
+    (3000, 24, 50, 8, 9, 100),       # ragged lists, k = 100
+    (20000, 64, 33, 32, 6, 64),      # Mp = 32
+    (20000, 96, 40, 24, 8, 33),      # M not a multiple of 16 (padded to 32)
+    (9000, 96, 25, 48, 5, 20),       # Mp = 48
+    (30000, 256, 64, 64, 12, 100),   # the M = 64 scan kernel
+    (4000, 200, 16, 100, 4, 10),     # M = 100 (padded to 112), d not a multiple of 16
+    (6000, 128, 30, 128, 7, 50),     # largest M
+    (2500, 18, 12, 6, 3, 1000),      # k larger than most candidate sets, d % 4 != 0
+])
+def test_small_shapes_search_and_encode(N, d, nlist, M, nprobe, k):
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(N, d, nlist, M, seed=N + d + M, nq=9)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=64, max_k=1024)
+    run_search_parity(pkg, ix, oidx, q, nprobe, k)
+    ix2 = pkg.Index.ivf_create(coarse, pq, N)
+    gl, gc = ix2.ivf_encode(dev(x))
+    torch.cuda.synchronize()
+    parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), x, coarse, pq)
+
+
+def test_empty_lists_few_candidates_and_given_probes():
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(300, 16, 64, 4, seed=5, nq=12)
+    oidx = oracle.make_index(x[:90], coarse, pq)          # 90 vectors in 64 lists: some lists stay empty
+    lens = np.diff(oidx.list_off)
+    assert (lens == 0).any()
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=64, max_k=64)
+    run_search_parity(pkg, ix, oidx, q, 1, 40)       # most lists hold fewer than 40 vectors -> padding
+    run_search_parity(pkg, ix, oidx, q, 64, 64)
+    # probe lists chosen by the caller, including empty lists and skipped (-1) entries
+    probes = np.full((len(q), 3), -1, dtype=np.int32)
+    probes[:, 0] = int(np.argmin(lens))
+    probes[:, 2] = np.arange(len(q)) % 64
+    od, oi = ix.ivfpq_search_probes(dev(q), dev(probes), 20)
+    torch.cuda.synchronize()
+    parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), oidx, q, probes, 20)
+
+
+def test_identity_codebook_is_exact_search():
+    # dsub = 1, coordinates from a 256-value alphabet that is the codebook: IVF-PQ with nprobe = nlist
+    # must return the exact nearest neighbours
+    pkg = P()
+    rng = np.random.default_rng(12)
+    N, d, nlist = 4000, 16, 10
+    alphabet = np.sort(rng.standard_normal(256)).astype(np.float32)
+    x = alphabet[rng.integers(0, 256, size=(N, d))]
+    q = rng.standard_normal((8, d)).astype(np.float32)
+    pq = np.repeat(alphabet[None, :, None], d, 0)
+    coarse = oracle.kmeans(x, nlist, gen.draw_distinct_rows(N, nlist, 1), 3)
+    ix = pkg.Index.ivf_create(coarse, pq, N, max_nprobe=16, max_k=32)
+    ix.ivf_add(dev(x))
+    ix.ivf_finalize()
+    od, oi = ix.ivfpq_search(dev(q), nlist, 20)
+    torch.cuda.synchronize()
+    bd, bi = oracle.brute_force_knn(x, q, 20)
+    assert np.all(parity.close(od.cpu().numpy(), bd))
+    got = oi.cpu().numpy()
+    for a, b, dist in zip(got, bi, bd):
+        clear = dist < dist[-1] * (1 - parity.RTOL)
+        assert set(b[clear].tolist()) <= set(a.tolist())
+
+
+def test_custom_ids_and_incremental_add():
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(4000, 32, 16, 8, seed=21, nq=5)
+    ids = (np.arange(4000, dtype=np.int64) * 7919 + 10**12)
+    oidx = oracle.make_index(x, coarse, pq, ids=ids)
+    ix = pkg.Index.ivf_create(coarse, pq, 5000, max_k=16)
+    xd, idd = dev(x), dev(ids)
+    for a, b in [(0, 1), (1, 1000), (1000, 1000), (1000, 4000)]:
+        ix.ivf_add(xd[a:b], idd[a:b])
+    ix.ivf_finalize()
+    od, oi = ix.ivfpq_search(dev(q), 4, 10)
+    torch.cuda.synchronize()
+    gl, _ = ix.ivf_coarse(dev(q), 4)
+    torch.cuda.synchronize()
+    parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), oidx, q, gl.cpu().numpy(), 10)
+
+
+def test_argument_errors():
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(500, 16, 8, 4, seed=3, nq=4)
+    ix = pkg.Index.ivf_create(coarse, pq, 500, max_nq=4, max_nprobe=4, max_k=8)
+    qd = dev(q)
+    with pytest.raises(pkg.PiperagError) as e:       # not finalized yet
+        ix.ivfpq_search(qd, 2, 4)
+    assert e.value.code == -1
+    ix.ivf_add(dev(x))
+    with pytest.raises(pkg.PiperagError) as e:       # beyond capacity
+        ix.ivf_add(dev(x[:1]))
+    assert e.value.code == -5
+    ix.ivf_finalize()
+    with pytest.raises(pkg.PiperagError) as e:
+        ix.ivf_add(dev(x[:1]))
+    assert e.value.code == -1
+    for args, code in [((2, 9), -5), ((5, 4), -5), ((9, 4), -1), ((0, 4), -1), ((2, 0), -1)]:
+        with pytest.raises(pkg.PiperagError) as e:
+            ix.ivfpq_search(qd, *args)
+        assert e.value.code == code, args
+    with pytest.raises(pkg.PiperagError) as e:       # more queries than max_nq
+        ix.ivfpq_search(torch.cat([qd, qd]), 2, 4)
+    assert e.value.code == -5
+    od, oi = ix.ivfpq_search(qd[:0], 2, 4)           # nq = 0 is a no-op
+    assert od.shape == (0, 4)
+    bad = dev(np.array([0, 99], dtype=np.int32))
+    ix3 = pkg.Index.ivf_create(coarse, pq, 10)
+    with pytest.raises(pkg.PiperagError) as e:       # list number out of range
+        ix3.ivf_add_encoded(bad, dev(np.zeros((2, 4), np.uint8)))
+    assert e.value.code == -1
+    with pytest.raises(ValueError):
+        pkg.Index.ivf_create(coarse, pq[:, :100], 10)
+
+
+def test_results_are_deterministic(cfg0):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = gpu_index_from_oracle(pkg, oidx)
+    qd = dev(q)
+    a = ix.ivfpq_search(qd, 16, 50)
+    b = ix.ivfpq_search(qd, 16, 50)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_latency_profile_and_stage_times(cfg0):
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = gpu_index_from_oracle(pkg, oidx)
+    qd = dev(q[:1])
+    p50, fit = ix.latency_profile(qd, [1, 2, 4, 8, 16, 32, 64], 10, reps=5)
+    assert np.all(p50 > 0) and fit[0] > 0              # positive intercept: the index scan (Section 3.1, O3)
+    ix.set_stage_timing(True)
+    ix.ivfpq_search(qd, 8, 10)
+    t = ix.stage_times()
+    assert t.shape == (pkg.NSTAGES,) and np.all(t >= 0) and t.sum() > 0
+    ix.set_stage_timing(False)
