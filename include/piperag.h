@@ -69,6 +69,18 @@ int piperag_ivf_load(const char *path, const piperag_params *limits, piperag_ind
 int piperag_ivf_create(const piperag_params *params, const float *centroids_host, const float *pq_codebook_host,
                        piperag_index **out);
 
+/* Index training.  The paper does not say how the lists and codebooks are trained (Section 3.2, S3 only
+ * states that the database is clustered into nlist lists); this is Lloyd's k-means with a fixed number of
+ * iterations: centre j starts as row init_rows_host[j] of x; each iteration assigns every row to its
+ * nearest centre (direct-form fp32 distance, lower index on equal values) and replaces each centre by the
+ * mean of its rows (coordinate sums are exact 2^-24 fixed-point integers, so the result does not depend on
+ * summation order; coordinates must stay below 2^15 in magnitude); a centre without rows keeps its value.
+ * x_dev f32: n rows of d coordinates, row stride ldx floats (a column slice of a wider matrix trains one
+ * sub-quantiser).  centroids_out_dev f32 [K*d].  inertia_out_host f64 [iters] or NULL: sum of
+ * row-to-centre distances seen by each iteration's assignment.  Allocates scratch; synchronises `stream`. */
+int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_t K, int32_t iters,
+                   const int64_t *init_rows_host, float *centroids_out_dev, double *inertia_out_host, void *stream);
+
 /* Database construction (Section 2; Appendix, Software: each vector becomes a list number and M code
  * bytes): encodes n vectors x_dev f32 [n*d] on the GPU and appends them.  list(x) = nearest centre,
  * code[m] = nearest of the 256 centres of sub-quantiser m to the m-th slice of x; on equal distances the

@@ -7,6 +7,7 @@ anywhere, but any call fails loudly if the shared library has not been built.
 """
 from .binding import (  # noqa: F401
     Index,
+    kmeans,
     PiperagError,
     lib_path,
     load_library,

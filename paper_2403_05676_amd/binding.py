@@ -43,6 +43,7 @@ def load_library() -> C.CDLL:
     sig = {
         "piperag_ivf_load": [C.c_char_p, C.POINTER(Params), C.POINTER(vp)],
         "piperag_ivf_create": [C.POINTER(Params), vp, vp, C.POINTER(vp)],
+        "piperag_kmeans": [vp, i64, i32, i64, i32, i32, vp, vp, vp, vp],
         "piperag_ivf_add": [vp, vp, i64, vp, vp],
         "piperag_ivf_add_encoded": [vp, vp, vp, vp, i64, vp],
         "piperag_ivf_finalize": [vp, vp],
@@ -86,6 +87,21 @@ def _dev(t: torch.Tensor, dtype: torch.dtype) -> int:
     if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
     return t.data_ptr()
+
+
+def kmeans(x: torch.Tensor, K: int, init_rows: np.ndarray, iters: int = 10, return_inertia: bool = False):
+    """piperag_kmeans on a 2-D float32 CUDA tensor (rows may be strided: a column slice of a wider matrix)."""
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1):
+        raise TypeError("expected a 2-D float32 CUDA tensor with unit column stride")
+    n, d = x.shape
+    rows = np.ascontiguousarray(init_rows, dtype=np.int64)
+    if rows.shape != (K,):
+        raise ValueError("init_rows must hold K row numbers")
+    out = torch.empty((K, d), dtype=torch.float32, device=x.device)
+    inertia = np.empty(iters, dtype=np.float64) if return_inertia else None
+    _check(load_library().piperag_kmeans(x.data_ptr(), n, d, x.stride(0), K, iters, rows.ctypes.data, out.data_ptr(),
+                                         inertia.ctypes.data if return_inertia else None, _stream()))
+    return (out, inertia) if return_inertia else out
 
 
 class Index:

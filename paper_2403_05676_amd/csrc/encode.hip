@@ -2,6 +2,8 @@
 // Setup", Software: every vector is assigned to one of nlist inverted lists and quantised into M code
 // bytes).  list(x) = argmin_j ||x - centre_j||^2, code[m] = argmin_j ||x_m - pq[m][j]||^2, both in the
 // direct (difference) form in fp32, lowest index on equal values.
+#include <stdlib.h>
+
 #include "common.h"
 
 using namespace piperag;
@@ -17,15 +19,15 @@ constexpr int TM = 64, TN = 64, TK = 16, LDT = 68;   // tile of rows x centres x
 
 // Nearest-centre assignment.  One workgroup = 64 rows of x against all centres, 64 at a time; each thread
 // accumulates a 4x4 patch of squared differences from coordinate-major LDS tiles.
-__global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x, int64_t n, int d,
+__global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
                                                      const float *__restrict__ cent, int nlist,
-                                                     int32_t *__restrict__ out_idx) {
+                                                     int32_t *__restrict__ out_idx, float *__restrict__ out_dist,
+                                                     int vec4) {
     __shared__ __align__(16) float xs[TK * LDT];
     __shared__ __align__(16) float cs[TK * LDT];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int64_t row0 = (int64_t)blockIdx.x * TM;
     const int lr = tid >> 2, lk = (tid & 3) * 4;          // this thread loads 4 coordinates of row lr of each tile
-    const bool vec4 = (d & 3) == 0;
 
     float best_d[4];
     int best_j[4];
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x
             const int kk = k0 + lk;
             if (vec4) {
                 if (xr < n && kk < d) {
-                    const float4 v = *reinterpret_cast<const float4 *>(x + xr * d + kk);
+                    const float4 v = *reinterpret_cast<const float4 *>(x + xr * ldx + kk);
                     xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w;
                 }
                 if (cr < nlist && kk < d) {
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if (xr < n && kk + i < d) xv[i] = x[xr * d + kk + i];
+                    if (xr < n && kk + i < d) xv[i] = x[xr * ldx + kk + i];
                     if (cr < nlist && kk + i < d) cv[i] = cent[(size_t)cr * d + kk + i];
                 }
             }
@@ -104,7 +106,10 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t r = row0 + ty * 4 + i;
-            if (r < n) out_idx[r] = best_j[i];
+            if (r < n) {
+                out_idx[r] = best_j[i];
+                if (out_dist) out_dist[r] = best_d[i];
+            }
         }
     }
 }
@@ -147,15 +152,58 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
     for (int i = tid; i < rows * M; i += 256) dst[i] = code_s[i];
 }
 
-int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
-    const piperag_params &p = ix->p;
-    PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
+// rows of x (stride ldx floats) against K centres; 16-byte loads only when every row start is 16-byte aligned
+void launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, int K, int32_t *out_idx, float *out_dist,
+                   hipStream_t st) {
+    const int vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(cent) % 16 == 0);
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
-        if (out_lists)
-            hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * p.d, cnt, p.d,
-                               ix->centroids, p.nlist, out_lists + a);
+        hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent, K,
+                           out_idx + a, out_dist ? out_dist + a : nullptr, vec4);
+    }
+}
+
+// ---- k-means training ------------------------------------------------------------------------
+constexpr float kFixScale = 16777216.f;             // 2^24: coordinate sums are kept in 40.24 fixed point
+
+__global__ void gather_rows_kernel(const float *__restrict__ x, int64_t ldx, int d, const int64_t *__restrict__ rows,
+                                   float *__restrict__ out) {
+    const int j = blockIdx.x;
+    for (int t = threadIdx.x; t < d; t += blockDim.x) out[(size_t)j * d + t] = x[rows[j] * ldx + t];
+}
+
+__global__ void kmeans_accum_kernel(const float *__restrict__ x, int64_t ldx, int d, const int32_t *__restrict__ assign,
+                                    long long *__restrict__ sum, int *__restrict__ count) {
+    const int64_t row = blockIdx.x;
+    const int a = assign[row];
+    for (int t = threadIdx.x; t < d; t += blockDim.x)
+        atomicAdd(reinterpret_cast<unsigned long long *>(&sum[(size_t)a * d + t]),
+                  (unsigned long long)__float2ll_rn(x[row * ldx + t] * kFixScale));
+    if (threadIdx.x == 0) atomicAdd(&count[a], 1);
+}
+
+__global__ void kmeans_update_kernel(const long long *__restrict__ sum, const int *__restrict__ count, int K, int d,
+                                     float *__restrict__ cent) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)K * d) return;
+    const int c = count[e / d];
+    if (c > 0) cent[e] = (float)((double)sum[e] * (1.0 / 16777216.0) / (double)c);
+}
+
+__global__ void zero_kernel(unsigned long long *__restrict__ p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
+int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
+    const piperag_params &p = ix->p;
+    PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
+    if (out_lists) launch_assign(x, n, p.d, p.d, ix->centroids, p.nlist, out_lists, nullptr, st);
+    constexpr int64_t kSlice = 1 << 22;              // rows per launch
+    for (int64_t a = 0; a < n; a += kSlice) {
+        const int64_t cnt = n - a < kSlice ? n - a : kSlice;
         if (out_codes) {
             const size_t lds = sizeof(float) * 2 * kKsub * ix->dsub + (size_t)256 * p.M;
             static size_t configured = 0;
@@ -184,6 +232,60 @@ int piperag_ivf_encode(const piperag_index *index, const float *x_dev, int64_t n
     PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
     PR_CHECK_HIP(hipSetDevice(index->device));
     return encode_impl(index, x_dev, n, out_lists_dev, out_codes_dev, (hipStream_t)stream);
+}
+
+int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_t K, int32_t iters,
+                   const int64_t *init_rows_host, float *centroids_out_dev, double *inertia_out_host, void *stream) {
+    PR_REQUIRE(x_dev && init_rows_host && centroids_out_dev, PIPERAG_ERR_ARG, "NULL argument");
+    PR_REQUIRE(n >= 1 && n <= (1ll << 31) - 1 && d >= 1 && d <= 8192 && ldx >= d, PIPERAG_ERR_ARG, "n / d / ldx out of range");
+    PR_REQUIRE(K >= 1 && K <= n && K <= (1 << 20) && iters >= 0, PIPERAG_ERR_ARG, "K = %d / iters = %d out of range", K, iters);
+    for (int j = 0; j < K; ++j)
+        PR_REQUIRE(init_rows_host[j] >= 0 && init_rows_host[j] < n, PIPERAG_ERR_ARG, "init row %d out of range", j);
+    hipStream_t st = (hipStream_t)stream;
+    int64_t *rows = nullptr;
+    int32_t *assign = nullptr;
+    float *adist = nullptr;
+    long long *sum = nullptr;
+    int *count = nullptr;
+    float *hdist = inertia_out_host ? (float *)malloc(sizeof(float) * (size_t)n) : nullptr;
+    auto done = [&](int code) {
+        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count);
+        free(hdist);
+        return code;
+    };
+    if (inertia_out_host && !hdist) { set_error("host allocation failed"); return done(PIPERAG_ERR_OOM); }
+    if (hipMalloc((void **)&rows, sizeof(int64_t) * K) != hipSuccess || hipMalloc((void **)&assign, sizeof(int32_t) * n) != hipSuccess ||
+        hipMalloc((void **)&adist, sizeof(float) * n) != hipSuccess ||
+        hipMalloc((void **)&sum, sizeof(long long) * (size_t)K * d) != hipSuccess ||
+        hipMalloc((void **)&count, sizeof(int) * (K + 1)) != hipSuccess) {
+        set_error("out of device memory in piperag_kmeans");
+        return done(PIPERAG_ERR_OOM);
+    }
+    hipError_t e = hipMemcpyAsync(rows, init_rows_host, sizeof(int64_t) * K, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { set_error("upload failed: %s", hipGetErrorString(e)); return done(PIPERAG_ERR_HIP); }
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(K), dim3(256), 0, st, x_dev, ldx, d, rows, centroids_out_dev);
+    const int64_t nsum = (int64_t)K * d;
+    for (int it = 0; it < iters; ++it) {
+        launch_assign(x_dev, n, d, ldx, centroids_out_dev, K, assign, adist, st);
+        hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, (unsigned long long *)sum, nsum);
+        hipLaunchKernelGGL(zero_kernel, dim3((K / 2 + 256) / 256), dim3(256), 0, st, (unsigned long long *)count, (int64_t)(K + 1) / 2);
+        hipLaunchKernelGGL(kmeans_accum_kernel, dim3((unsigned)n), dim3(d >= 256 ? 256 : 64), 0, st, x_dev, ldx, d, assign, sum, count);
+        hipLaunchKernelGGL(kmeans_update_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, sum, count, K, d,
+                           centroids_out_dev);
+        if (inertia_out_host) {
+            e = hipMemcpyAsync(hdist, adist, sizeof(float) * n, hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipStreamSynchronize(st);
+            if (e != hipSuccess) { set_error("read-back failed: %s", hipGetErrorString(e)); return done(PIPERAG_ERR_HIP); }
+            double tot = 0.0;
+            for (int64_t i = 0; i < n; ++i) tot += (double)hdist[i];
+            inertia_out_host[it] = tot;
+        }
+    }
+    e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) { set_error("k-means failed: %s", hipGetErrorString(e)); return done(PIPERAG_ERR_HIP); }
+    return done(PIPERAG_OK);
 }
 
 int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream) {

@@ -303,3 +303,41 @@ def test_latency_profile_and_stage_times(cfg0):
     t = ix.stage_times()
     assert t.shape == (pkg.NSTAGES,) and np.all(t >= 0) and t.sum() > 0
     ix.set_stage_timing(False)
+
+
+# ------------------------------------------------------------------------------------------------
+def test_device_generator_is_bit_identical_to_numpy():
+    from workload import gen_gpu
+    for name, count in [("cfg0", 700), ("cfg1", 300)]:
+        cfg = gen.CONFIGS[name]
+        g = gen_gpu.DeviceGenerator(cfg)
+        for row0 in (0, 12345, gen.QUERY_ROW0 + 3):
+            a = g.rows(row0, count)
+            torch.cuda.synchronize()
+            assert np.array_equal(a.cpu().numpy(), gen.rows(cfg, row0, count))
+
+
+def test_gpu_kmeans_follows_the_oracle():
+    pkg = P()
+    cfg = gen.CONFIGS["cfg0"].scaled(N=20000)
+    x = gen.database(cfg)
+    xd = dev(x)
+    K = 40
+    rows = gen.draw_distinct_rows(cfg.N, K, 77)
+    # one iteration: same assignments (up to ties), means equal to fp32 rounding
+    c1 = pkg.kmeans(xd, K, rows, 1).cpu().numpy()
+    o1 = oracle.kmeans(x, K, rows, 1)
+    np.testing.assert_allclose(c1, o1, rtol=2e-6, atol=2e-6)
+    # zero iterations: the initial rows
+    np.testing.assert_array_equal(pkg.kmeans(xd, K, rows, 0).cpu().numpy(), x[rows])
+    # ten iterations: same trajectory of the objective
+    c10, inert = pkg.kmeans(xd, K, rows, 10, return_inertia=True)
+    o10, oin = oracle.kmeans(x, K, rows, 10, return_inertia=True)
+    np.testing.assert_allclose(inert, oin, rtol=1e-3)
+    assert np.all(np.diff(inert) <= 1e-6 * inert[0])
+    # a column slice (one sub-quantiser's coordinates) with 256 centres
+    rows2 = gen.draw_distinct_rows(cfg.N, 256, 78)
+    s1 = pkg.kmeans(xd[:, 8:16], 256, rows2, 1).cpu().numpy()
+    np.testing.assert_allclose(s1, oracle.kmeans(x[:, 8:16], 256, rows2, 1), rtol=2e-6, atol=2e-6)
+    # deterministic
+    assert torch.equal(pkg.kmeans(xd, K, rows, 3), pkg.kmeans(xd, K, rows, 3))

@@ -1,0 +1,72 @@
+// On-device version of the seeded workload generator (see workload/gen.py for the recipe).  Integer hashing
+// plus three correctly rounded fp32 operations per coordinate, so the output is bit-identical to the numpy
+// implementation.  Draws inputs only: none of the retrieval method's arithmetic lives here.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+constexpr int kIhMean = 262140;
+constexpr float kInvStd = 1.8688123650118534e-05f;
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ inline uint64_t stream_key(uint64_t seed, uint64_t stream) { return mix64(seed * kGolden + stream); }
+__device__ inline uint64_t hash_ctr(uint64_t key, uint64_t ctr) { return mix64(key + ctr * kGolden); }
+__device__ inline int fields16(uint64_t h) {
+    return (int)(h & 0xFFFF) + (int)((h >> 16) & 0xFFFF) + (int)((h >> 32) & 0xFFFF) + (int)(h >> 48);
+}
+__device__ inline float variate(uint64_t key, uint64_t ctr) {
+    const int s = fields16(hash_ctr(key, 2 * ctr)) + fields16(hash_ctr(key, 2 * ctr + 1));
+    return __fmul_rn((float)(s - kIhMean), kInvStd);
+}
+
+// One workgroup per row: thread 0 picks the mixture component, all threads fill the coordinates.
+__global__ __launch_bounds__(256) void rows_kernel(uint64_t key_comp, uint64_t key_noise, uint64_t row0, int d, float sigma,
+                                                   const float *__restrict__ centres, const uint64_t *__restrict__ cum,
+                                                   int ncomp, float *__restrict__ out) {
+    __shared__ int s_comp;
+    const uint64_t row = row0 + blockIdx.x;
+    if (threadIdx.x == 0) {
+        const uint64_t u = hash_ctr(key_comp, row) >> 32;
+        int lo = 0, hi = ncomp;                  // number of entries with cum[j] <= u
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cum[mid] <= u) lo = mid + 1; else hi = mid;
+        }
+        s_comp = lo < ncomp ? lo : ncomp - 1;
+    }
+    __syncthreads();
+    const float *c = centres + (size_t)s_comp * d;
+    float *o = out + (size_t)blockIdx.x * d;
+    for (int t = threadIdx.x; t < d; t += blockDim.x) {
+        const float z = variate(key_noise, row * (uint64_t)d + (uint64_t)t);
+        o[t] = __fadd_rn(c[t], __fmul_rn(sigma, z));
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// Rows row0 .. row0+count-1 of the row space of `seed` into out_dev (f32 [count*d]).  centres_dev: f32
+// [ncomp*d]; cum_dev: u64 [ncomp] cumulative weights scaled to 2^32.  Enqueues on `stream`; returns 0 or a
+// hipError_t value.
+int workload_gen_rows(uint64_t seed, uint64_t row0, int64_t count, int32_t d, float sigma, const float *centres_dev,
+                      const uint64_t *cum_dev, int32_t ncomp, float *out_dev, void *stream) {
+    if (count <= 0) return 0;
+    const uint64_t kc = stream_key(seed, 2), kn = stream_key(seed, 3);
+    constexpr int64_t kSlice = 1 << 30;
+    for (int64_t a = 0; a < count; a += kSlice) {
+        const int64_t n = count - a < kSlice ? count - a : kSlice;
+        hipLaunchKernelGGL(rows_kernel, dim3((unsigned)n), dim3(256), 0, (hipStream_t)stream, kc, kn, row0 + (uint64_t)a, d, sigma,
+                           centres_dev, cum_dev, ncomp, out_dev + (size_t)a * d);
+    }
+    return (int)hipGetLastError();
+}
+
+}  // extern "C"
