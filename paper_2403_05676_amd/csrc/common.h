@@ -18,9 +18,9 @@ constexpr int kMaxK = 1024;
 constexpr int kMaxNprobe = 1024;
 constexpr int kScanThreads = 256;  // 4 waves per scan workgroup
 constexpr int kScanWaves = kScanThreads / kWave;
-constexpr int kQueueCap = 128;     // per-wave candidate queue (flushed when more than 64 are pending)
-constexpr int kTargetScanWGs = 2048;
+constexpr int kTargetScanWGs = 1024;   // scan workgroups per search call (segments per query = this / nq)
 constexpr int kMaxSegments = 1024;
+constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
@@ -78,8 +78,9 @@ struct piperag_index {
     float *ws_probe_d;    // [max_nq*max_nprobe]
     int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
     int64_t *ws_scanned;  // [max_nq]
+    uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
-    uint64_t *ws_part;    // [(kTargetScanWGs+max_nq)*max_k] per-workgroup partial results
+    uint64_t *ws_part;    // [(2*kTargetScanWGs+2*max_nq)*max_k] per-workgroup partial results
     float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
     int64_t *ws_out_i;    // [max_nq*max_k]
     int *flag;            // [1] device flag for argument checks

@@ -212,9 +212,9 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_probe, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_probe_d, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_pfx, (size_t)p.max_nq * (p.max_nprobe + 1))) ||
-        (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) ||
+        (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) || (rc = dev_alloc(&ix->ws_thr, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
-        (rc = dev_alloc(&ix->ws_part, ((size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * p.max_k)) ||
+        (rc = dev_alloc(&ix->ws_part, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
         return fail(rc);
@@ -268,7 +268,7 @@ void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
     void *ptrs[] = {ix->centroids, ix->pq, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
-                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_lut, ix->ws_part, ix->ws_out_d, ix->ws_out_i, ix->flag};
+                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_lut, ix->ws_part, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);

@@ -5,6 +5,8 @@
 // the product-quantised vectors inside them are compared with the query; Section 2 - the k closest are
 // returned.  The retrieval latency model of S3 splits the time into an index-scan term (stages 0-1 here)
 // and a vector-scan term proportional to nprobe (stages 2-4).
+#include <stdlib.h>
+
 #include <algorithm>
 #include <vector>
 
@@ -17,12 +19,6 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 // small device helpers
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void wave_sync() {
-    // Orders LDS traffic between the lanes of one wavefront (no s_barrier needed: a wave runs in lock-step).
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -30,12 +26,15 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// k-th smallest (1-based `kth`) of n 64-bit keys, by most-significant-digit radix selection with the whole
-// workgroup.  key_at(i) may be evaluated several times.  Requires 1 <= kth <= n.
+// Largest key of the kth (1-based) smallest among n distinct 64-bit keys - i.e. a threshold T such that exactly
+// kth keys are <= T - by most-significant-digit radix selection with the whole workgroup (blockDim >= 256,
+// a multiple of 64).  key_at(i) may be evaluated several times.  Requires 1 <= kth <= n.  Stops as soon as
+// the digits fixed so far isolate exactly the keys that are needed, which for float-derived keys is
+// usually after the 32 distance bits.
 template <class KeyFn>
 __device__ uint64_t block_radix_select(KeyFn key_at, int n, int kth, unsigned *s_hist /*[256]*/,
-                                       unsigned long long *s_state /*[2]*/) {
-    const int tid = threadIdx.x, nt = blockDim.x;
+                                       unsigned long long *s_state /*[4]*/) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     uint64_t prefix = 0;
     for (int shift = 56; shift >= 0; shift -= 8) {
         for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
@@ -46,21 +45,34 @@ __device__ uint64_t block_radix_select(KeyFn key_at, int n, int kth, unsigned *s
             if (in) atomicAdd(&s_hist[(unsigned)(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) {
-            unsigned cum = 0;
-            int dgt = 0;
-            for (; dgt < 255; ++dgt) {
-                const unsigned c = s_hist[dgt];
-                if (cum + c >= (unsigned)kth) break;
-                cum += c;
+        // inclusive prefix sum of the 256 digit counts: within each of the first 4 waves, then across them
+        unsigned h = 0, incl = 0;
+        if (tid < 256) {
+            h = s_hist[tid];
+            incl = h;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned o = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += o;
             }
-            s_state[0] = prefix | ((uint64_t)dgt << shift);
-            s_state[1] = (unsigned long long)(kth - (int)cum);
+            if (lane == 63) s_state[wave] = incl;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            for (int w = 0; w < wave; ++w) incl += (unsigned)s_state[w];
+        }
+        __syncthreads();
+        if (tid < 256 && incl - h < (unsigned)kth && (unsigned)kth <= incl) {   // exactly one digit qualifies
+            s_state[0] = prefix | ((uint64_t)tid << shift);
+            s_state[1] = (unsigned long long)((unsigned)kth - (incl - h));
+            s_state[2] = h;
         }
         __syncthreads();
         prefix = s_state[0];
         kth = (int)s_state[1];
+        const bool whole_bucket = (unsigned long long)kth == s_state[2];
         __syncthreads();
+        if (whole_bucket) return prefix | (shift > 0 ? ((1ull << shift) - 1ull) : 0ull);
     }
     return prefix;
 }
@@ -142,7 +154,7 @@ __global__ __launch_bounds__(256) void select_probes_kernel(const float *__restr
                                                             int32_t *__restrict__ probe, float *__restrict__ probe_d,
                                                             int probe_stride) {
     __shared__ unsigned s_hist[256];
-    __shared__ unsigned long long s_state[2];
+    __shared__ unsigned long long s_state[4];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count;
     const int qi = blockIdx.x;
@@ -184,12 +196,13 @@ __global__ void copy_probes_kernel(const int32_t *__restrict__ src, int nprobe, 
 }
 
 // Stage 1b: scan plan.  pfx[q][i] = number of 64-vector blocks in the first i probed lists of query q;
-// scanned[q] = number of vectors in its probed lists.
+// scanned[q] = number of vectors in its probed lists; thr[q] = "no bound yet" for the scan's shared threshold.
 __global__ void plan_kernel(const int32_t *__restrict__ probe, int probe_stride, int nprobe,
                             const int32_t *__restrict__ list_blk, const int32_t *__restrict__ list_len,
-                            int32_t *__restrict__ pfx, int64_t *__restrict__ scanned) {
+                            int32_t *__restrict__ pfx, int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
     const int qi = blockIdx.x;
     if (threadIdx.x != 0) return;
+    thr[qi] = 0xFFFFFFFFu;
     int32_t blocks = 0;
     int64_t vecs = 0;
     int32_t *out = pfx + (size_t)qi * (probe_stride + 1);
@@ -234,12 +247,18 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ q, c
 // grid = (S segments, nq).  The probed lists of a query, concatenated in probe order, form a sequence of
 // 64-vector blocks; segment s takes an equal share of it, and the 4 waves of the workgroup take its blocks
 // round-robin.  A lane owns one vector of the block: it reads its Mp code bytes with Mp/16 16-byte loads
-// and adds Mp table entries from LDS.  Because of the rotated code layout (see common.h), at step t lane l
-// looks up sub-quantiser (l + t) mod Mp, so with the table stored [j][Mp] the lanes of a half-wave hit
-// different LDS banks when Mp is 32 or 64.
-// k-selection: each wave keeps its k best (distance bits << 32 | slot) sorted in LDS, filters candidates
-// against the current k-th best, queues the survivors and merges the queue when it fills up.  At the end
-// the 4 wave lists are merged and written to the partial-result buffer.
+// (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.  Because of the rotated
+// code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp, so with the table
+// stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
+// For Mp = 64 the LDS byte address of a lookup is (code byte << 8) | (((l + t) mod 64) << 2): one byte
+// permute of the code word with a per-step lane constant held in a register.
+// k-selection: candidates (distance bits << 32 | slot) that pass a bound on the final k-th best distance
+// are appended to one candidate buffer per workgroup.  Once per round of NSETS blocks per wave the
+// workgroup meets at a barrier; when the buffer is nearly full it keeps only its k smallest keys (radix
+// selection in LDS, no sorting) and tightens the bound.  The bound is the smallest k-th best any workgroup
+// of the query has reached so far (thr[q] in global memory, polled with every block load); a candidate
+// above it cannot be in the result.  At the end the workgroup's (at most k) keys go to the
+// partial-result buffer, unsorted.
 // ------------------------------------------------------------------------------------------------
 struct ScanArgs {
     const uint8_t *codes;
@@ -249,63 +268,114 @@ struct ScanArgs {
     const int32_t *list_blk;
     const int32_t *list_len;
     uint64_t *part;
+    uint32_t *thr;
     int nprobe, probe_stride, k, KP;
+#ifdef PIPERAG_TRACE
+    unsigned long long *trace;   // [workgroups][8] timestamps
+#endif
 };
 
-// Number of keys in sorted[0..n) that are smaller than key.
-__device__ __forceinline__ int lower_bound_u64(const uint64_t *sorted, int n, uint64_t key) {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (sorted[mid] < key) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
+typedef const __attribute__((address_space(3))) float *lds_cfptr;
 
-// Merges the wave's pending queue into its sorted best list (double-buffered: cur -> alt, then swapped).
-__device__ void wave_flush(uint64_t *&cur, uint64_t *&alt, const uint64_t *queue, int qn, int k, int KP, int lane) {
-    wave_sync();
-    for (int i = lane; i < KP; i += kWave) alt[i] = kSentinel;
-    wave_sync();
-    for (int i = lane; i < qn; i += kWave) {
-        const uint64_t key = queue[i];
-        int r = lower_bound_u64(cur, KP, key);
-        for (int j = 0; j < qn; ++j) r += (queue[j] < key) ? 1 : 0;
-        if (r < k) alt[r] = key;
-    }
-    for (int i = lane; i < KP; i += kWave) {
-        const uint64_t key = cur[i];
-        if (key != kSentinel) {
-            int r = i;
-            for (int j = 0; j < qn; ++j) r += (queue[j] < key) ? 1 : 0;
-            if (r < k) alt[r] = key;
+constexpr int kCandRoom = 1536;                       // candidate slots beyond KP
+constexpr int kCandPerThread = (kMaxK + kCandRoom) / kScanThreads;
+
+// Distance of this lane's vector of one block, any Mp: table index = byte * Mp + (lane + t) mod Mp.
+template <int C>
+__device__ __forceinline__ float block_dist_generic(const uint4 (&w)[C], const float *s_lut, int lane_m) {
+    constexpr int MP = 16 * C;
+    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const uint32_t ww[4] = {w[c].x, w[c].y, w[c].z, w[c].w};
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            int m = lane_m + c * 16 + u;
+            if (m >= MP) m -= MP;
+            const uint32_t byte = (ww[u >> 2] >> (8 * (u & 3))) & 0xFFu;
+            const float v = s_lut[byte * MP + m];
+            if ((u & 3) == 0) acc0 += v; else if ((u & 3) == 1) acc1 += v; else if ((u & 3) == 2) acc2 += v; else acc3 += v;
         }
     }
-    wave_sync();
-    uint64_t *t = cur; cur = alt; alt = t;
+    return (acc0 + acc1) + (acc2 + acc3);
 }
 
-template <int C>
-__global__ __launch_bounds__(kScanThreads) void adc_scan_kernel(ScanArgs a) {
+// Mp = 64 with the table at LDS address 0.  The LDS byte address of lookup t is (code byte << 8) | off(t) with
+// off(t) = ((lane + t) mod 64) * 4 < 256, so four consecutive off values fit one register (off4[t / 4], byte
+// t % 4) and a single byte permute assembles the address from the code word and that register.
+__device__ __forceinline__ float block_dist_m64(const uint4 (&w)[4], const uint32_t (&off4)[16]) {
+    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t ww[4] = {w[c].x, w[c].y, w[c].z, w[c].w};
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            // result bytes: [0] = byte (u & 3) of off4, [1] = byte (u & 3) of the code word, [2] = [3] = 0
+            const uint32_t n = (uint32_t)(u & 3);
+            const uint32_t addr = __builtin_amdgcn_perm(ww[u >> 2], off4[c * 4 + (u >> 2)], 0x0c0c0400u + (n << 8) + n);
+            const float v = *reinterpret_cast<lds_cfptr>(static_cast<uintptr_t>(addr));
+            if (n == 0) acc0 += v; else if (n == 1) acc1 += v; else if (n == 2) acc2 += v; else acc3 += v;
+        }
+    }
+    return (acc0 + acc1) + (acc2 + acc3);
+}
+
+// Keeps the k smallest of the n (> k, distinct) keys in s_cand[0..n) at the front (any order) and returns
+// the largest key kept.  Whole workgroup, called at a barrier-synchronised point; *s_count becomes k.
+__device__ uint64_t wg_keep_k_smallest(uint64_t *s_cand, int n, int k, unsigned *s_hist, unsigned long long *s_state,
+                                       unsigned *s_count) {
+    const int tid = threadIdx.x;
+    auto key_at = [&](int i) { return s_cand[i]; };
+    const uint64_t T = block_radix_select(key_at, n, k, s_hist, s_state);
+    uint64_t mine[kCandPerThread];
+#pragma unroll
+    for (int e = 0; e < kCandPerThread; ++e) {
+        const int i = tid + e * kScanThreads;
+        mine[e] = i < n ? s_cand[i] : kSentinel;
+    }
+    if (tid == 0) *s_count = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kCandPerThread; ++e)
+        if (mine[e] <= T && mine[e] != kSentinel) s_cand[atomicAdd(s_count, 1u)] = mine[e];
+    __syncthreads();
+    return T;
+}
+
+template <int C, int NSETS>
+__global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     constexpr int MP = 16 * C;
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
+    const int k = a.k, KP = a.KP;
+    const int cap = KP + kCandRoom;
     float *s_lut = reinterpret_cast<float *>(smem);                                  // [256*MP]
-    uint64_t *s_best = reinterpret_cast<uint64_t *>(smem + (size_t)1024 * MP);       // [4 waves][2][KP]
-    uint64_t *s_queue = s_best + kScanWaves * 2 * a.KP;                              // [4][kQueueCap]
-    uint64_t *s_wg = s_queue + kScanWaves * kQueueCap;                               // [KP]
-    int32_t *s_pfx = reinterpret_cast<int32_t *>(s_wg + a.KP);                       // [nprobe+1]
+    uint64_t *s_cand = reinterpret_cast<uint64_t *>(smem + (size_t)1024 * MP);       // [cap]
+    unsigned long long *s_state = reinterpret_cast<unsigned long long *>(s_cand + cap);   // [4]
+    unsigned *s_hist = reinterpret_cast<unsigned *>(s_state + 4);                    // [256]
+    unsigned *s_count = s_hist + 256;                                                // [1] (+1 pad)
+    int32_t *s_pfx = reinterpret_cast<int32_t *>(s_count + 2);                       // [nprobe+1]
     int32_t *s_blk = s_pfx + (a.nprobe + 1);                                         // [nprobe]
     int32_t *s_len = s_blk + a.nprobe;                                               // [nprobe]
-    __shared__ int s_sel[kScanWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = blockIdx.y, seg = blockIdx.x, S = gridDim.x;
-    const int k = a.k, KP = a.KP;
+    const bool lut_at_zero =
+        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
 
+#ifdef PIPERAG_TRACE
+    unsigned long long *tr = a.trace + ((size_t)qi * S + seg) * 8;
+    unsigned nflush = 0;
+    if (tid == 0) tr[0] = wall_clock64();
+#endif
     {   // stage the query's table and probe tables
         const float4 *src = reinterpret_cast<const float4 *>(a.lut + (size_t)qi * kKsub * MP);
         float4 *dst = reinterpret_cast<float4 *>(s_lut);
-        for (int i = tid; i < kKsub * MP / 4; i += kScanThreads) dst[i] = src[i];
+        constexpr int kPer = kKsub * MP / 4 / kScanThreads;     // 16-byte pieces per thread (4*C)
+        float4 tmp[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) tmp[i] = src[tid + i * kScanThreads];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) dst[tid + i * kScanThreads] = tmp[i];
         const int32_t *pf = a.pfx + (size_t)qi * (a.probe_stride + 1);
         for (int i = tid; i <= a.nprobe; i += kScanThreads) s_pfx[i] = pf[i];
         for (int i = tid; i < a.nprobe; i += kScanThreads) {
@@ -313,113 +383,175 @@ __global__ __launch_bounds__(kScanThreads) void adc_scan_kernel(ScanArgs a) {
             s_blk[i] = l >= 0 ? a.list_blk[l] : 0;
             s_len[i] = l >= 0 ? a.list_len[l] : 0;
         }
-        for (int i = tid; i < kScanWaves * 2 * KP; i += kScanThreads) s_best[i] = kSentinel;
+        if (tid == 0) *s_count = 0;
     }
     __syncthreads();
 
-    uint64_t *cur = s_best + (size_t)wave * 2 * KP, *alt = cur + KP;
-    uint64_t *queue = s_queue + (size_t)wave * kQueueCap;
-    int qn = 0;
-    uint32_t thr = 0xFFFFFFFFu;     // distance bits of the wave's current k-th best
-
+#ifdef PIPERAG_TRACE
+    if (tid == 0) tr[1] = wall_clock64();
+#endif
+    uint32_t thr = 0xFFFFFFFFu;     // best known bound on the k-th best distance (bits)
     const int TB = s_pfx[a.nprobe];
     const int b_begin = (int)((int64_t)TB * seg / S), b_end = (int)((int64_t)TB * (seg + 1) / S);
+    const int rounds = (b_end - b_begin + kScanWaves * NSETS - 1) / (kScanWaves * NSETS);   // same for all waves
+    const int trigger = cap - kScanThreads * NSETS;      // a round appends at most 256*NSETS keys; trigger >= KP >= k
     const int lane_m = lane % MP;
-    int pi = 0;
+    uint32_t off4[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        off4[i] = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) off4[i] |= ((uint32_t)((lane + 4 * i + j) & 63) << 2) << (8 * j);
+    }
 
-    for (int b = b_begin + wave; b < b_end; b += kScanWaves) {
-        while (b >= s_pfx[pi + 1]) ++pi;                     // b < TB = s_pfx[nprobe], so pi stays < nprobe
-        const int bl = b - s_pfx[pi];
-        const uint32_t gblock = (uint32_t)(s_blk[pi] + bl);
-        const int nvalid = s_len[pi] - bl * kBlockVecs;      // >= 1; lanes >= nvalid hold padding
-        const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock * kBlockVecs * MP);
-        uint4 w[C];
+    int b_next = b_begin + wave;    // next block this wave will request
+    int pi = 0;                     // probe whose list holds b_next (advanced monotonically)
+
+    struct Meta { uint32_t gblock; int nvalid; uint32_t tg; bool valid; };
+    auto issue = [&](uint4 (&w)[C], Meta &m) {
+        m.valid = b_next < b_end;
+        if (!m.valid) return;
+        while (b_next >= s_pfx[pi + 1]) ++pi;                 // b_next < TB = s_pfx[nprobe], so pi stays < nprobe
+        const int bl = b_next - s_pfx[pi];
+        m.gblock = (uint32_t)(s_blk[pi] + bl);
+        m.nvalid = s_len[pi] - bl * kBlockVecs;               // >= 1; lanes >= nvalid hold padding
+        const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP);
 #pragma unroll
         for (int c = 0; c < C; ++c) w[c] = blk[c * kWave + lane];
-
-        float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const uint32_t ww[4] = {w[c].x, w[c].y, w[c].z, w[c].w};
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int t = c * 16 + u;
-                int m = lane_m + t;
-                if (m >= MP) m -= MP;
-                const uint32_t byte = (ww[u >> 2] >> (8 * (u & 3))) & 0xFFu;
-                const float v = s_lut[byte * MP + m];
-                if ((u & 3) == 0) acc0 += v; else if ((u & 3) == 1) acc1 += v; else if ((u & 3) == 2) acc2 += v; else acc3 += v;
-            }
-        }
-        const float dist = (acc0 + acc1) + (acc2 + acc3);
+        m.tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        b_next += kScanWaves;
+    };
+    auto process = [&](const uint4 (&w)[C], const Meta &m) {
+        float dist;
+        if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
+        else dist = block_dist_generic<C>(w, s_lut, lane_m);
         const uint32_t dbits = __float_as_uint(dist);
-        const bool pass = (lane < nvalid) && (dbits <= thr);
+        thr = min(thr, m.tg);
+        const bool pass = (lane < m.nvalid) && (dbits <= thr);
         const uint64_t mask = __ballot(pass);
         if (mask != 0) {
+            unsigned base = 0;
+            if (lane == 0) base = atomicAdd(s_count, (unsigned)__popcll(mask));
+            base = __builtin_amdgcn_readfirstlane(base);
             if (pass) {
-                const int off = __popcll(mask & ((1ull << lane) - 1ull));
-                queue[qn + off] = ((uint64_t)dbits << 32) | (uint64_t)(gblock * kBlockVecs + lane);
-            }
-            qn += __popcll(mask);
-            if (qn > kQueueCap - kWave) {
-                wave_flush(cur, alt, queue, qn, k, KP, lane);
-                qn = 0;
-                thr = (uint32_t)(cur[k - 1] >> 32);
+                const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+                if (slot < (unsigned)cap)     // always true (see trigger); keeps a logic error from writing out of bounds
+                    s_cand[slot] = ((uint64_t)dbits << 32) | (uint64_t)(m.gblock * kBlockVecs + lane);
             }
         }
-    }
-    if (qn > 0) wave_flush(cur, alt, queue, qn, k, KP, lane);
-    if (lane == 0) s_sel[wave] = (cur == s_best + (size_t)wave * 2 * KP) ? 0 : 1;
-    for (int i = tid; i < KP; i += kScanThreads) s_wg[i] = kSentinel;
-    __syncthreads();
+    };
 
-    // merge the four sorted wave lists: rank of a key = its index + number of smaller keys in the other lists
-    for (int e = tid; e < kScanWaves * KP; e += kScanThreads) {
-        const int w = e / KP, i = e - w * KP;
-        const uint64_t *mine = s_best + ((size_t)w * 2 + s_sel[w]) * KP;
-        const uint64_t key = mine[i];
-        if (key == kSentinel) continue;
-        int r = i;
-        for (int o = 0; o < kScanWaves; ++o) {
-            if (o == w) continue;
-            r += lower_bound_u64(s_best + ((size_t)o * 2 + s_sel[o]) * KP, KP, key);
+    uint4 w[NSETS][C];
+    Meta meta[NSETS];
+#pragma unroll
+    for (int s = 0; s < NSETS; ++s) issue(w[s], meta[s]);
+    for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+        for (int s = 0; s < NSETS; ++s) {
+            if (meta[s].valid) process(w[s], meta[s]);
+            issue(w[s], meta[s]);
         }
-        if (r < k) s_wg[r] = key;
+        __syncthreads();
+        const int n = (int)*reinterpret_cast<volatile unsigned *>(s_count);
+        if (n > trigger) {          // uniform: every thread reads the same value after the barrier
+            const uint64_t T = wg_keep_k_smallest(s_cand, min(n, cap), k, s_hist, s_state, s_count);
+            const uint32_t kth = (uint32_t)(T >> 32);
+            thr = min(thr, kth);
+            if (tid == 0) atomicMin(&a.thr[qi], kth);
+#ifdef PIPERAG_TRACE
+            ++nflush;
+#endif
+        }
     }
+#ifdef PIPERAG_TRACE
+    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)(b_end - b_begin); }
+#endif
     __syncthreads();
+    int n = min((int)*reinterpret_cast<volatile unsigned *>(s_count), cap);
+    if (n > k) {
+        const uint64_t T = wg_keep_k_smallest(s_cand, n, k, s_hist, s_state, s_count);
+        if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
+        n = k;
+    }
+#ifdef PIPERAG_TRACE
+    if (tid == 0) tr[3] = wall_clock64();
+#endif
     uint64_t *out = a.part + ((size_t)qi * S + seg) * k;
-    for (int i = tid; i < k; i += kScanThreads) out[i] = s_wg[i];
+    for (int i = tid; i < k; i += kScanThreads) out[i] = i < n ? s_cand[i] : kSentinel;
+#ifdef PIPERAG_TRACE
+    if (tid == 0) tr[4] = wall_clock64();
+#endif
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage 4: merge of the partial results of one query + id gather.  One workgroup per query: radix
-// selection of the k-th smallest key over the S*k partial keys, compaction, id lookup, bitonic sort by
-// (distance, id), padded output.
+// Stage 4: merge of the partial results of one query + id gather.  One workgroup of 1024 threads per
+// query.  Only keys within the query's final bound thr[q] can be among the k best; they are compacted into
+// LDS, the k smallest are selected there by radix selection.  If more than kMergeCap keys survive the
+// bound (e.g. no workgroup ever collected k candidates, so there is no bound), the selection runs over the
+// partial keys in global memory instead.  Then ids are looked up and the k results are sorted by
+// (distance, id).
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void merge_kernel(const uint64_t *__restrict__ part, int S, int k,
-                                                    const int64_t *__restrict__ ids, float *__restrict__ out_d,
-                                                    int64_t *__restrict__ out_i) {
+constexpr int kMergeThreads = 1024;
+
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__restrict__ part, int S, int k,
+                                                              const int64_t *__restrict__ ids,
+                                                              const uint32_t *__restrict__ thr, float *__restrict__ out_d,
+                                                              int64_t *__restrict__ out_i) {
+    __shared__ uint64_t s_keys[kMergeCap];
     __shared__ unsigned s_hist[256];
-    __shared__ unsigned long long s_state[2];
+    __shared__ unsigned long long s_state[4];
     __shared__ uint32_t s_d[kMaxK];
     __shared__ int64_t s_id[kMaxK];
     __shared__ unsigned s_count;
     const int qi = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
     const int n = S * k;
     const uint64_t *keys = part + (size_t)qi * n;
-    auto key_at = [&](int i) { return keys[i]; };
-    const uint64_t T = block_radix_select(key_at, n, k, s_hist, s_state);
+    const uint32_t bound = thr[qi];
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
     for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
     if (tid == 0) s_count = 0;
     __syncthreads();
     for (int i = tid; i < n; i += nt) {
         const uint64_t key = keys[i];
-        if (key <= T && key != kSentinel) {
-            const unsigned slot = atomicAdd(&s_count, 1u);   // exactly k keys are <= T (keys are distinct)
-            if (slot < (unsigned)k) {
-                s_d[slot] = (uint32_t)(key >> 32);
-                s_id[slot] = ids[(uint32_t)key];
+        if (key != kSentinel && (uint32_t)(key >> 32) <= bound) {
+            const unsigned slot = atomicAdd(&s_count, 1u);
+            if (slot < (unsigned)kMergeCap) s_keys[slot] = key;
+        }
+    }
+    __syncthreads();
+    const int found = (int)s_count;
+    __syncthreads();
+    if (found <= kMergeCap) {
+        uint64_t T = kSentinel - 1;                              // fewer than k candidates: keep them all
+        if (found > k) {
+            auto key_at = [&](int i) { return s_keys[i]; };
+            T = block_radix_select(key_at, found, k, s_hist, s_state);
+        }
+        if (tid == 0) s_count = 0;
+        __syncthreads();
+        for (int i = tid; i < found; i += nt) {
+            const uint64_t key = s_keys[i];
+            if (key <= T) {
+                const unsigned slot = atomicAdd(&s_count, 1u);   // min(found, k) keys qualify (keys are distinct)
+                if (slot < (unsigned)k) {
+                    s_d[slot] = (uint32_t)(key >> 32);
+                    s_id[slot] = ids[(uint32_t)key];
+                }
+            }
+        }
+    } else {
+        auto key_at = [&](int i) { return keys[i]; };
+        const uint64_t T = block_radix_select(key_at, n, k, s_hist, s_state);
+        if (tid == 0) s_count = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += nt) {
+            const uint64_t key = keys[i];
+            if (key <= T && key != kSentinel) {
+                const unsigned slot = atomicAdd(&s_count, 1u);   // exactly k keys are <= T (keys are distinct)
+                if (slot < (unsigned)k) {
+                    s_d[slot] = (uint32_t)(key >> 32);
+                    s_id[slot] = ids[(uint32_t)key];
+                }
             }
         }
     }
@@ -451,19 +583,20 @@ __global__ __launch_bounds__(256) void merge_kernel(const uint64_t *__restrict__
 // host side
 // ------------------------------------------------------------------------------------------------
 size_t scan_lds_bytes(int Mp, int KP, int nprobe) {
-    return (size_t)1024 * Mp + sizeof(uint64_t) * ((size_t)kScanWaves * 2 * KP + kScanWaves * kQueueCap + KP) +
+    return (size_t)1024 * Mp + sizeof(uint64_t) * ((size_t)KP + kCandRoom + 4) + sizeof(unsigned) * (256 + 2) +
            sizeof(int32_t) * (3 * (size_t)nprobe + 1);
 }
 
 template <int C>
 int launch_scan(const ScanArgs &a, int S, int nq, size_t lds, hipStream_t st) {
+    constexpr int NSETS = C <= 4 ? 4 : (C <= 6 ? 2 : 1);   // code blocks in flight per wave: as many as fit without register spills
     static size_t configured = 0;
     if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C>),
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    hipLaunchKernelGGL(adc_scan_kernel<C>, dim3(S, nq), dim3(kScanThreads), lds, st, a);
+    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS>), dim3(S, nq), dim3(kScanThreads), lds, st, a);
     return PIPERAG_OK;
 }
 
@@ -487,6 +620,11 @@ int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t s
         hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 1>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
     return PIPERAG_OK;
 }
+
+#ifdef PIPERAG_TRACE
+unsigned long long *g_trace_buf = nullptr;
+int g_trace_n = 0;
+#endif
 
 int check_search_args(const piperag_index *ix, const void *q, int32_t nq, int32_t nprobe, int32_t k, const void *od,
                       const void *oi) {
@@ -520,16 +658,27 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     else
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride);
     hipLaunchKernelGGL(plan_kernel, dim3(nq), dim3(64), 0, st, ix->ws_probe, pstride, nprobe, ix->list_blk, ix->list_len,
-                       ix->ws_pfx, ix->ws_scanned);
+                       ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     hipLaunchKernelGGL(lut_kernel, dim3(ix->Mp, nq), dim3(256), 0, st, q, ix->pq, ix->p.d, ix->p.M, ix->dsub, ix->Mp,
                        ix->ws_lut, 0);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
 
     const int KP = std::max(kWave, next_pow2(k));
-    int S = (kTargetScanWGs + nq - 1) / nq;
+    static const int target_wgs = [] {                      // tuning override, read once
+        const char *e = getenv("PIPERAG_SCAN_WGS");
+        const int v = e ? atoi(e) : 0;
+        return v > 0 && v <= 2 * kTargetScanWGs ? v : kTargetScanWGs;
+    }();
+    int S = (target_wgs + nq - 1) / nq;
     S = std::max(1, std::min(S, kMaxSegments));
-    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_probe, ix->ws_pfx, ix->list_blk, ix->list_len, ix->ws_part, nprobe, pstride, k, KP};
+    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_probe, ix->ws_pfx, ix->list_blk, ix->list_len, ix->ws_part, ix->ws_thr, nprobe, pstride, k, KP};
+#ifdef PIPERAG_TRACE
+    static unsigned long long *trace_buf = nullptr;
+    if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
+    a.trace = trace_buf;
+    g_trace_buf = trace_buf; g_trace_n = S * nq;
+#endif
     const size_t lds = scan_lds_bytes(ix->Mp, KP, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
     switch (ix->Mp / 16) {
@@ -545,7 +694,7 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     }
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[4], st));
-    hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(256), 0, st, ix->ws_part, S, k, ix->ids, out_d, out_i);
+    hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, S, k, ix->ids, ix->ws_thr, out_d, out_i);
     if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[5], st)); ix->ev_valid = true; }
     ix->last_nq = nq;
     PR_CHECK_HIP(hipGetLastError());
@@ -606,6 +755,14 @@ int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
 }
+
+#ifdef PIPERAG_TRACE
+__attribute__((visibility("default"))) int piperag_debug_trace(unsigned long long *out_host, int max_wg) {
+    const int n = g_trace_n < max_wg ? g_trace_n : max_wg;
+    if (hipMemcpy(out_host, g_trace_buf, sizeof(unsigned long long) * 8 * n, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return n;
+}
+#endif
 
 int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, int64_t *scanned_code_bytes) {
     PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
