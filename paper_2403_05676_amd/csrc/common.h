@@ -18,8 +18,9 @@ constexpr int kMaxK = 1024;
 constexpr int kMaxNprobe = 1024;
 constexpr int kScanThreads = 256;  // 4 waves per scan workgroup
 constexpr int kScanWaves = kScanThreads / kWave;
-constexpr int kTargetScanWGs = 1024;   // scan workgroups per search call (segments per query = this / nq)
+constexpr int kTargetScanWGs = 512;    // scan workgroups per search call: two per compute unit, all resident at once
 constexpr int kMaxSegments = 1024;
+constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
 constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
@@ -59,7 +60,8 @@ struct piperag_index {
     int dsub, Mp, device;
     // trained parameters (device)
     float *centroids;  // [nlist*d]
-    float *pq;         // [M*256*dsub]
+    float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
+    float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize
     int64_t cap, nadded;
     int32_t *st_list;   // [cap]
@@ -78,9 +80,11 @@ struct piperag_index {
     float *ws_probe_d;    // [max_nq*max_nprobe]
     int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
     int64_t *ws_scanned;  // [max_nq]
+    int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
+    int32_t *ws_wgq;      // [2*kTargetScanWGs+max_nq] query of each scan workgroup
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
-    uint64_t *ws_part;    // [(2*kTargetScanWGs+2*max_nq)*max_k] per-workgroup partial results
+    uint64_t *ws_part;    // [(2*kTargetScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results
     float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
     int64_t *ws_out_i;    // [max_nq*max_k]
     int *flag;            // [1] device flag for argument checks

@@ -26,55 +26,82 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Largest key of the kth (1-based) smallest among n distinct 64-bit keys - i.e. a threshold T such that exactly
-// kth keys are <= T - by most-significant-digit radix selection with the whole workgroup (blockDim >= 256,
-// a multiple of 64).  key_at(i) may be evaluated several times.  Requires 1 <= kth <= n.  Stops as soon as
-// the digits fixed so far isolate exactly the keys that are needed, which for float-derived keys is
-// usually after the 32 distance bits.
+// Workgroup-wide selection: returns a threshold T such that exactly kth of the keys key_at(0..n-1) are <= T.
+// Keys equal to kSentinel are ignored; the others must be distinct and at least kth of them must exist
+// (if fewer exist, kSentinel - 1 is returned: "keep all").  blockDim is a multiple of 64, >= 64.
+// Method: bucket counting over the value range that still contains the kth key - 256 equal-width buckets
+// over [lo, hi], starting from the actual minimum and maximum, narrowed to one bucket per round - so the
+// histogram is spread over the buckets from the first round on, whatever bits the keys have in common.
+// key_at(i) is evaluated once per round.  s_hist: 256 words, s_state: 8 words of LDS.
 template <class KeyFn>
-__device__ uint64_t block_radix_select(KeyFn key_at, int n, int kth, unsigned *s_hist /*[256]*/,
-                                       unsigned long long *s_state /*[4]*/) {
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
-    uint64_t prefix = 0;
-    for (int shift = 56; shift >= 0; shift -= 8) {
-        for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
-        __syncthreads();
+__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    // round 0: minimum, maximum and number of valid keys
+    uint64_t lo = kSentinel, hi = 0;
+    unsigned cnt = 0;
+    for (int i = tid; i < n; i += nt) {
+        const uint64_t key = key_at(i);
+        if (key != kSentinel) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; ++cnt; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint64_t ol = __shfl_xor(lo, off, 64), oh = __shfl_xor(hi, off, 64);
+        lo = ol < lo ? ol : lo; hi = oh > hi ? oh : hi;
+        cnt += __shfl_xor(cnt, off, 64);
+    }
+    if (tid == 0) { s_state[0] = kSentinel; s_state[1] = 0; s_state[2] = 0; }
+    for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
+    __syncthreads();
+    if (lane == 0) {
+        atomicMin(&s_state[0], (unsigned long long)lo);
+        atomicMax(&s_state[1], (unsigned long long)hi);
+        atomicAdd(&s_state[2], (unsigned long long)cnt);
+    }
+    __syncthreads();
+    lo = s_state[0]; hi = s_state[1];
+    const unsigned total = (unsigned)s_state[2];
+    __syncthreads();
+    if (total < (unsigned)kth) return kSentinel - 1;
+    unsigned need = (unsigned)kth;          // rank of the wanted key among the keys in [lo, hi]
+    for (;;) {
+        const uint64_t width = hi - lo;
+        const int sh = width < 256 ? 0 : (56 - __clzll((long long)width));     // (width >> sh) <= 255
         for (int i = tid; i < n; i += nt) {
             const uint64_t key = key_at(i);
-            const bool in = (shift == 56) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
-            if (in) atomicAdd(&s_hist[(unsigned)(key >> shift) & 255u], 1u);
+            if (key != kSentinel && key >= lo && key <= hi) atomicAdd(&s_hist[(unsigned)((key - lo) >> sh)], 1u);
         }
         __syncthreads();
-        // inclusive prefix sum of the 256 digit counts: within each of the first 4 waves, then across them
-        unsigned h = 0, incl = 0;
-        if (tid < 256) {
-            h = s_hist[tid];
-            incl = h;
+        if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
+            unsigned h[4], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { h[j] = s_hist[4 * lane + j]; s_hist[4 * lane + j] = 0; sum += h[j]; }
+            unsigned incl = sum;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const unsigned o = __shfl_up(incl, off, 64);
                 if (lane >= off) incl += o;
             }
-            if (lane == 63) s_state[wave] = incl;
+            unsigned before = incl - sum;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (before < need && need <= before + h[j]) {      // exactly one bucket qualifies
+                    s_state[0] = (unsigned long long)(4 * lane + j);
+                    s_state[1] = before;
+                    s_state[2] = h[j];
+                }
+                before += h[j];
+            }
         }
         __syncthreads();
-        if (tid < 256) {
-            for (int w = 0; w < wave; ++w) incl += (unsigned)s_state[w];
-        }
+        const unsigned bucket = (unsigned)s_state[0], below = (unsigned)s_state[1], inb = (unsigned)s_state[2];
         __syncthreads();
-        if (tid < 256 && incl - h < (unsigned)kth && (unsigned)kth <= incl) {   // exactly one digit qualifies
-            s_state[0] = prefix | ((uint64_t)tid << shift);
-            s_state[1] = (unsigned long long)((unsigned)kth - (incl - h));
-            s_state[2] = h;
-        }
-        __syncthreads();
-        prefix = s_state[0];
-        kth = (int)s_state[1];
-        const bool whole_bucket = (unsigned long long)kth == s_state[2];
-        __syncthreads();
-        if (whole_bucket) return prefix | (shift > 0 ? ((1ull << shift) - 1ull) : 0ull);
+        need -= below;
+        lo = lo + ((uint64_t)bucket << sh);
+        const uint64_t bhi = lo + ((sh > 0 ? (1ull << sh) : 1ull) - 1ull);
+        hi = bhi < hi ? bhi : hi;
+        if (inb == need) return hi;         // every key of this bucket is wanted: T = its upper end
+        // sh == 0 means one key value per bucket, so inb == 1 == need there: the loop ends at the latest then
     }
-    return prefix;
 }
 
 // In-place ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
@@ -146,21 +173,55 @@ __global__ __launch_bounds__(256) void coarse_rowwise_kernel(const float *__rest
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage 1a: per query, the nprobe smallest D[q][.] ordered by (distance, list).  One workgroup per query:
-// radix selection of the nprobe-th smallest key (distance bits << 32 | list; distances are >= 0 so their
-// bit patterns order like the values), compaction, bitonic sort.
+// Stage 1: top-nprobe selection and scan plan.
 // ------------------------------------------------------------------------------------------------
+// Per-query part of the plan, run by the first wavefront of a workgroup: pfx[i] = number of 64-vector blocks
+// in the first i probed lists (i = 0..nprobe), *scanned = vectors in the probed lists, *thr = "no bound yet"
+// for the scan's shared threshold.  probe_at(i) gives the i-th probed list or -1.
+template <class ProbeFn>
+__device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restrict__ list_blk,
+                           const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx, int64_t *__restrict__ scanned,
+                           uint32_t *__restrict__ thr) {
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    int32_t running = 0;
+    int64_t vecs = 0;
+    for (int base = 0; base < nprobe; base += 64) {
+        const int i = base + lane;
+        const int32_t l = i < nprobe ? probe_at(i) : -1;
+        const int32_t nb = l >= 0 ? list_blk[l + 1] - list_blk[l] : 0;
+        int64_t len = l >= 0 ? list_len[l] : 0;
+        int32_t incl = nb;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        if (i < nprobe) pfx[i] = running + incl - nb;
+        running += __shfl(incl, 63, 64);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) len += __shfl_xor(len, off, 64);
+        vecs += len;
+    }
+    if (lane == 0) { pfx[nprobe] = running; *scanned = vecs; *thr = 0xFFFFFFFFu; }
+}
+
+// Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
+// per query: selection of the nprobe-th smallest key (distance bits << 32 | list; distances are >= 0 so
+// their bit patterns order like the values), compaction, bitonic sort.
 __global__ __launch_bounds__(256) void select_probes_kernel(const float *__restrict__ D, int nlist, int nprobe,
                                                             int32_t *__restrict__ probe, float *__restrict__ probe_d,
-                                                            int probe_stride) {
+                                                            int probe_stride, const int32_t *__restrict__ list_blk,
+                                                            const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx,
+                                                            int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
     __shared__ unsigned s_hist[256];
-    __shared__ unsigned long long s_state[4];
+    __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count;
     const int qi = blockIdx.x;
     const float *row = D + (size_t)qi * nlist;
     auto key_at = [&](int i) { return ((uint64_t)__float_as_uint(row[i]) << 32) | (uint32_t)i; };
-    const uint64_t T = block_radix_select(key_at, nlist, nprobe, s_hist, s_state);
+    const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
     for (int i = threadIdx.x; i < np2; i += blockDim.x) s_keys[i] = kSentinel;
     if (threadIdx.x == 0) s_count = 0;
@@ -178,107 +239,142 @@ __global__ __launch_bounds__(256) void select_probes_kernel(const float *__restr
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
     }
+    auto probe_at = [&](int i) { return (int32_t)(s_keys[i] & 0xFFFFFFFFu); };
+    plan_query(probe_at, nprobe, list_blk, list_len, pfx + (size_t)qi * (probe_stride + 1), scanned + qi, thr + qi);
 }
 
 // Probe lists given by the caller: entries outside 0..nlist-1 and repeats of an earlier entry become -1
-// (skipped), so that no list is scanned twice.
-__global__ void copy_probes_kernel(const int32_t *__restrict__ src, int nprobe, int nlist, int32_t *__restrict__ dst,
-                                   int probe_stride) {
+// (skipped), so that no list is scanned twice.  Then the query's plan.
+__global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restrict__ src, int nprobe, int nlist,
+                                                         int32_t *__restrict__ dst, int probe_stride,
+                                                         const int32_t *__restrict__ list_blk,
+                                                         const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx,
+                                                         int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
     const int qi = blockIdx.x;
     const int32_t *row = src + (size_t)qi * nprobe;
+    int32_t *out = dst + (size_t)qi * probe_stride;
     for (int i = threadIdx.x; i < nprobe; i += blockDim.x) {
         int32_t l = row[i];
         if (l < 0 || l >= nlist) l = -1;
         for (int e = 0; e < i && l >= 0; ++e)
             if (row[e] == l) l = -1;
-        dst[(size_t)qi * probe_stride + i] = l;
+        out[i] = l;
     }
+    __syncthreads();
+    auto probe_at = [&](int i) { return out[i]; };
+    plan_query(probe_at, nprobe, list_blk, list_len, pfx + (size_t)qi * (probe_stride + 1), scanned + qi, thr + qi);
 }
 
-// Stage 1b: scan plan.  pfx[q][i] = number of 64-vector blocks in the first i probed lists of query q;
-// scanned[q] = number of vectors in its probed lists; thr[q] = "no bound yet" for the scan's shared threshold.
-__global__ void plan_kernel(const int32_t *__restrict__ probe, int probe_stride, int nprobe,
-                            const int32_t *__restrict__ list_blk, const int32_t *__restrict__ list_len,
-                            int32_t *__restrict__ pfx, int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
-    const int qi = blockIdx.x;
-    if (threadIdx.x != 0) return;
-    thr[qi] = 0xFFFFFFFFu;
-    int32_t blocks = 0;
-    int64_t vecs = 0;
-    int32_t *out = pfx + (size_t)qi * (probe_stride + 1);
-    for (int i = 0; i < nprobe; ++i) {
-        out[i] = blocks;
-        const int32_t l = probe[(size_t)qi * probe_stride + i];
-        if (l >= 0) {
-            blocks += list_blk[l + 1] - list_blk[l];
-            vecs += list_len[l];
+// Shares the scan workgroups out over the queries (one workgroup): query q gets
+// S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
+// per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
+// the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
+// use, at most max(target, nq)); wg_q[w] = query of workgroup w.  A workgroup gets at least kMinBlocksPerWG
+// blocks (unless its query has fewer), so that small searches are not spread over needlessly many workgroups.
+__global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
+                                                    int target, int32_t *__restrict__ seg0, int32_t *__restrict__ wg_q) {
+    __shared__ long long s_total;
+    __shared__ int32_t s_scan[256];
+    __shared__ int32_t s_carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) { s_total = 0; s_carry = 0; }
+    __syncthreads();
+    long long mine = 0;
+    for (int q = tid; q < nq; q += 256) mine += pfx[(size_t)q * (probe_stride + 1) + nprobe];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+    if ((tid & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&s_total), (unsigned long long)mine);
+    __syncthreads();
+    // sum of ceil(TB_q / per) <= total / per + nq, so dividing by (target - nq) keeps the sum within target
+    const long long denom = max(1, target - nq);
+    const long long per = max((long long)kMinBlocksPerWG, (s_total + denom - 1) / denom);
+    for (int q0 = 0; q0 < nq; q0 += 256) {
+        const int q = q0 + tid;
+        int32_t sq = 0;
+        if (q < nq) {
+            const long long tb = pfx[(size_t)q * (probe_stride + 1) + nprobe];
+            sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
         }
-    }
-    out[nprobe] = blocks;
-    scanned[qi] = vecs;
-}
-
-// ------------------------------------------------------------------------------------------------
-// Stage 2: lookup tables.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2.
-// Scan layout: lut[(q*256 + j)*Mp + m] (rows of padding sub-quantisers m >= M are zero);
-// canonical layout (tap): out[(q*M + m)*256 + j].
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ q, const float *__restrict__ pq, int d, int M,
-                                                  int dsub, int Mp, float *__restrict__ out, int canonical) {
-    const int qi = blockIdx.y, m = blockIdx.x, j = threadIdx.x;
-    float acc = 0.f;
-    if (m < M) {
-        const float *qs = q + (size_t)qi * d + m * dsub;
-        const float *c = pq + ((size_t)m * kKsub + j) * dsub;
-        for (int t = 0; t < dsub; ++t) {
-            const float diff = qs[t] - c[t];
-            acc += diff * diff;
+        s_scan[tid] = sq;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {          // Hillis-Steele inclusive scan
+            const int32_t add = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += add;
+            __syncthreads();
         }
+        const int32_t base = s_carry;
+        if (q < nq) seg0[q] = base + s_scan[tid] - sq;
+        __syncthreads();
+        if (tid == 255) s_carry = base + s_scan[255];
+        __syncthreads();
     }
-    if (canonical) {
-        if (m < M) out[((size_t)qi * M + m) * kKsub + j] = acc;
-    } else {
-        out[((size_t)qi * kKsub + j) * Mp + m] = acc;
+    if (tid == 0) seg0[nq] = s_carry;
+    __syncthreads();
+    const int total_wg = s_carry;
+    for (int w = tid; w < total_wg; w += 256) {            // query of workgroup w: last q with seg0[q] <= w
+        int lo = 0, hi = nq;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (seg0[mid] <= w) lo = mid; else hi = mid;
+        }
+        wg_q[w] = lo;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage 3: scan of the probed lists with k-selection.
-// grid = (S segments, nq).  The probed lists of a query, concatenated in probe order, form a sequence of
-// 64-vector blocks; segment s takes an equal share of it, and the 4 waves of the workgroup take its blocks
-// round-robin.  A lane owns one vector of the block: it reads its Mp code bytes with Mp/16 16-byte loads
-// (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.  Because of the rotated
-// code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp, so with the table
-// stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
-// For Mp = 64 the LDS byte address of a lookup is (code byte << 8) | (((l + t) mod 64) << 2): one byte
-// permute of the code word with a per-step lane constant held in a register.
-// k-selection: candidates (distance bits << 32 | slot) that pass a bound on the final k-th best distance
-// are appended to one candidate buffer per workgroup.  Once per round of NSETS blocks per wave the
-// workgroup meets at a barrier; when the buffer is nearly full it keeps only its k smallest keys (radix
-// selection in LDS, no sorting) and tightens the bound.  The bound is the smallest k-th best any workgroup
-// of the query has reached so far (thr[q] in global memory, polled with every block load); a candidate
-// above it cannot be in the result.  At the end the workgroup's (at most k) keys go to the
-// partial-result buffer, unsorted.
+// Stage 2 and 3 share the scan machinery below.
 // ------------------------------------------------------------------------------------------------
 struct ScanArgs {
     const uint8_t *codes;
-    const float *lut;
-    const int32_t *probe;
-    const int32_t *pfx;
+    const float *lut;          // [nq][256][Mp]
+    const int32_t *probe;      // [nq][probe_stride]
+    const int32_t *pfx;        // [nq][probe_stride+1]
     const int32_t *list_blk;
     const int32_t *list_len;
-    uint64_t *part;
-    uint32_t *thr;
-    int nprobe, probe_stride, k, KP;
+    uint64_t *part;            // [workgroups][KW] partial results
+    uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
+    const int32_t *seg0;       // [nq+1] first workgroup of each query
+    const int32_t *wg_q;       // [workgroups] query of each workgroup
+    int nq, nprobe, probe_stride, k, KW;
 #ifdef PIPERAG_TRACE
     unsigned long long *trace;   // [workgroups][8] timestamps
+    int flags;                   // experiments: 1 = no appends, 2 = no table lookups
 #endif
 };
 
 typedef const __attribute__((address_space(3))) float *lds_cfptr;
 
-constexpr int kCandRoom = 1536;                       // candidate slots beyond KP
-constexpr int kCandPerThread = (kMaxK + kCandRoom) / kScanThreads;
+constexpr int kKeepSlack = 64;                        // pruning keeps between k and k + kKeepSlack candidates
+constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack
+constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
+constexpr int kPrimeBlocks = 32;                      // blocks of the closest lists scanned to prime the bound
+
+// LDS carve-up shared by the priming and the scan kernel (all dynamic, so that the table starts at address 0)
+struct ScanLds {
+    float *lut;                  // [256*Mp]
+    uint64_t *cand;              // [cap]
+    unsigned long long *state;   // [8]
+    unsigned *hist;              // [256]
+    unsigned *misc;              // [8]: 0 count, 1 min distance bits, 2 max distance bits, 3 waves done
+    int32_t *pfx, *blk, *len;    // probe tables [nprobe+1], [nprobe], [nprobe]
+};
+__device__ __forceinline__ ScanLds carve_lds(unsigned char *smem, int Mp, int cap, int nprobe) {
+    ScanLds s;
+    s.lut = reinterpret_cast<float *>(smem);
+    s.cand = reinterpret_cast<uint64_t *>(smem + (size_t)1024 * Mp);
+    s.state = reinterpret_cast<unsigned long long *>(s.cand + cap);
+    s.hist = reinterpret_cast<unsigned *>(s.state + 8);
+    s.misc = s.hist + 256;
+    s.pfx = reinterpret_cast<int32_t *>(s.misc + 8);
+    s.blk = s.pfx + (nprobe + 1);
+    s.len = s.blk + nprobe;
+    return s;
+}
+size_t scan_lds_bytes(int Mp, int cap, int nprobe) {
+    return (size_t)1024 * Mp + sizeof(uint64_t) * ((size_t)cap + 8) + sizeof(unsigned) * (256 + 8) +
+           sizeof(int32_t) * (3 * (size_t)nprobe + 1);
+}
 
 // Distance of this lane's vector of one block, any Mp: table index = byte * Mp + (lane + t) mod Mp.
 template <int C>
@@ -320,89 +416,300 @@ __device__ __forceinline__ float block_dist_m64(const uint4 (&w)[4], const uint3
     return (acc0 + acc1) + (acc2 + acc3);
 }
 
-// Keeps the k smallest of the n (> k, distinct) keys in s_cand[0..n) at the front (any order) and returns
-// the largest key kept.  Whole workgroup, called at a barrier-synchronised point; *s_count becomes k.
-__device__ uint64_t wg_keep_k_smallest(uint64_t *s_cand, int n, int k, unsigned *s_hist, unsigned long long *s_state,
-                                       unsigned *s_count) {
-    const int tid = threadIdx.x;
-    auto key_at = [&](int i) { return s_cand[i]; };
-    const uint64_t T = block_radix_select(key_at, n, k, s_hist, s_state);
-    uint64_t mine[kCandPerThread];
-#pragma unroll
-    for (int e = 0; e < kCandPerThread; ++e) {
-        const int i = tid + e * kScanThreads;
-        mine[e] = i < n ? s_cand[i] : kSentinel;
-    }
-    if (tid == 0) *s_count = 0;
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < kCandPerThread; ++e)
-        if (mine[e] <= T && mine[e] != kSentinel) s_cand[atomicAdd(s_count, 1u)] = mine[e];
-    __syncthreads();
-    return T;
-}
-
-template <int C, int NSETS>
-__global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
-    constexpr int MP = 16 * C;
-    extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
-    const int k = a.k, KP = a.KP;
-    const int cap = KP + kCandRoom;
-    float *s_lut = reinterpret_cast<float *>(smem);                                  // [256*MP]
-    uint64_t *s_cand = reinterpret_cast<uint64_t *>(smem + (size_t)1024 * MP);       // [cap]
-    unsigned long long *s_state = reinterpret_cast<unsigned long long *>(s_cand + cap);   // [4]
-    unsigned *s_hist = reinterpret_cast<unsigned *>(s_state + 4);                    // [256]
-    unsigned *s_count = s_hist + 256;                                                // [1] (+1 pad)
-    int32_t *s_pfx = reinterpret_cast<int32_t *>(s_count + 2);                       // [nprobe+1]
-    int32_t *s_blk = s_pfx + (a.nprobe + 1);                                         // [nprobe]
-    int32_t *s_len = s_blk + a.nprobe;                                               // [nprobe]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qi = blockIdx.y, seg = blockIdx.x, S = gridDim.x;
-    const bool lut_at_zero =
-        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
-
-#ifdef PIPERAG_TRACE
-    unsigned long long *tr = a.trace + ((size_t)qi * S + seg) * 8;
-    unsigned nflush = 0;
-    if (tid == 0) tr[0] = wall_clock64();
-#endif
-    {   // stage the query's table and probe tables
-        const float4 *src = reinterpret_cast<const float4 *>(a.lut + (size_t)qi * kKsub * MP);
-        float4 *dst = reinterpret_cast<float4 *>(s_lut);
-        constexpr int kPer = kKsub * MP / 4 / kScanThreads;     // 16-byte pieces per thread (4*C)
-        float4 tmp[kPer];
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) tmp[i] = src[tid + i * kScanThreads];
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) dst[tid + i * kScanThreads] = tmp[i];
-        const int32_t *pf = a.pfx + (size_t)qi * (a.probe_stride + 1);
-        for (int i = tid; i <= a.nprobe; i += kScanThreads) s_pfx[i] = pf[i];
-        for (int i = tid; i < a.nprobe; i += kScanThreads) {
-            const int32_t l = a.probe[(size_t)qi * a.probe_stride + i];
-            s_blk[i] = l >= 0 ? a.list_blk[l] : 0;
-            s_len[i] = l >= 0 ? a.list_len[l] : 0;
-        }
-        if (tid == 0) *s_count = 0;
-    }
-    __syncthreads();
-
-#ifdef PIPERAG_TRACE
-    if (tid == 0) tr[1] = wall_clock64();
-#endif
-    uint32_t thr = 0xFFFFFFFFu;     // best known bound on the k-th best distance (bits)
-    const int TB = s_pfx[a.nprobe];
-    const int b_begin = (int)((int64_t)TB * seg / S), b_end = (int)((int64_t)TB * (seg + 1) / S);
-    const int rounds = (b_end - b_begin + kScanWaves * NSETS - 1) / (kScanWaves * NSETS);   // same for all waves
-    const int trigger = cap - kScanThreads * NSETS;      // a round appends at most 256*NSETS keys; trigger >= KP >= k
-    const int lane_m = lane % MP;
-    uint32_t off4[16];
+__device__ __forceinline__ void make_off4(uint32_t (&off4)[16], int lane) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         off4[i] = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) off4[i] |= ((uint32_t)((lane + 4 * i + j) & 63) << 2) << (8 * j);
     }
+}
+
+// Appends the passing lanes' candidates of one block to the workgroup's buffer.
+__device__ __forceinline__ void append_candidates(bool pass, uint32_t dbits, uint32_t slot_id, uint64_t *s_cand,
+                                                  unsigned *s_count, int cap, int lane) {
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    unsigned base = 0;
+    if (lane == 0) base = atomicAdd(s_count, (unsigned)__popcll(mask));
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (pass) {
+        const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+        if (slot < (unsigned)cap)      // always true (see the callers' capacity argument); guards against logic errors
+            s_cand[slot] = ((uint64_t)dbits << 32) | (uint64_t)slot_id;
+    }
+}
+
+// Prunes the candidate buffer s_cand[0..n), n > k: keeps every key whose distance is <= T, where T is chosen
+// so that between k and k + kKeepSlack keys remain (exactly k in the rare fall-back), and returns T (distance
+// bits).  Nothing that could be among the k best is dropped, and no sorting is done.  T is found by bucket
+// counting on the distance bits over [min, max], narrowed to one bucket per round.  Whole workgroup (at
+// least kScanThreads threads), called with all threads at the same point; *s.misc (the count) becomes the
+// number kept.
+__device__ uint32_t wg_prune(const ScanLds s, int n, int k) {
+    const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
+    uint64_t mine[kCandPerThread];
+    uint32_t dmin = 0xFFFFFFFFu, dmax = 0;
+#pragma unroll
+    for (int e = 0; e < kCandPerThread; ++e) {
+        const int i = tid + e * nt;
+        mine[e] = i < n ? s.cand[i] : kSentinel;
+        if (i < n) { const uint32_t d = (uint32_t)(mine[e] >> 32); dmin = min(dmin, d); dmax = max(dmax, d); }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        dmin = min(dmin, (uint32_t)__shfl_xor(dmin, off, 64));
+        dmax = max(dmax, (uint32_t)__shfl_xor(dmax, off, 64));
+    }
+    if (tid == 0) { s.misc[1] = 0xFFFFFFFFu; s.misc[2] = 0; }
+    for (int i = tid; i < 256; i += nt) s.hist[i] = 0;
+    __syncthreads();
+    if (lane == 0) { atomicMin(&s.misc[1], dmin); atomicMax(&s.misc[2], dmax); }
+    __syncthreads();
+    uint32_t lo = s.misc[1], hi = s.misc[2];
+    unsigned need = (unsigned)k, kept_below = 0;
+    bool accepted = false;
+    uint32_t T = hi;
+    for (int round = 0; round < 4 && !accepted; ++round) {
+        const uint32_t width = hi - lo;
+        const int sh = width < 256 ? 0 : (24 - __clz(width));            // (width >> sh) <= 255
+#pragma unroll
+        for (int e = 0; e < kCandPerThread; ++e) {
+            const uint32_t d = (uint32_t)(mine[e] >> 32);
+            if (mine[e] != kSentinel && d >= lo && d <= hi) atomicAdd(&s.hist[(d - lo) >> sh], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
+            unsigned h[4], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { h[j] = s.hist[4 * lane + j]; s.hist[4 * lane + j] = 0; sum += h[j]; }
+            unsigned incl = sum;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned o = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += o;
+            }
+            unsigned before = incl - sum;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (before < need && need <= before + h[j]) {      // the bucket that holds the need-th key
+                    s.state[0] = (unsigned long long)(4 * lane + j);
+                    s.state[1] = before;
+                    s.state[2] = h[j];
+                }
+                before += h[j];
+            }
+        }
+        __syncthreads();
+        const unsigned bucket = (unsigned)s.state[0], before = (unsigned)s.state[1], inb = (unsigned)s.state[2];
+        __syncthreads();
+        const uint32_t blo = lo + (bucket << sh);
+        const uint32_t edge = min(hi, blo + ((sh > 0 ? (1u << sh) : 1u) - 1u));
+        if (kept_below + before + inb <= (unsigned)(k + kKeepSlack)) {   // keeping the whole bucket is within the slack
+            T = edge;
+            accepted = true;
+        } else if (sh == 0) {
+            break;                                                       // too many equal distances: exact fall-back
+        } else {
+            kept_below += before; need -= before; lo = blo; hi = edge;   // look inside the bucket
+        }
+    }
+    uint64_t Tkey = ((uint64_t)T << 32) | 0xFFFFFFFFull;
+    if (!accepted) {                        // exact selection on (distance, slot) keys: keeps exactly k
+        auto key_at = [&](int i) { return s.cand[i]; };
+        Tkey = block_select_kth(key_at, n, k, s.hist, s.state);
+        T = (uint32_t)(Tkey >> 32);
+    }
+    if (tid == 0) s.misc[0] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kCandPerThread; ++e)
+        if (mine[e] <= Tkey && mine[e] != kSentinel) s.cand[atomicAdd(&s.misc[0], 1u)] = mine[e];
+    __syncthreads();
+    return T;
+}
+
+// Copies the query's probe tables into LDS (block prefix sums, first block and length of each probed list).
+__device__ __forceinline__ void stage_probe_tables(const ScanArgs &a, const ScanLds &s, int qi) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int32_t *pf = a.pfx + (size_t)qi * (a.probe_stride + 1);
+    for (int i = tid; i <= a.nprobe; i += nt) s.pfx[i] = pf[i];
+    for (int i = tid; i < a.nprobe; i += nt) {
+        const int32_t l = a.probe[(size_t)qi * a.probe_stride + i];
+        s.blk[i] = l >= 0 ? a.list_blk[l] : 0;
+        s.len[i] = l >= 0 ? a.list_len[l] : 0;
+    }
+    if (tid == 0) { s.misc[0] = 0; s.misc[3] = 0; }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Stage 2: lookup tables + priming of the bound.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2.
+// One workgroup (512 threads) per query builds the table in LDS in the scan layout [j][Mp] (rows of padding
+// sub-quantisers m >= M are zero) from the centre-major copy of the codebook pqT[j][m][t] - a wave takes four
+// j at a time and its lanes the sub-quantisers, so both the global reads and the LDS writes are contiguous -
+// and writes it to lut[q].  It then scans the first kPrimeBlocks blocks of the query's probed lists (the
+// closest lists come first) with that table and sets thr[q] to a distance that at least k of those vectors
+// reach: the scan proper starts with a useful bound instead of accepting everything.
+// ------------------------------------------------------------------------------------------------
+constexpr int kLutThreads = 512;
+constexpr int kLutWaves = kLutThreads / kWave;
+
+// One table entry: squared distance between dsub query coordinates and dsub centre coordinates.  DSUB > 0
+// fixes dsub at compile time (all loads of several entries can then be in flight together).
+template <int DSUB>
+__device__ __forceinline__ float lut_entry(const float *__restrict__ qs, const float *__restrict__ c, int dsub) {
+    float acc = 0.f;
+    if (DSUB > 0) {
+        float cv[DSUB > 0 ? DSUB : 1];
+        if (DSUB % 4 == 0) {
+#pragma unroll
+            for (int t = 0; t < DSUB; t += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(c + t);
+                cv[t] = v.x; cv[(t + 1) % (DSUB > 0 ? DSUB : 1)] = v.y; cv[(t + 2) % (DSUB > 0 ? DSUB : 1)] = v.z;
+                cv[(t + 3) % (DSUB > 0 ? DSUB : 1)] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < DSUB; ++t) cv[t] = c[t];
+        }
+#pragma unroll
+        for (int t = 0; t < DSUB; ++t) {
+            const float diff = qs[t] - cv[t];
+            acc += diff * diff;
+        }
+    } else {
+        for (int t = 0; t < dsub; ++t) {
+            const float diff = qs[t] - c[t];
+            acc += diff * diff;
+        }
+    }
+    return acc;
+}
+
+template <int C, int DSUB>
+__global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__restrict__ q, const float *__restrict__ pqT,
+                                                                int d, int M, int dsub, float *__restrict__ lut_out,
+                                                                ScanArgs a) {
+    constexpr int MP = 16 * C;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int cap = kPrimeBlocks * kBlockVecs;
+    const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
+    float *s_q = reinterpret_cast<float *>(s.len + a.nprobe);      // [d] the query
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = blockIdx.x;
+    const bool lut_at_zero =
+        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
+    stage_probe_tables(a, s, qi);
+    for (int t = tid; t < d; t += kLutThreads) s_q[t] = q[(size_t)qi * d + t];
+    __syncthreads();
+    // table: lane <-> sub-quantiser, wave <-> centre (4 centres at a time)
+    for (int m = lane; m < MP; m += kWave) {
+        const float *qs = s_q + m * dsub;
+        for (int j0 = wave * 4; j0 < kKsub; j0 += kLutWaves * 4) {
+            float e[4] = {0.f, 0.f, 0.f, 0.f};
+            if (m < M) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) e[jj] = lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) s.lut[(j0 + jj) * MP + m] = e[jj];
+        }
+    }
+    __syncthreads();
+    {
+        float4 *dst = reinterpret_cast<float4 *>(lut_out + (size_t)qi * kKsub * MP);
+        const float4 *src = reinterpret_cast<const float4 *>(s.lut);
+        for (int i = tid; i < kKsub * MP / 4; i += kLutThreads) dst[i] = src[i];
+    }
+    // priming scan
+    const int TB = s.pfx[a.nprobe];
+    const int nb = min(TB, kPrimeBlocks);
+    const int lane_m = lane % MP;
+    uint32_t off4[16];
+    make_off4(off4, lane);
+    int pi = 0;
+    for (int b = wave; b < nb; b += kLutWaves) {
+        while (b >= s.pfx[pi + 1]) ++pi;                      // b < TB = pfx[nprobe]
+        const int bl = b - s.pfx[pi];
+        const uint32_t gblock = (uint32_t)(s.blk[pi] + bl);
+        const int nvalid = s.len[pi] - bl * kBlockVecs;
+        const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock * kBlockVecs * MP);
+        uint4 w[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) w[c] = blk[c * kWave + lane];
+        float dist;
+        if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
+        else dist = block_dist_generic<C>(w, s.lut, lane_m);
+        append_candidates(lane < nvalid, __float_as_uint(dist), gblock * kBlockVecs + lane, s.cand, &s.misc[0], cap, lane);
+    }
+    __syncthreads();
+    const int n = min((int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]), cap);
+    if (n > a.k) {                          // uniform
+        const uint32_t T = wg_prune(s, n, a.k);
+        if (tid == 0) a.thr[qi] = T;        // plan_query set "no bound"; the scan only lowers it from here
+    }
+}
+
+// Tap: the tables in canonical layout out[(q*M + m)*256 + j].
+__global__ __launch_bounds__(256) void lut_tap_kernel(const float *__restrict__ q, const float *__restrict__ pq, int d, int M,
+                                                      int dsub, float *__restrict__ out) {
+    const int qi = blockIdx.y, m = blockIdx.x, j = threadIdx.x;
+    const float *qs = q + (size_t)qi * d + m * dsub;
+    const float *c = pq + ((size_t)m * kKsub + j) * dsub;
+    float acc = 0.f;
+    for (int t = 0; t < dsub; ++t) {
+        const float diff = qs[t] - c[t];
+        acc += diff * diff;
+    }
+    out[((size_t)qi * M + m) * kKsub + j] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Stage 3: scan of the probed lists with candidate selection.
+// The probed lists of a query, concatenated in probe order, form a sequence of 64-vector blocks; the plan
+// gives workgroup w a query and an equal share [b_begin, b_end) of that sequence, and the 4 waves of the
+// workgroup take its blocks round-robin.  A lane owns one vector of the block: it reads its Mp code bytes
+// with Mp/16 16-byte loads (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.
+// Because of the rotated code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp,
+// so with the table stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
+// Candidates (distance bits << 32 | slot) that pass the bound on the final k-th best distance are appended
+// to one buffer per workgroup.  The waves run independently; a wave that sees the buffer nearly full (or has
+// no blocks left) waits at a barrier, and once all four are there the buffer is pruned to about k keys and
+// the bound tightened.  The bound is the smallest such value any workgroup of the query has reached
+// (thr[q] in global memory, polled with every block load).  At the end the workgroup's (at most KW)
+// surviving keys go to the partial-result buffer, unsorted; stage 4 selects among them.
+// ------------------------------------------------------------------------------------------------
+template <int C, int NSETS>
+__global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
+    constexpr int MP = 16 * C;
+    extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
+    const int k = a.k, KW = a.KW;
+    const int cap = KW + kCandRoom;
+    const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wg = blockIdx.x;
+    if (wg >= a.seg0[a.nq]) return;                         // spare workgroup (uniform exit)
+    const int qi = a.wg_q[wg];
+    const int seg = wg - a.seg0[qi], S = a.seg0[qi + 1] - a.seg0[qi];
+    const bool lut_at_zero =
+        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
+#ifdef PIPERAG_TRACE
+    unsigned long long *tr = a.trace + (size_t)wg * 8;
+    unsigned nflush = 0;
+    unsigned long long tflush = 0;
+    if (tid == 0) tr[0] = wall_clock64();
+#endif
+    stage_probe_tables(a, s, qi);          // first: the first code loads depend on them
+    __syncthreads();
+
+    uint32_t thr = 0xFFFFFFFFu;     // best known bound on the k-th best distance (bits)
+    const int TB = s.pfx[a.nprobe];
+    const int b_begin = (int)((int64_t)TB * seg / S), b_end = (int)((int64_t)TB * (seg + 1) / S);
+    // a wave checks the count before every block and appends at most 64 keys per block
+    const int trigger = cap - kScanThreads;
+    const int lane_m = lane % MP;
+    uint32_t off4[16];
+    make_off4(off4, lane);
 
     int b_next = b_begin + wave;    // next block this wave will request
     int pi = 0;                     // probe whose list holds b_next (advanced monotonically)
@@ -411,10 +718,10 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     auto issue = [&](uint4 (&w)[C], Meta &m) {
         m.valid = b_next < b_end;
         if (!m.valid) return;
-        while (b_next >= s_pfx[pi + 1]) ++pi;                 // b_next < TB = s_pfx[nprobe], so pi stays < nprobe
-        const int bl = b_next - s_pfx[pi];
-        m.gblock = (uint32_t)(s_blk[pi] + bl);
-        m.nvalid = s_len[pi] - bl * kBlockVecs;               // >= 1; lanes >= nvalid hold padding
+        while (b_next >= s.pfx[pi + 1]) ++pi;                 // b_next < TB = pfx[nprobe], so pi stays < nprobe
+        const int bl = b_next - s.pfx[pi];
+        m.gblock = (uint32_t)(s.blk[pi] + bl);
+        m.nvalid = s.len[pi] - bl * kBlockVecs;               // >= 1; lanes >= nvalid hold padding
         const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP);
 #pragma unroll
         for (int c = 0; c < C; ++c) w[c] = blk[c * kWave + lane];
@@ -423,61 +730,98 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     };
     auto process = [&](const uint4 (&w)[C], const Meta &m) {
         float dist;
+#ifdef PIPERAG_TRACE
+        if (a.flags & 2) {
+            uint32_t x = 0;
+#pragma unroll
+            for (int c = 0; c < C; ++c) x += w[c].x ^ w[c].y ^ w[c].z ^ w[c].w;
+            dist = (float)(x & 0xFFFF) + 1.0f;
+        } else
+#endif
         if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
-        else dist = block_dist_generic<C>(w, s_lut, lane_m);
+        else dist = block_dist_generic<C>(w, s.lut, lane_m);
         const uint32_t dbits = __float_as_uint(dist);
         thr = min(thr, m.tg);
-        const bool pass = (lane < m.nvalid) && (dbits <= thr);
-        const uint64_t mask = __ballot(pass);
-        if (mask != 0) {
-            unsigned base = 0;
-            if (lane == 0) base = atomicAdd(s_count, (unsigned)__popcll(mask));
-            base = __builtin_amdgcn_readfirstlane(base);
-            if (pass) {
-                const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
-                if (slot < (unsigned)cap)     // always true (see trigger); keeps a logic error from writing out of bounds
-                    s_cand[slot] = ((uint64_t)dbits << 32) | (uint64_t)(m.gblock * kBlockVecs + lane);
-            }
-        }
+        bool pass = (lane < m.nvalid) && (dbits <= thr);
+#ifdef PIPERAG_TRACE
+        if (a.flags & 1) pass = false;
+#endif
+        append_candidates(pass, dbits, m.gblock * kBlockVecs + lane, s.cand, &s.misc[0], cap, lane);
     };
 
     uint4 w[NSETS][C];
     Meta meta[NSETS];
 #pragma unroll
-    for (int s = 0; s < NSETS; ++s) issue(w[s], meta[s]);
-    for (int r = 0; r < rounds; ++r) {
+    for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i]);
+    {   // the query's table, while the first code blocks are on their way
+        const float4 *src = reinterpret_cast<const float4 *>(a.lut + (size_t)qi * kKsub * MP);
+        float4 *dst = reinterpret_cast<float4 *>(s.lut);
+        constexpr int kPer = kKsub * MP / 4 / kScanThreads;     // 16-byte pieces per thread (4*C)
 #pragma unroll
-        for (int s = 0; s < NSETS; ++s) {
-            if (meta[s].valid) process(w[s], meta[s]);
-            issue(w[s], meta[s]);
+        for (int i0 = 0; i0 < kPer; i0 += 8) {
+            float4 tmp[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) if (i0 + i < kPer) tmp[i] = src[tid + (i0 + i) * kScanThreads];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) if (i0 + i < kPer) dst[tid + (i0 + i) * kScanThreads] = tmp[i];
+        }
+    }
+    __syncthreads();
+#ifdef PIPERAG_TRACE
+    if (tid == 0) tr[1] = wall_clock64();
+#endif
+    bool announced = false;         // this wave has told the others that it is out of blocks
+    for (;;) {
+        bool hold = false, any = false;
+#pragma unroll
+        for (int i = 0; i < NSETS; ++i) {
+            if (meta[i].valid) {
+                any = true;
+                if (!hold) hold = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]) > trigger;
+                if (!hold) {
+                    process(w[i], meta[i]);
+                    issue(w[i], meta[i]);
+                }
+            }
+        }
+        if (!hold && any) continue;
+        // buffer nearly full, or this wave is out of blocks: meet the other waves
+        if (!any && !announced) {
+            announced = true;
+            if (lane == 0) atomicAdd(&s.misc[3], 1u);
         }
         __syncthreads();
-        const int n = (int)*reinterpret_cast<volatile unsigned *>(s_count);
-        if (n > trigger) {          // uniform: every thread reads the same value after the barrier
-            const uint64_t T = wg_keep_k_smallest(s_cand, min(n, cap), k, s_hist, s_state, s_count);
-            const uint32_t kth = (uint32_t)(T >> 32);
-            thr = min(thr, kth);
-            if (tid == 0) atomicMin(&a.thr[qi], kth);
+        const int n = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]);
+        const int ndone = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[3]);
+        __syncthreads();            // nobody appends again before everybody has read the two counters
+        if (n > trigger) {          // uniform: all threads read the same values between the barriers
 #ifdef PIPERAG_TRACE
+            const unsigned long long tf0 = wall_clock64();
+#endif
+            const uint32_t T = wg_prune(s, min(n, cap), k);
+            thr = min(thr, T);
+            if (tid == 0) atomicMin(&a.thr[qi], T);
+#ifdef PIPERAG_TRACE
+            tflush += wall_clock64() - tf0;
             ++nflush;
 #endif
         }
+        if (ndone == kScanWaves) break;
     }
 #ifdef PIPERAG_TRACE
-    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)(b_end - b_begin); }
+    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)(b_end - b_begin); tr[7] = tflush; }
 #endif
-    __syncthreads();
-    int n = min((int)*reinterpret_cast<volatile unsigned *>(s_count), cap);
-    if (n > k) {
-        const uint64_t T = wg_keep_k_smallest(s_cand, n, k, s_hist, s_state, s_count);
-        if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
-        n = k;
+    int n = min((int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]), cap);
+    if (n > KW) {                   // uniform
+        const uint32_t T = wg_prune(s, n, k);
+        if (tid == 0) atomicMin(&a.thr[qi], T);
+        n = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]);
     }
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[3] = wall_clock64();
 #endif
-    uint64_t *out = a.part + ((size_t)qi * S + seg) * k;
-    for (int i = tid; i < k; i += kScanThreads) out[i] = i < n ? s_cand[i] : kSentinel;
+    uint64_t *out = a.part + (size_t)wg * KW;
+    for (int i = tid; i < KW; i += kScanThreads) out[i] = i < n ? s.cand[i] : kSentinel;
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[4] = wall_clock64();
 #endif
@@ -493,19 +837,20 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 // ------------------------------------------------------------------------------------------------
 constexpr int kMergeThreads = 1024;
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__restrict__ part, int S, int k,
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__restrict__ part,
+                                                              const int32_t *__restrict__ seg0, int KW, int k,
                                                               const int64_t *__restrict__ ids,
                                                               const uint32_t *__restrict__ thr, float *__restrict__ out_d,
                                                               int64_t *__restrict__ out_i) {
     __shared__ uint64_t s_keys[kMergeCap];
     __shared__ unsigned s_hist[256];
-    __shared__ unsigned long long s_state[4];
+    __shared__ unsigned long long s_state[8];
     __shared__ uint32_t s_d[kMaxK];
     __shared__ int64_t s_id[kMaxK];
     __shared__ unsigned s_count;
     const int qi = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    const int n = S * k;
-    const uint64_t *keys = part + (size_t)qi * n;
+    const int n = (seg0[qi + 1] - seg0[qi]) * KW;            // KW slots per workgroup, unused ones hold kSentinel
+    const uint64_t *keys = part + (size_t)seg0[qi] * KW;
     const uint32_t bound = thr[qi];
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
     for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
@@ -525,7 +870,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__
         uint64_t T = kSentinel - 1;                              // fewer than k candidates: keep them all
         if (found > k) {
             auto key_at = [&](int i) { return s_keys[i]; };
-            T = block_radix_select(key_at, found, k, s_hist, s_state);
+            T = block_select_kth(key_at, found, k, s_hist, s_state);
         }
         if (tid == 0) s_count = 0;
         __syncthreads();
@@ -541,7 +886,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__
         }
     } else {
         auto key_at = [&](int i) { return keys[i]; };
-        const uint64_t T = block_radix_select(key_at, n, k, s_hist, s_state);
+        const uint64_t T = block_select_kth(key_at, n, k, s_hist, s_state);
         if (tid == 0) s_count = 0;
         __syncthreads();
         for (int i = tid; i < n; i += nt) {
@@ -582,13 +927,30 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-size_t scan_lds_bytes(int Mp, int KP, int nprobe) {
-    return (size_t)1024 * Mp + sizeof(uint64_t) * ((size_t)KP + kCandRoom + 4) + sizeof(unsigned) * (256 + 2) +
-           sizeof(int32_t) * (3 * (size_t)nprobe + 1);
+template <int C, int DSUB>
+int launch_lut_prime_d(const piperag_index *ix, const float *q, int nq, const ScanArgs &a, hipStream_t st) {
+    const size_t lds = scan_lds_bytes(ix->Mp, kPrimeBlocks * kBlockVecs, a.nprobe) + sizeof(float) * ix->p.d;
+    PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "table kernel needs %zu bytes of LDS", lds);
+    static size_t configured = 0;
+    if (lds > configured) {
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&lut_prime_kernel<C, DSUB>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    hipLaunchKernelGGL((lut_prime_kernel<C, DSUB>), dim3(nq), dim3(kLutThreads), lds, st, q, ix->pqT, ix->p.d, ix->p.M, ix->dsub,
+                       ix->ws_lut, a);
+    return PIPERAG_OK;
 }
 
 template <int C>
-int launch_scan(const ScanArgs &a, int S, int nq, size_t lds, hipStream_t st) {
+int launch_lut_prime(const piperag_index *ix, const float *q, int nq, const ScanArgs &a, hipStream_t st) {
+    if (C == 4 && ix->p.M == 64 && ix->dsub == 12) return launch_lut_prime_d<C == 4 ? 4 : C, C == 4 ? 12 : 0>(ix, q, nq, a, st);
+    if (C == 4 && ix->p.M == 64 && ix->dsub == 6) return launch_lut_prime_d<C == 4 ? 4 : C, C == 4 ? 6 : 0>(ix, q, nq, a, st);
+    return launch_lut_prime_d<C, 0>(ix, q, nq, a, st);
+}
+
+template <int C>
+int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
     constexpr int NSETS = C <= 4 ? 4 : (C <= 6 ? 2 : 1);   // code blocks in flight per wave: as many as fit without register spills
     static size_t configured = 0;
     if (lds > configured) {
@@ -596,9 +958,22 @@ int launch_scan(const ScanArgs &a, int S, int nq, size_t lds, hipStream_t st) {
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS>), dim3(S, nq), dim3(kScanThreads), lds, st, a);
+    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS>), dim3(G), dim3(kScanThreads), lds, st, a);
     return PIPERAG_OK;
 }
+
+#define PR_DISPATCH_C(expr_prefix, ...)                                         \
+    switch (ix->Mp / 16) {                                                      \
+        case 1: rc = expr_prefix<1>(__VA_ARGS__); break;                        \
+        case 2: rc = expr_prefix<2>(__VA_ARGS__); break;                        \
+        case 3: rc = expr_prefix<3>(__VA_ARGS__); break;                        \
+        case 4: rc = expr_prefix<4>(__VA_ARGS__); break;                        \
+        case 5: rc = expr_prefix<5>(__VA_ARGS__); break;                        \
+        case 6: rc = expr_prefix<6>(__VA_ARGS__); break;                        \
+        case 7: rc = expr_prefix<7>(__VA_ARGS__); break;                        \
+        case 8: rc = expr_prefix<8>(__VA_ARGS__); break;                        \
+        default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");           \
+    }
 
 int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
     constexpr int QT = 4;
@@ -652,49 +1027,42 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
     if (!probes && (rc = launch_coarse(ix, q, nq, st)) != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
-    if (!probes)
-        hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(256), 0, st, ix->ws_D, ix->p.nlist, nprobe, ix->ws_probe,
-                           ix->ws_probe_d, pstride);
-    else
-        hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride);
-    hipLaunchKernelGGL(plan_kernel, dim3(nq), dim3(64), 0, st, ix->ws_probe, pstride, nprobe, ix->list_blk, ix->list_len,
-                       ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
-    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
-    hipLaunchKernelGGL(lut_kernel, dim3(ix->Mp, nq), dim3(256), 0, st, q, ix->pq, ix->p.d, ix->p.M, ix->dsub, ix->Mp,
-                       ix->ws_lut, 0);
-    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
-
-    const int KP = std::max(kWave, next_pow2(k));
     static const int target_wgs = [] {                      // tuning override, read once
         const char *e = getenv("PIPERAG_SCAN_WGS");
         const int v = e ? atoi(e) : 0;
         return v > 0 && v <= 2 * kTargetScanWGs ? v : kTargetScanWGs;
     }();
-    int S = (target_wgs + nq - 1) / nq;
-    S = std::max(1, std::min(S, kMaxSegments));
-    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_probe, ix->ws_pfx, ix->list_blk, ix->list_len, ix->ws_part, ix->ws_thr, nprobe, pstride, k, KP};
+    if (!probes)
+        hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(256), 0, st, ix->ws_D, ix->p.nlist, nprobe, ix->ws_probe,
+                           ix->ws_probe_d, pstride, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
+    else
+        hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
+                           ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
+    hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, ix->ws_seg0,
+                       ix->ws_wgq);
+    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
+    const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
+    const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
+    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_probe, ix->ws_pfx, ix->list_blk, ix->list_len, ix->ws_part, ix->ws_thr,
+               ix->ws_seg0, ix->ws_wgq, nq, nprobe, pstride, k, KW};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
+    PR_CHECK_HIP(hipMemsetAsync(trace_buf, 0, 8 * sizeof(unsigned long long) * 8192, st));
     a.trace = trace_buf;
-    g_trace_buf = trace_buf; g_trace_n = S * nq;
+    { const char *e = getenv("PIPERAG_DEBUG_FLAGS"); a.flags = e ? atoi(e) : 0; }
+    g_trace_buf = trace_buf; g_trace_n = G;
 #endif
-    const size_t lds = scan_lds_bytes(ix->Mp, KP, nprobe);
+    PR_DISPATCH_C(launch_lut_prime, ix, q, nq, a, st)
+    if (rc != PIPERAG_OK) return rc;
+    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
+    const size_t lds = scan_lds_bytes(ix->Mp, KW + kCandRoom, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
-    switch (ix->Mp / 16) {
-        case 1: rc = launch_scan<1>(a, S, nq, lds, st); break;
-        case 2: rc = launch_scan<2>(a, S, nq, lds, st); break;
-        case 3: rc = launch_scan<3>(a, S, nq, lds, st); break;
-        case 4: rc = launch_scan<4>(a, S, nq, lds, st); break;
-        case 5: rc = launch_scan<5>(a, S, nq, lds, st); break;
-        case 6: rc = launch_scan<6>(a, S, nq, lds, st); break;
-        case 7: rc = launch_scan<7>(a, S, nq, lds, st); break;
-        case 8: rc = launch_scan<8>(a, S, nq, lds, st); break;
-        default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");
-    }
+    PR_DISPATCH_C(launch_scan, a, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[4], st));
-    hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, S, k, ix->ids, ix->ws_thr, out_d, out_i);
+    hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, ix->ws_seg0, KW, k, ix->ids, ix->ws_thr, out_d,
+                       out_i);
     if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[5], st)); ix->ev_valid = true; }
     ix->last_nq = nq;
     PR_CHECK_HIP(hipGetLastError());
@@ -734,7 +1102,7 @@ int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int
     const int rc = launch_coarse(ix, queries_dev, nq, st);
     if (rc != PIPERAG_OK) return rc;
     hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(256), 0, st, ix->ws_D, ix->p.nlist, nprobe, ix->ws_probe,
-                       ix->ws_probe_d, ix->p.max_nprobe);
+                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
     PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ix->ws_probe, sizeof(int32_t) * ix->p.max_nprobe,
                                   sizeof(int32_t) * nprobe, nq, hipMemcpyDeviceToDevice, st));
     if (out_dist_dev)
@@ -750,8 +1118,8 @@ int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_
     if (nq == 0) return PIPERAG_OK;
     PR_REQUIRE(queries_dev && out_lut_dev, PIPERAG_ERR_ARG, "queries / output pointer is NULL");
     PR_CHECK_HIP(hipSetDevice(index->device));
-    hipLaunchKernelGGL(lut_kernel, dim3(index->p.M, nq), dim3(256), 0, (hipStream_t)stream, queries_dev, index->pq, index->p.d,
-                       index->p.M, index->dsub, index->Mp, out_lut_dev, 1);
+    hipLaunchKernelGGL(lut_tap_kernel, dim3(index->p.M, nq), dim3(256), 0, (hipStream_t)stream, queries_dev, index->pq,
+                       index->p.d, index->p.M, index->dsub, out_lut_dev);
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
 }

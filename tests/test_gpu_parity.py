@@ -341,3 +341,15 @@ def test_gpu_kmeans_follows_the_oracle():
     np.testing.assert_allclose(s1, oracle.kmeans(x[:, 8:16], 256, rows2, 1), rtol=2e-6, atol=2e-6)
     # deterministic
     assert torch.equal(pkg.kmeans(xd, K, rows, 3), pkg.kmeans(xd, K, rows, 3))
+
+
+def test_long_lists_exercise_the_in_loop_candidate_pruning():
+    # few long lists, many candidates per workgroup: the scan's candidate buffer fills up and is pruned
+    # several times inside the scan loop (short lists never get there)
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(120000, 64, 4, 64, seed=99, nq=16, sigma=0.5, ncomp=4)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=4, max_k=128)
+    for k in (1, 100, 128):                     # ~29 blocks per workgroup, 16 per round: pruned in the first round
+        run_search_parity(pkg, ix, oidx, q, 4, k)
+    run_search_parity(pkg, ix, oidx, q[:1], 2, 100)
