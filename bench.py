@@ -77,6 +77,50 @@ def host_copy(ix, coarse, pq):
     return oracle.Index(coarse, pq, off, codes, ids)
 
 
+def shorten(kernel_name):
+    name = kernel_name.replace("(anonymous namespace)::", "").replace("void ", "")
+    return name.split("(")[0][:60]
+
+
+def summarize_rocprof(root, command):
+    """Short text summary of rocprofv3 --output-format csv results: per-kernel totals from the kernel trace and
+    per-kernel means of every counter collected."""
+    import collections
+    import csv
+    lines = [f"command: {command}" if command else "command: (not given)"]
+    for dirpath, _, files in os.walk(root):
+        for f in sorted(files):
+            path = os.path.join(dirpath, f)
+            if f.endswith("kernel_trace.csv"):
+                agg = collections.defaultdict(list)
+                for r in csv.DictReader(open(path)):
+                    agg[r["Kernel_Name"]].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+                tot = sum(sum(v) for v in agg.values())
+                lines.append(f"kernel trace ({f}): calls, total us, average us, min us, max us, share")
+                for name, v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
+                    short = shorten(name)
+                    lines.append(f"  {short:60s} {len(v):6d} {sum(v):12.1f} {sum(v)/len(v):10.2f} {min(v):10.2f} {max(v):10.2f} {100*sum(v)/tot:6.2f}%")
+            if f.endswith("counter_collection.csv"):
+                agg = collections.defaultdict(list)
+                for r in csv.DictReader(open(path)):
+                    agg[(shorten(r["Kernel_Name"]), r["Counter_Name"])].append(float(r["Counter_Value"]))
+                lines.append(f"counters ({f}): kernel, counter, dispatches, mean, min, max per dispatch")
+                for (name, ctr), v in sorted(agg.items()):
+                    lines.append(f"  {name:44s} {ctr:24s} {len(v):5d} {sum(v)/len(v):16.1f} {min(v):16.1f} {max(v):16.1f}")
+    return "\n".join(lines)
+
+
+def stored_traffic(workload):
+    """HBM bytes per scan launch from the committed counter summary (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", f"adc_scan_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,7 +128,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 1 GiB copy kernel three times (reference for the HBM traffic counters)")
+    ap.add_argument("--summarize", metavar="DIR", help="write a text summary of rocprofv3 CSV output found under DIR and exit")
+    ap.add_argument("--command", default="", help="with --summarize: the command line that produced DIR")
     args = ap.parse_args()
+    if args.summarize:
+        print(summarize_rocprof(args.summarize, args.command))
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: the library is single-GPU by design (no collectives); run with --gpus 1",
               file=sys.stderr)
@@ -131,13 +183,13 @@ def main():
     # ---- single-query latency (host call -> stream synchronised), p50 --------------------------
     q1 = q[:1].contiguous()
     lat = []
-    for r in range(args.warmup + args.steps):
+    for r in range(0 if args.no_latency else args.warmup + args.steps):
         t1 = time.perf_counter()
         ix.ivfpq_search(q1, cfg.nprobe, cfg.k, out_d[:1], out_i[:1])
         torch.cuda.synchronize()
         if r >= args.warmup:
             lat.append((time.perf_counter() - t1) * 1e3)
-    p50_1q = float(np.median(lat))
+    p50_1q = float(np.median(lat)) if lat else None
 
     result = {
         "metric": "IVF-PQ queries/sec + scanned-code HBM GB/s at nprobe; p50 1-query latency",
@@ -153,9 +205,18 @@ def main():
         "stage_ms": {n: float(v) for n, v in zip(pkg.STAGE_NAMES, stage_ms)},
         "build_s": {k: round(info[k], 2) for k in ("train_s", "encode_s", "finalize_s")},
         "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(cfg.name),
                      "bytes_per_launch": scanned_bytes, "avg_launch_ms": scan_ms},
     }
+
+    if args.calibrate_copy:
+        from workload import gen_gpu
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            gen_gpu.plain_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the CPU oracle on this machine's host cores, same index, same queries --------------------
     if not args.no_cpu_baseline:

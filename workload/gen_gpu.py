@@ -34,6 +34,8 @@ def _load():
         _lib.workload_gen_rows.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                            C.c_int32, C.c_void_p, C.c_void_p]
         _lib.workload_gen_rows.restype = C.c_int
+        _lib.workload_plain_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib.workload_plain_copy.restype = C.c_int
     return _lib
 
 
@@ -62,3 +64,12 @@ class DeviceGenerator:
 
     def queries(self, nq: int, start: int = 0) -> torch.Tensor:
         return self.rows(gen.QUERY_ROW0 + start, nq)
+
+
+def plain_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Launches the plain copy kernel (profiling calibration: its HBM traffic is 2 * nbytes by construction)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and nbytes % 16 == 0
+    rc = _load().workload_plain_copy(src.data_ptr(), dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"workload_plain_copy failed with hipError {rc}")

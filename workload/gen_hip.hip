@@ -70,3 +70,16 @@ int workload_gen_rows(uint64_t seed, uint64_t row0, int64_t count, int32_t d, fl
 }
 
 }  // extern "C"
+
+// ---- calibration helper for profiling: a plain copy kernel of known size (no part of any workload) ----
+namespace {
+__global__ __launch_bounds__(256) void plain_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+}  // namespace
+
+extern "C" int workload_plain_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream) {
+    hipLaunchKernelGGL(plain_copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src_dev, (uint4 *)dst_dev,
+                       bytes / 16);
+    return (int)hipGetLastError();
+}
