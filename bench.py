@@ -61,19 +61,24 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
                    "coarse": coarse, "pq": pq}
 
 
-def host_copy(ix, coarse, pq):
-    """The GPU-built index in the oracle's canonical form (read back list by list through the C ABI)."""
+def host_copy(ix, coarse, pq, lists=None):
+    """The GPU-built index in the oracle's canonical form, read back list by list through the C ABI.  With
+    `lists` given, only those lists are fetched and every other list is left empty (enough for an oracle
+    search that probes only them)."""
     import oracle
     lens = ix.ivf_list_lengths()
+    if lists is not None:
+        keep = np.zeros(ix.nlist, dtype=bool)
+        keep[np.asarray(lists, dtype=np.int64)] = True
+        lens = np.where(keep, lens, 0)
     off = np.zeros(ix.nlist + 1, dtype=np.int64)
     np.cumsum(lens, out=off[1:])
     codes = np.empty((int(off[-1]), ix.M), dtype=np.uint8)
     ids = np.empty(int(off[-1]), dtype=np.int64)
-    for l in range(ix.nlist):
-        if lens[l]:
-            c, i = ix.ivf_get_list(l)
-            codes[off[l]:off[l + 1]] = c
-            ids[off[l]:off[l + 1]] = i
+    for l in np.nonzero(lens)[0]:
+        c, i = ix.ivf_get_list(int(l))
+        codes[off[l]:off[l + 1]] = c
+        ids[off[l]:off[l + 1]] = i
     return oracle.Index(coarse, pq, off, codes, ids)
 
 
@@ -126,7 +131,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -224,8 +229,11 @@ def main():
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         import parity
         coarse_h, pq_h = info["coarse"].cpu().numpy(), info["pq"].cpu().numpy()
-        hidx = host_copy(ix, coarse_h, pq_h)
         qh = q.cpu().numpy()
+        gl0, _ = ix.ivf_coarse(q, cfg.nprobe)
+        torch.cuda.synchronize()
+        needed = np.union1d(gl0.cpu().numpy().ravel(), oracle.coarse_search(qh, coarse_h, cfg.nprobe)[0].ravel())
+        hidx = host_copy(ix, coarse_h, pq_h, lists=needed)   # only the lists either side probes
         oracle.search(hidx, qh, cfg.nprobe, cfg.k)            # warm-up
         times = []
         t_budget = time.time()

@@ -25,6 +25,7 @@ constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
+void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);   // squared row norms
 
 #define PR_CHECK_HIP(expr)                                                                     \
     do {                                                                                       \
@@ -60,6 +61,7 @@ struct piperag_index {
     int dsub, Mp, device;
     // trained parameters (device)
     float *centroids;  // [nlist*d]
+    float *cnorm;      // [nlist] squared norms of the centres
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize
@@ -82,6 +84,7 @@ struct piperag_index {
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
     int32_t *ws_wgq;      // [2*kTargetScanWGs+max_nq] query of each scan workgroup
+    float *ws_qn;         // [max_nq] squared norms of the queries
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
     uint64_t *ws_part;    // [(2*kTargetScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results

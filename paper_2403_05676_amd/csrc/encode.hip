@@ -5,12 +5,14 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "mfma_tile.h"
 
 using namespace piperag;
 
 namespace piperag {
 int check_can_add(piperag_index *ix, int64_t n);
 int append_ids(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStream_t st);
+void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);
 }  // namespace piperag
 
 namespace {
@@ -152,17 +154,111 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
     for (int i = tid; i < rows * M; i += 256) dst[i] = code_s[i];
 }
 
+// Squared norms of the rows of a matrix: one wavefront per row.
+__global__ __launch_bounds__(256) void rownorm_kernel(const float *__restrict__ a, int64_t n, int d, int64_t lda,
+                                                      float *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    float acc = 0.f;
+    for (int t = lane; t < d; t += 64) { const float v = a[row * lda + t]; acc += v * v; }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) out[row] = acc;
+}
+
+// Nearest-centre assignment on the matrix cores: |x - c|^2 = |x|^2 + |c|^2 - 2 <x, c>, and |x|^2 does not
+// change the argmin, so a workgroup takes 128 rows of x, walks over the centres 128 at a time with the fp32
+// MFMA tile product and keeps, per row, the smallest |c|^2 - 2 <x, c> and its centre (lower index on equal
+// values).  Requires d % 4 == 0 and 16-byte aligned rows.
+using AssignTile = MfmaTile<2, 2, 2, 2>;
+
+__global__ __launch_bounds__(256) void assign_mfma_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
+                                                          const float *__restrict__ cent, const float *__restrict__ cnorm,
+                                                          int K, int32_t *__restrict__ out_idx, float *__restrict__ out_dist) {
+    __shared__ __align__(16) float s_mem[AssignTile::kLdsFloats];
+    const int tid = threadIdx.x, lane = tid & 63, wc = (tid >> 6) % 2;
+    const int64_t row0 = (int64_t)blockIdx.x * AssignTile::kRowsA;
+    float best_v[2][16];
+    int best_j[2][16];
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { best_v[bi][r] = __builtin_inff(); best_j[bi][r] = 0; }
+
+    for (int j0 = 0; j0 < K; j0 += AssignTile::kRowsB) {
+        mfma_acc_t acc[2][2];
+        AssignTile::run(x, n, ldx, row0, cent, K, d, j0, d, s_mem, acc);
+        const int c0 = j0 + AssignTile::acc_col(0), c1 = j0 + AssignTile::acc_col(1);
+        const float n0 = c0 < K ? cnorm[c0] : __builtin_inff(), n1 = c1 < K ? cnorm[c1] : __builtin_inff();
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v0 = n0 - 2.f * acc[bi][0][r], v1 = n1 - 2.f * acc[bi][1][r];
+                float v = v0;
+                int c = c0;
+                if (v1 < v0) { v = v1; c = c1; }
+#pragma unroll
+                for (int off = 1; off < 32; off <<= 1) {      // over the 32 lanes (columns) of this half-wave
+                    const float ov = __shfl_xor(v, off, 64);
+                    const int oc = __shfl_xor(c, off, 64);
+                    if (ov < v || (ov == v && oc < c)) { v = ov; c = oc; }
+                }
+                if (v < best_v[bi][r]) { best_v[bi][r] = v; best_j[bi][r] = c; }
+            }
+    }
+    // the two waves that share these rows (column halves wc = 0, 1) meet in LDS
+    __syncthreads();
+    float *s_v = s_mem;
+    int *s_j = reinterpret_cast<int *>(s_mem + 2 * AssignTile::kRowsA);
+    if ((lane & 31) == 0) {
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = AssignTile::acc_row(bi, r);
+                s_v[row * 2 + wc] = best_v[bi][r];
+                s_j[row * 2 + wc] = best_j[bi][r];
+            }
+    }
+    __syncthreads();
+    if (tid < AssignTile::kRowsA && row0 + tid < n) {
+        float v = s_v[tid * 2];
+        int j = s_j[tid * 2];
+        if (s_v[tid * 2 + 1] < v) { v = s_v[tid * 2 + 1]; j = s_j[tid * 2 + 1]; }   // equal values: the lower half holds the lower index
+        out_idx[row0 + tid] = j;
+        if (out_dist) {
+            float xn = 0.f;
+            const float *xr = x + (row0 + tid) * ldx;
+            for (int t = 0; t < d; ++t) xn += xr[t] * xr[t];
+            out_dist[row0 + tid] = fmaxf(0.f, v + xn);
+        }
+    }
+}
+
 // rows of x (stride ldx floats) against K centres; 16-byte loads only when every row start is 16-byte aligned
-void launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, int K, int32_t *out_idx, float *out_dist,
-                   hipStream_t st) {
+// cnorm: squared norms of the centres (f32 [K]) or NULL.  The matrix-core path is taken when the shape pays for
+// it and allows 16-byte loads; otherwise the direct-form VALU kernel runs.
+void launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, const float *cnorm, int K,
+                   int32_t *out_idx, float *out_dist, hipStream_t st) {
     const int vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(cent) % 16 == 0);
+    const bool mfma = vec4 && cnorm != nullptr && K >= 128 && d >= 64;
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
-        hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent, K,
-                           out_idx + a, out_dist ? out_dist + a : nullptr, vec4);
+        if (mfma)
+            hipLaunchKernelGGL(assign_mfma_kernel, dim3((unsigned)((cnt + AssignTile::kRowsA - 1) / AssignTile::kRowsA)), dim3(256), 0,
+                               st, x + a * ldx, cnt, d, ldx, cent, cnorm, K, out_idx + a, out_dist ? out_dist + a : nullptr);
+        else
+            hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
+                               K, out_idx + a, out_dist ? out_dist + a : nullptr, vec4);
     }
+}
+
+void launch_rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) {
+    hipLaunchKernelGGL(rownorm_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, a, n, d, lda, out);
 }
 
 // ---- k-means training ------------------------------------------------------------------------
@@ -197,10 +293,18 @@ __global__ void zero_kernel(unsigned long long *__restrict__ p, int64_t n) {
     if (i < n) p[i] = 0ull;
 }
 
+}  // namespace
+
+namespace piperag {
+void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) { launch_rownorm(a, n, d, lda, out, st); }
+}  // namespace piperag
+
+namespace {
+
 int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
     const piperag_params &p = ix->p;
     PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
-    if (out_lists) launch_assign(x, n, p.d, p.d, ix->centroids, p.nlist, out_lists, nullptr, st);
+    if (out_lists) launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, p.nlist, out_lists, nullptr, st);
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
@@ -247,9 +351,10 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     float *adist = nullptr;
     long long *sum = nullptr;
     int *count = nullptr;
+    float *cnorm = nullptr;
     float *hdist = inertia_out_host ? (float *)malloc(sizeof(float) * (size_t)n) : nullptr;
     auto done = [&](int code) {
-        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count);
+        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count); (void)hipFree(cnorm);
         free(hdist);
         return code;
     };
@@ -257,7 +362,7 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     if (hipMalloc((void **)&rows, sizeof(int64_t) * K) != hipSuccess || hipMalloc((void **)&assign, sizeof(int32_t) * n) != hipSuccess ||
         hipMalloc((void **)&adist, sizeof(float) * n) != hipSuccess ||
         hipMalloc((void **)&sum, sizeof(long long) * (size_t)K * d) != hipSuccess ||
-        hipMalloc((void **)&count, sizeof(int) * (K + 1)) != hipSuccess) {
+        hipMalloc((void **)&count, sizeof(int) * (K + 1)) != hipSuccess || hipMalloc((void **)&cnorm, sizeof(float) * K) != hipSuccess) {
         set_error("out of device memory in piperag_kmeans");
         return done(PIPERAG_ERR_OOM);
     }
@@ -267,7 +372,8 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     hipLaunchKernelGGL(gather_rows_kernel, dim3(K), dim3(256), 0, st, x_dev, ldx, d, rows, centroids_out_dev);
     const int64_t nsum = (int64_t)K * d;
     for (int it = 0; it < iters; ++it) {
-        launch_assign(x_dev, n, d, ldx, centroids_out_dev, K, assign, adist, st);
+        launch_rownorm(centroids_out_dev, K, d, d, cnorm, st);
+        launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, K, assign, adist, st);
         hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, (unsigned long long *)sum, nsum);
         hipLaunchKernelGGL(zero_kernel, dim3((K / 2 + 256) / 256), dim3(256), 0, st, (unsigned long long *)count, (int64_t)(K + 1) / 2);
         hipLaunchKernelGGL(kmeans_accum_kernel, dim3((unsigned)n), dim3(d >= 256 ? 256 : 64), 0, st, x_dev, ldx, d, assign, sum, count);

@@ -216,7 +216,8 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_wgq, 2 * (size_t)kTargetScanWGs + p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
         (rc = dev_alloc(&ix->ws_part, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
-        (rc = dev_alloc(&ix->pqT, npq)) ||
+        (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
+        (rc = dev_alloc(&ix->ws_qn, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
         return fail(rc);
@@ -225,6 +226,8 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         set_error("upload of trained parameters failed");
         return fail(PIPERAG_ERR_HIP);
     }
+    rownorm(ix->centroids, p.nlist, p.d, p.d, ix->cnorm, nullptr);
+    if (hipStreamSynchronize(nullptr) != hipSuccess) { set_error("centre norms failed"); return fail(PIPERAG_ERR_HIP); }
     {   // centre-major copy of the codebook
         std::vector<float> t(npq);
         for (int m = 0; m < p.M; ++m)
@@ -279,7 +282,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
-    void *ptrs[] = {ix->centroids, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
+    void *ptrs[] = {ix->centroids, ix->cnorm, ix->ws_qn, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
                     ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_wgq, ix->ws_lut, ix->ws_part, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)

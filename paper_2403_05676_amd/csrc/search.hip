@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "common.h"
+#include "mfma_tile.h"
 
 using namespace piperag;
 
@@ -169,6 +170,28 @@ __global__ __launch_bounds__(256) void coarse_rowwise_kernel(const float *__rest
             const float s = wave_sum(acc[qi]);
             if (lane == 0 && qi < nqt) D[(size_t)(q0 + qi) * nlist + j] = s;
         }
+    }
+}
+
+// Coarse distances on the matrix cores for batches: D[q][j] = |q|^2 + |c_j|^2 - 2 <q, c_j> (clamped at 0), a
+// 64-query x 64-centre tile per workgroup with the fp32 MFMA tile product.  The lanes of a half-wave hold 32
+// consecutive centres of one query, so the rows of D are written in contiguous runs.  Requires d % 4 == 0
+// and 16-byte aligned rows.  grid = (ceil(nlist / 64), ceil(nq / 64)).
+using CoarseTile = MfmaTile<2, 2, 1, 1, 32>;
+
+__global__ __launch_bounds__(256) void coarse_mfma_kernel(const float *__restrict__ q, int nq, const float *__restrict__ qn,
+                                                          const float *__restrict__ cent, const float *__restrict__ cn,
+                                                          int nlist, int d, float *__restrict__ D) {
+    __shared__ __align__(16) float s_mem[CoarseTile::kLdsFloats];
+    const int64_t c0 = (int64_t)blockIdx.x * CoarseTile::kRowsB, q0 = (int64_t)blockIdx.y * CoarseTile::kRowsA;
+    mfma_acc_t acc[1][1];
+    CoarseTile::run(q, nq, d, q0, cent, nlist, d, c0, d, s_mem, acc);
+    const int64_t col = c0 + CoarseTile::acc_col(0);
+    const float cnv = col < nlist ? cn[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int64_t row = q0 + CoarseTile::acc_row(0, r);
+        if (row < nq && col < nlist) D[row * nlist + col] = fmaxf(0.f, qn[row] + cnv - 2.f * acc[0][0][r]);
     }
 }
 
@@ -978,6 +1001,13 @@ int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
 int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
     constexpr int QT = 4;
     const int d = ix->p.d, nlist = ix->p.nlist;
+    if (nq > QT && d % 4 == 0 && d >= 64 && reinterpret_cast<uintptr_t>(q) % 16 == 0) {     // batches: matrix cores
+        rownorm(q, nq, d, d, ix->ws_qn, st);
+        hipLaunchKernelGGL(coarse_mfma_kernel, dim3((nlist + CoarseTile::kRowsB - 1) / CoarseTile::kRowsB,
+                                                    (nq + CoarseTile::kRowsA - 1) / CoarseTile::kRowsA),
+                           dim3(256), 0, st, q, nq, ix->ws_qn, ix->centroids, ix->cnorm, nlist, d, ix->ws_D);
+        return PIPERAG_OK;
+    }
     const int groups = std::min((nlist + 3) / 4, 2048);
     const dim3 grid(groups, (nq + QT - 1) / QT);
     const size_t lds = sizeof(float) * QT * d;

@@ -1,0 +1,99 @@
+"""Benchmark configurations at full size, in the launch configuration bench.py times: the index is trained
+and encoded on the GPU, a slice of the encoder output is checked against the oracle, the structure of the
+whole index is checked by invariants, and the oracle searches a host copy of the probed lists.
+
+cfg1 runs by default.  cfg2-cfg4 take minutes to build and are enabled with PIPERAG_LARGE=cfg2,cfg3,..."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import parity
+from workload import gen
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+LARGE = set(filter(None, os.environ.get("PIPERAG_LARGE", "").split(",")))
+
+
+def run_config(name, slice_rows, batches):
+    import paper_2403_05676_amd as pkg
+    import bench
+    pkg.load_library()
+    cfg = gen.CONFIGS[name]
+    t0 = time.time()
+    max_nq = max(nq for nq, _ in batches)
+    max_np = max(npr for _, npr in batches)
+    ix, g, info = bench.build_index(pkg, cfg, torch, max_nq=max_nq, max_nprobe=max_np, max_k=cfg.k)
+    print(f"\n[{name}] built in {time.time() - t0:.1f}s (train {info['train_s']:.1f} encode {info['encode_s']:.1f} "
+          f"finalize {info['finalize_s']:.1f})", flush=True)
+    coarse, pq = info["coarse"].cpu().numpy(), info["pq"].cpu().numpy()
+    # ---- structure of the whole index
+    lens = ix.ivf_list_lengths()
+    assert ix.ivf_ntotal() == cfg.N and lens.sum() == cfg.N and lens.min() >= 0
+    # ---- encoder against the oracle on a slice in the middle of the database
+    row0 = (cfg.N // 2) // 64 * 64 + 17
+    xs = g.database(row0, slice_rows)
+    gl, gc = ix.ivf_encode(xs)
+    torch.cuda.synchronize()
+    xh = xs.cpu().numpy()
+    assert np.array_equal(xh, gen.database(cfg, row0, slice_rows))        # device generator == numpy generator
+    nl, nc = parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), xh, coarse, pq)
+    print(f"[{name}] encode slice of {slice_rows}: {nl} list / {nc} code-byte differences, all at ties", flush=True)
+    assert nl <= max(2, slice_rows // 200) and nc <= slice_rows * cfg.M // 200
+    # the slice's vectors sit in the lists the encoder chose, with those codes
+    gl_h, gc_h = gl.cpu().numpy(), gc.cpu().numpy()
+    for l in np.unique(gl_h)[:8]:
+        codes, ids = ix.ivf_get_list(int(l))
+        assert np.all(np.diff(ids) > 0)
+        sel = np.nonzero(gl_h == l)[0]
+        pos = np.searchsorted(ids, row0 + sel)
+        assert np.array_equal(ids[pos], row0 + sel) and np.array_equal(codes[pos], gc_h[sel])
+    # ---- search against the oracle on a host copy of the probed lists
+    for nq, nprobe in batches:
+        q = g.queries(nq)
+        qh = q.cpu().numpy()
+        probes, pd = ix.ivf_coarse(q, nprobe)
+        od, oi = ix.ivfpq_search(q, nprobe, cfg.k)
+        torch.cuda.synchronize()
+        probes = probes.cpu().numpy()
+        ex_p = parity.check_probes(probes, pd.cpu().numpy(), qh, coarse, nprobe)
+        hidx = bench.host_copy(ix, coarse, pq, lists=np.unique(probes))
+        ex_k, rel = parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), hidx, qh, probes, cfg.k)
+        scanned, nbytes = ix.search_stats()
+        assert scanned == int(lens[probes].sum())
+        # throughput of this launch configuration (scan stage, HIP events)
+        ix.set_stage_timing(True)
+        ts = []
+        for _ in range(10):
+            ix.ivfpq_search(q, nprobe, cfg.k)
+            ts.append(ix.stage_times().copy())
+        ix.set_stage_timing(False)
+        t = np.median(np.array(ts), axis=0)
+        print(f"[{name}] nq={nq} nprobe={nprobe}: probe ties {ex_p}, top-k ties {ex_k}, max rel err {rel:.1e}; "
+              f"scanned {scanned} vectors; stages us {np.round(t * 1e3, 1)}; scan {nbytes / t[3] / 1e6:.0f} GB/s "
+              f"({nbytes / t[3] / 1e6 / 80:.1f}% of HBM peak); {nq / t.sum() * 1e3:.0f} queries/s", flush=True)
+        assert rel < 1e-4
+    return ix
+
+
+def test_cfg1_full_size():
+    run_config("cfg1", 4096, [(64, 32), (1, 32)])
+
+
+@pytest.mark.skipif("cfg2" not in LARGE, reason="set PIPERAG_LARGE=cfg2 (builds 16.8 M vectors)")
+def test_cfg2_full_size():
+    run_config("cfg2", 4096, [(1, 1), (1, 32), (1, 256), (8, 1), (8, 64), (8, 256)])
+
+
+@pytest.mark.skipif("cfg3" not in LARGE, reason="set PIPERAG_LARGE=cfg3 (builds 268 M vectors, minutes)")
+def test_cfg3_full_size():
+    run_config("cfg3", 8192, [(64, 64)])
+
+
+@pytest.mark.skipif("cfg4" not in LARGE, reason="set PIPERAG_LARGE=cfg4 (builds 1.07 G vectors, tens of minutes)")
+def test_cfg4_full_size():
+    run_config("cfg4", 8192, [(1, 128), (16, 128), (256, 128)])
