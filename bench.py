@@ -36,6 +36,8 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
     sample = g.database(0, cfg.train_sample)
     init_c = gen.draw_distinct_rows(cfg.train_sample, cfg.nlist, cfg.seed)
     coarse = pkg.kmeans(sample, cfg.nlist, init_c, cfg.kmeans_iters)
+    torch.cuda.synchronize()
+    log(f"[build] coarse centres trained, {time.time() - t0:.0f}s")
     pq = torch.empty((cfg.M, 256, cfg.dsub), dtype=torch.float32, device="cuda")
     for m in range(cfg.M):
         init_m = gen.draw_distinct_rows(cfg.train_sample, 256, cfg.seed + 1 + m)
@@ -47,10 +49,16 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
                               max_nprobe=max_nprobe or cfg.nprobe, max_k=max_k or cfg.k)
     t0 = time.time()
     buf = torch.empty((min(tile_rows, cfg.N), cfg.d), dtype=torch.float32, device="cuda")
-    for a in range(0, cfg.N, tile_rows):
+    t_log = time.time()
+    for it, a in enumerate(range(0, cfg.N, tile_rows)):
         n = min(tile_rows, cfg.N - a)
         x = g.database(a, n, out=buf)
         ix.ivf_add(x[:n])
+        if it % 4 == 3:                                 # keep the launch queue short, so progress can be reported
+            torch.cuda.synchronize()
+            if time.time() - t_log > 20:
+                log(f"[build] encoded {a + n} of {cfg.N} vectors, {time.time() - t0:.0f}s")
+                t_log = time.time()
     torch.cuda.synchronize()
     t_encode = time.time() - t0
     del buf

@@ -26,6 +26,7 @@ constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);   // squared row norms
+void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st);   // bf16 hi / lo parts
 
 #define PR_CHECK_HIP(expr)                                                                     \
     do {                                                                                       \
@@ -62,6 +63,7 @@ struct piperag_index {
     // trained parameters (device)
     float *centroids;  // [nlist*d]
     float *cnorm;      // [nlist] squared norms of the centres
+    uint16_t *cent_hi, *cent_lo;   // [nlist*d] bf16 split of the centres for the encoder (NULL when the shape rules it out)
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize
@@ -76,6 +78,9 @@ struct piperag_index {
     int64_t *ids;       // [nblocks*64]
     int32_t *list_blk;  // [nlist+1] first block of each list
     int32_t *list_len;  // [nlist]
+    int64_t max_list_len;
+    uint8_t *rb_codes;  // read-back scratch for piperag_ivf_get_list (allocated on first use)
+    int64_t *rb_ids;
     // search workspace
     float *ws_D;          // [max_nq*nlist]
     int32_t *ws_probe;    // [max_nq*max_nprobe]

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "mfma_bf16x3.h"
 #include "mfma_tile.h"
 
 using namespace piperag;
@@ -13,6 +14,7 @@ namespace piperag {
 int check_can_add(piperag_index *ix, int64_t n);
 int append_ids(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStream_t st);
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);
+void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st);
 }  // namespace piperag
 
 namespace {
@@ -238,23 +240,118 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const float *__restric
 }
 
 // rows of x (stride ldx floats) against K centres; 16-byte loads only when every row start is 16-byte aligned
+// bf16 hi / lo parts of an fp32 array (see mfma_bf16x3.h).
+__global__ void split_bf16_kernel(const float *__restrict__ src, int64_t n, uint16_t *__restrict__ hi, uint16_t *__restrict__ lo) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float v = src[i];
+    const __bf16 h = (__bf16)v;
+    const __bf16 l = (__bf16)(v - (float)h);
+    hi[i] = __builtin_bit_cast(uint16_t, h);
+    lo[i] = __builtin_bit_cast(uint16_t, l);
+}
+
+// Nearest-centre assignment with the split-bf16 tile product: 256 rows of x per workgroup against the centres
+// 128 at a time; per row the smallest |c|^2 - 2 <x, c> and its centre (lower index on equal values) are
+// kept in LDS by the lane that owns the row in each of the two column halves.  d % 8 == 0, 16-byte aligned rows.
+__global__ __launch_bounds__(256) void assign_bf16x3_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
+                                                            const uint16_t *__restrict__ chi, const uint16_t *__restrict__ clo,
+                                                            const float *__restrict__ cnorm, int K,
+                                                            int32_t *__restrict__ out_idx, float *__restrict__ out_dist) {
+    extern __shared__ __align__(16) unsigned char bsmem[];
+    float *s_bv = reinterpret_cast<float *>(bsmem + Bf16x3Tile::kLdsBytes);       // [256 rows][2 column halves]
+    int *s_bj = reinterpret_cast<int *>(s_bv + 2 * Bf16x3Tile::kRowsA);
+    const int tid = threadIdx.x, lane = tid & 63, wc = (tid >> 6) & 1;
+    const bool owner = (lane & 31) == 0;
+    const int64_t row0 = (int64_t)blockIdx.x * Bf16x3Tile::kRowsA;
+    if (owner) {
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = Bf16x3Tile::acc_row(bi, r);
+                s_bv[row * 2 + wc] = __builtin_inff();
+                s_bj[row * 2 + wc] = 0;
+            }
+    }
+    for (int j0 = 0; j0 < K; j0 += Bf16x3Tile::kRowsB) {
+        acc16_t acc[4][2];
+        Bf16x3Tile::run(x, n, ldx, row0, chi, clo, K, d, j0, d, bsmem, acc);
+        const int c0 = j0 + Bf16x3Tile::acc_col(0), c1 = j0 + Bf16x3Tile::acc_col(1);
+        const float n0 = c0 < K ? cnorm[c0] : __builtin_inff(), n1 = c1 < K ? cnorm[c1] : __builtin_inff();
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v0 = n0 - 2.f * acc[bi][0][r], v1 = n1 - 2.f * acc[bi][1][r];
+                float v = v0;
+                int c = c0;
+                if (v1 < v0) { v = v1; c = c1; }
+#pragma unroll
+                for (int off = 1; off < 32; off <<= 1) {      // over the 32 lanes (columns) of this half-wave
+                    const float ov = __shfl_xor(v, off, 64);
+                    const int oc = __shfl_xor(c, off, 64);
+                    if (ov < v || (ov == v && oc < c)) { v = ov; c = oc; }
+                }
+                if (owner) {
+                    const int row = Bf16x3Tile::acc_row(bi, r);
+                    if (v < s_bv[row * 2 + wc]) { s_bv[row * 2 + wc] = v; s_bj[row * 2 + wc] = c; }
+                }
+            }
+    }
+    __syncthreads();
+    if (row0 + tid < n) {                 // 256 threads, 256 rows
+        float v = s_bv[tid * 2];
+        int j = s_bj[tid * 2];
+        if (s_bv[tid * 2 + 1] < v) { v = s_bv[tid * 2 + 1]; j = s_bj[tid * 2 + 1]; }   // equal values: the lower half holds the lower index
+        out_idx[row0 + tid] = j;
+        if (out_dist) {
+            float xn = 0.f;
+            const float *xr = x + (row0 + tid) * ldx;
+            for (int t = 0; t < d; ++t) xn += xr[t] * xr[t];
+            out_dist[row0 + tid] = fmaxf(0.f, v + xn);
+        }
+    }
+}
+
 // cnorm: squared norms of the centres (f32 [K]) or NULL.  The matrix-core path is taken when the shape pays for
 // it and allows 16-byte loads; otherwise the direct-form VALU kernel runs.
-void launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, const float *cnorm, int K,
-                   int32_t *out_idx, float *out_dist, hipStream_t st) {
+// chi / clo: bf16 split of the centres (u16 [K*d] each) or NULL.  The matrix-core paths are taken when the shape
+// pays for them and allows 16-byte loads: split-bf16 first, fp32 MFMA second; otherwise the direct-form VALU
+// kernel runs.
+int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, const float *cnorm, const uint16_t *chi,
+                  const uint16_t *clo, int K, int32_t *out_idx, float *out_dist, hipStream_t st) {
     const int vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(cent) % 16 == 0);
     const bool mfma = vec4 && cnorm != nullptr && K >= 128 && d >= 64;
+    const bool bf16 = mfma && chi != nullptr && clo != nullptr && d % 8 == 0;
+    constexpr size_t kBfLds = Bf16x3Tile::kLdsBytes + 4 * sizeof(float) * Bf16x3Tile::kRowsA;
+    if (bf16) {
+        static bool configured = false;
+        if (!configured) {
+            PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_bf16x3_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBfLds));
+            configured = true;
+        }
+    }
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
-        if (mfma)
+        if (bf16)
+            hipLaunchKernelGGL(assign_bf16x3_kernel, dim3((unsigned)((cnt + Bf16x3Tile::kRowsA - 1) / Bf16x3Tile::kRowsA)), dim3(256),
+                               kBfLds, st, x + a * ldx, cnt, d, ldx, chi, clo, cnorm, K, out_idx + a, out_dist ? out_dist + a : nullptr);
+        else if (mfma)
             hipLaunchKernelGGL(assign_mfma_kernel, dim3((unsigned)((cnt + AssignTile::kRowsA - 1) / AssignTile::kRowsA)), dim3(256), 0,
                                st, x + a * ldx, cnt, d, ldx, cent, cnorm, K, out_idx + a, out_dist ? out_dist + a : nullptr);
         else
             hipLaunchKernelGGL(assign_kernel, dim3((unsigned)((cnt + TM - 1) / TM)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
                                K, out_idx + a, out_dist ? out_dist + a : nullptr, vec4);
     }
+    return PIPERAG_OK;
+}
+
+void launch_split(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st) {
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, n, hi, lo);
 }
 
 void launch_rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) {
@@ -297,6 +394,7 @@ __global__ void zero_kernel(unsigned long long *__restrict__ p, int64_t n) {
 
 namespace piperag {
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) { launch_rownorm(a, n, d, lda, out, st); }
+void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st) { launch_split(src, n, hi, lo, st); }
 }  // namespace piperag
 
 namespace {
@@ -304,7 +402,10 @@ namespace {
 int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
     const piperag_params &p = ix->p;
     PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
-    if (out_lists) launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, p.nlist, out_lists, nullptr, st);
+    if (out_lists) {
+        const int rc = launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, p.nlist, out_lists, nullptr, st);
+        if (rc != PIPERAG_OK) return rc;
+    }
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
@@ -352,9 +453,10 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     long long *sum = nullptr;
     int *count = nullptr;
     float *cnorm = nullptr;
+    uint16_t *chi = nullptr, *clo = nullptr;
     float *hdist = inertia_out_host ? (float *)malloc(sizeof(float) * (size_t)n) : nullptr;
     auto done = [&](int code) {
-        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count); (void)hipFree(cnorm);
+        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count); (void)hipFree(cnorm); (void)hipFree(chi); (void)hipFree(clo);
         free(hdist);
         return code;
     };
@@ -366,6 +468,12 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
         set_error("out of device memory in piperag_kmeans");
         return done(PIPERAG_ERR_OOM);
     }
+    const bool use_split = K >= 128 && d >= 64 && d % 8 == 0;
+    if (use_split && (hipMalloc((void **)&chi, sizeof(uint16_t) * (size_t)K * d) != hipSuccess ||
+                      hipMalloc((void **)&clo, sizeof(uint16_t) * (size_t)K * d) != hipSuccess)) {
+        set_error("out of device memory in piperag_kmeans");
+        return done(PIPERAG_ERR_OOM);
+    }
     hipError_t e = hipMemcpyAsync(rows, init_rows_host, sizeof(int64_t) * K, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) { set_error("upload failed: %s", hipGetErrorString(e)); return done(PIPERAG_ERR_HIP); }
@@ -373,7 +481,9 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     const int64_t nsum = (int64_t)K * d;
     for (int it = 0; it < iters; ++it) {
         launch_rownorm(centroids_out_dev, K, d, d, cnorm, st);
-        launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, K, assign, adist, st);
+        if (use_split) launch_split(centroids_out_dev, (int64_t)K * d, chi, clo, st);
+        const int rca = launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, chi, clo, K, assign, adist, st);
+        if (rca != PIPERAG_OK) return done(rca);
         hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, (unsigned long long *)sum, nsum);
         hipLaunchKernelGGL(zero_kernel, dim3((K / 2 + 256) / 256), dim3(256), 0, st, (unsigned long long *)count, (int64_t)(K + 1) / 2);
         hipLaunchKernelGGL(kmeans_accum_kernel, dim3((unsigned)n), dim3(d >= 256 ? 256 : 64), 0, st, x_dev, ldx, d, assign, sum, count);

@@ -226,6 +226,10 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         set_error("upload of trained parameters failed");
         return fail(PIPERAG_ERR_HIP);
     }
+    if (p.nlist >= 128 && p.d >= 64 && p.d % 8 == 0) {
+        if ((rc = dev_alloc(&ix->cent_hi, ncent)) || (rc = dev_alloc(&ix->cent_lo, ncent))) return fail(rc);
+        split_bf16(ix->centroids, (int64_t)ncent, ix->cent_hi, ix->cent_lo, nullptr);
+    }
     rownorm(ix->centroids, p.nlist, p.d, p.d, ix->cnorm, nullptr);
     if (hipStreamSynchronize(nullptr) != hipSuccess) { set_error("centre norms failed"); return fail(PIPERAG_ERR_HIP); }
     {   // centre-major copy of the codebook
@@ -282,7 +286,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
-    void *ptrs[] = {ix->centroids, ix->cnorm, ix->ws_qn, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
+    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
                     ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_wgq, ix->ws_lut, ix->ws_part, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
@@ -356,6 +360,15 @@ int piperag_ivf_finalize(piperag_index *ix, void *stream) {
     e = hipStreamSynchronize(st);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) { set_error("finalize (placement) failed: %s", hipGetErrorString(e)); return cleanup(PIPERAG_ERR_HIP); }
+    {
+        std::vector<int32_t> hl(nlist);
+        if (hipMemcpy(hl.data(), ix->list_len, sizeof(int32_t) * nlist, hipMemcpyDeviceToHost) != hipSuccess) {
+            set_error("finalize (list lengths) failed");
+            return cleanup(PIPERAG_ERR_HIP);
+        }
+        ix->max_list_len = 0;
+        for (int32_t v : hl) ix->max_list_len = std::max<int64_t>(ix->max_list_len, v);
+    }
     free_staging(ix);
     ix->ntotal = n;
     ix->finalized = true;
@@ -381,25 +394,24 @@ int piperag_ivf_get_list(const piperag_index *ix, int32_t list, int64_t *len_out
     PR_CHECK_HIP(hipMemcpy(&blk, ix->list_blk + list, sizeof(int32_t), hipMemcpyDeviceToHost));
     if (len_out) *len_out = len;
     if (len == 0 || (!codes_host && !ids_host)) return PIPERAG_OK;
-    uint8_t *dc = nullptr;
-    int64_t *di = nullptr;
-    int rc = PIPERAG_OK;
-    hipError_t e = hipSuccess;
-    if (codes_host) e = hipMalloc(reinterpret_cast<void **>(&dc), (size_t)len * ix->p.M);
-    if (e == hipSuccess && ids_host) e = hipMalloc(reinterpret_cast<void **>(&di), (size_t)len * sizeof(int64_t));
-    if (e == hipSuccess) {
-        hipLaunchKernelGGL(gather_list_kernel, dim3((len + 255) / 256), dim3(256), 0, 0, ix->codes, ix->ids,
-                           (uint32_t)blk * kBlockVecs, (int64_t)0, (int64_t)len, ix->p.M, ix->Mp, dc, di);
-        if (codes_host) e = hipMemcpy(codes_host, dc, (size_t)len * ix->p.M, hipMemcpyDeviceToHost);
-        if (e == hipSuccess && ids_host) e = hipMemcpy(ids_host, di, (size_t)len * sizeof(int64_t), hipMemcpyDeviceToHost);
+    // read-back scratch sized for the longest list, allocated on first use and kept with the index
+    piperag_index *mix = const_cast<piperag_index *>(ix);
+    if (!mix->rb_codes) {
+        const size_t cap = (size_t)std::max<int64_t>(ix->max_list_len, 1);
+        if (hipMalloc(reinterpret_cast<void **>(&mix->rb_codes), cap * ix->p.M) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void **>(&mix->rb_ids), cap * sizeof(int64_t)) != hipSuccess) {
+            (void)hipFree(mix->rb_codes); mix->rb_codes = nullptr;
+            set_error("out of device memory for the list read-back buffer");
+            return PIPERAG_ERR_OOM;
+        }
     }
-    if (e != hipSuccess) {
-        set_error("get_list failed: %s", hipGetErrorString(e));
-        rc = e == hipErrorOutOfMemory ? PIPERAG_ERR_OOM : PIPERAG_ERR_HIP;
-    }
-    (void)hipFree(dc);
-    (void)hipFree(di);
-    return rc;
+    PR_REQUIRE(len <= ix->max_list_len, PIPERAG_ERR_HIP, "list length %d exceeds the recorded maximum", len);
+    hipLaunchKernelGGL(gather_list_kernel, dim3((len + 255) / 256), dim3(256), 0, 0, ix->codes, ix->ids,
+                       (uint32_t)blk * kBlockVecs, (int64_t)0, (int64_t)len, ix->p.M, ix->Mp, codes_host ? mix->rb_codes : nullptr,
+                       ids_host ? mix->rb_ids : nullptr);
+    if (codes_host) PR_CHECK_HIP(hipMemcpy(codes_host, mix->rb_codes, (size_t)len * ix->p.M, hipMemcpyDeviceToHost));
+    if (ids_host) PR_CHECK_HIP(hipMemcpy(ids_host, mix->rb_ids, (size_t)len * sizeof(int64_t), hipMemcpyDeviceToHost));
+    return PIPERAG_OK;
 }
 
 // ---- file I/O ---------------------------------------------------------------------------------

@@ -27,23 +27,24 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Workgroup-wide selection: returns a threshold T such that exactly kth of the keys key_at(0..n-1) are <= T.
+// Workgroup-wide selection: returns a threshold T such that exactly kth of the given keys are <= T.
 // Keys equal to kSentinel are ignored; the others must be distinct and at least kth of them must exist
 // (if fewer exist, kSentinel - 1 is returned: "keep all").  blockDim is a multiple of 64, >= 64.
 // Method: bucket counting over the value range that still contains the kth key - 256 equal-width buckets
 // over [lo, hi], starting from the actual minimum and maximum, narrowed to one bucket per round - so the
 // histogram is spread over the buckets from the first round on, whatever bits the keys have in common.
-// key_at(i) is evaluated once per round.  s_hist: 256 words, s_state: 8 words of LDS.
-template <class KeyFn>
-__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state) {
+// for_each_key(f) calls f(key) for every key this thread is responsible for (the threads of the workgroup
+// together cover every key exactly once); it is run once per round, so keys may live in registers, LDS or
+// global memory.  s_hist: 256 words, s_state: 8 words of LDS.
+template <class ForEach>
+__device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigned *s_hist, unsigned long long *s_state) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     // round 0: minimum, maximum and number of valid keys
     uint64_t lo = kSentinel, hi = 0;
     unsigned cnt = 0;
-    for (int i = tid; i < n; i += nt) {
-        const uint64_t key = key_at(i);
+    for_each_key([&](uint64_t key) {
         if (key != kSentinel) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; ++cnt; }
-    }
+    });
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         const uint64_t ol = __shfl_xor(lo, off, 64), oh = __shfl_xor(hi, off, 64);
@@ -67,10 +68,9 @@ __device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_h
     for (;;) {
         const uint64_t width = hi - lo;
         const int sh = width < 256 ? 0 : (56 - __clzll((long long)width));     // (width >> sh) <= 255
-        for (int i = tid; i < n; i += nt) {
-            const uint64_t key = key_at(i);
+        for_each_key([&](uint64_t key) {
             if (key != kSentinel && key >= lo && key <= hi) atomicAdd(&s_hist[(unsigned)((key - lo) >> sh)], 1u);
-        }
+        });
         __syncthreads();
         if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
             unsigned h[4], sum = 0;
@@ -103,6 +103,15 @@ __device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_h
         if (inb == need) return hi;         // every key of this bucket is wanted: T = its upper end
         // sh == 0 means one key value per bucket, so inb == 1 == need there: the loop ends at the latest then
     }
+}
+
+// The same for keys addressed by index: key_at(i), i = 0..n-1.
+template <class KeyFn>
+__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state) {
+    auto each = [&](auto f) {
+        for (int i = threadIdx.x; i < n; i += blockDim.x) f(key_at(i));
+    };
+    return block_select_kth_each(each, kth, s_hist, s_state);
 }
 
 // In-place ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
@@ -230,26 +239,38 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
 }
 
 // Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
-// per query: selection of the nprobe-th smallest key (distance bits << 32 | list; distances are >= 0 so
-// their bit patterns order like the values), compaction, bitonic sort.
-__global__ __launch_bounds__(256) void select_probes_kernel(const float *__restrict__ D, int nlist, int nprobe,
-                                                            int32_t *__restrict__ probe, float *__restrict__ probe_d,
-                                                            int probe_stride, const int32_t *__restrict__ list_blk,
-                                                            const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx,
-                                                            int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
+// of 512 threads per query: selection of the nprobe-th smallest key (distance bits << 32 | list; distances
+// are >= 0 so their bit patterns order like the values), compaction, bitonic sort.  The row of D is staged in
+// LDS (dynamic, nlist * 4 bytes) for the rounds of the selection when it fits (stage_row != 0).
+constexpr int kSelThreads = 512;
+constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
+
+__global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float *__restrict__ D, int nlist, int nprobe,
+                                                                    int stage_row, int32_t *__restrict__ probe,
+                                                                    float *__restrict__ probe_d, int probe_stride,
+                                                                    const int32_t *__restrict__ list_blk,
+                                                                    const int32_t *__restrict__ list_len,
+                                                                    int32_t *__restrict__ pfx, int64_t *__restrict__ scanned,
+                                                                    uint32_t *__restrict__ thr) {
+    extern __shared__ __align__(16) unsigned char sel_smem[];
     __shared__ unsigned s_hist[256];
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count;
-    const int qi = blockIdx.x;
-    const float *row = D + (size_t)qi * nlist;
-    auto key_at = [&](int i) { return ((uint64_t)__float_as_uint(row[i]) << 32) | (uint32_t)i; };
-    const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
+    const int qi = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *row = reinterpret_cast<const uint32_t *>(D + (size_t)qi * nlist);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
-    for (int i = threadIdx.x; i < np2; i += blockDim.x) s_keys[i] = kSentinel;
-    if (threadIdx.x == 0) s_count = 0;
+    for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
+    if (tid == 0) s_count = 0;
+    if (stage_row) {
+        uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
+        for (int i = tid; i < nlist; i += kSelThreads) s_row[i] = row[i];
+        row = s_row;
+    }
     __syncthreads();
-    for (int i = threadIdx.x; i < nlist; i += blockDim.x) {
+    auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
+    const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
+    for (int i = tid; i < nlist; i += kSelThreads) {
         const uint64_t key = key_at(i);
         if (key <= T) {                                    // exactly nprobe keys qualify (keys are distinct)
             const unsigned slot = atomicAdd(&s_count, 1u);
@@ -258,7 +279,7 @@ __global__ __launch_bounds__(256) void select_probes_kernel(const float *__restr
     }
     __syncthreads();
     block_bitonic_sort_u64(s_keys, np2);
-    for (int i = threadIdx.x; i < nprobe; i += blockDim.x) {
+    for (int i = tid; i < nprobe; i += kSelThreads) {
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
     }
@@ -576,6 +597,7 @@ __device__ __forceinline__ void stage_probe_tables(const ScanArgs &a, const Scan
 // ------------------------------------------------------------------------------------------------
 constexpr int kLutThreads = 512;
 constexpr int kLutWaves = kLutThreads / kWave;
+static_assert(kPrimeBlocks % kLutWaves == 0, "priming blocks are shared out evenly over the waves");
 
 // One table entry: squared distance between dsub query coordinates and dsub centre coordinates.  DSUB > 0
 // fixes dsub at compile time (all loads of several entries can then be in flight together).
@@ -625,17 +647,16 @@ __global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__r
     stage_probe_tables(a, s, qi);
     for (int t = tid; t < d; t += kLutThreads) s_q[t] = q[(size_t)qi * d + t];
     __syncthreads();
-    // table: lane <-> sub-quantiser, wave <-> centre (4 centres at a time)
+    // table: lane <-> sub-quantiser, wave <-> centre (8 centres at a time, so that their loads overlap)
     for (int m = lane; m < MP; m += kWave) {
         const float *qs = s_q + m * dsub;
-        for (int j0 = wave * 4; j0 < kKsub; j0 += kLutWaves * 4) {
-            float e[4] = {0.f, 0.f, 0.f, 0.f};
-            if (m < M) {
+        for (int j0 = wave * 8; j0 < kKsub; j0 += kLutWaves * 8) {
+            float e[8];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) e[jj] = lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub);
-            }
+            for (int jj = 0; jj < 8; ++jj)
+                e[jj] = m < M ? lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub) : 0.f;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) s.lut[(j0 + jj) * MP + m] = e[jj];
+            for (int jj = 0; jj < 8; ++jj) s.lut[(j0 + jj) * MP + m] = e[jj];
         }
     }
     __syncthreads();
@@ -644,26 +665,41 @@ __global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__r
         const float4 *src = reinterpret_cast<const float4 *>(s.lut);
         for (int i = tid; i < kKsub * MP / 4; i += kLutThreads) dst[i] = src[i];
     }
-    // priming scan
+    // priming scan: every wave first requests all its blocks, then works through them
     const int TB = s.pfx[a.nprobe];
     const int nb = min(TB, kPrimeBlocks);
     const int lane_m = lane % MP;
     uint32_t off4[16];
     make_off4(off4, lane);
+    constexpr int kPerWave = kPrimeBlocks / kLutWaves;
+    uint4 w[kPerWave][C];
+    uint32_t gblock[kPerWave];
+    int nvalid[kPerWave];
     int pi = 0;
-    for (int b = wave; b < nb; b += kLutWaves) {
-        while (b >= s.pfx[pi + 1]) ++pi;                      // b < TB = pfx[nprobe]
-        const int bl = b - s.pfx[pi];
-        const uint32_t gblock = (uint32_t)(s.blk[pi] + bl);
-        const int nvalid = s.len[pi] - bl * kBlockVecs;
-        const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock * kBlockVecs * MP);
-        uint4 w[C];
 #pragma unroll
-        for (int c = 0; c < C; ++c) w[c] = blk[c * kWave + lane];
-        float dist;
-        if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
-        else dist = block_dist_generic<C>(w, s.lut, lane_m);
-        append_candidates(lane < nvalid, __float_as_uint(dist), gblock * kBlockVecs + lane, s.cand, &s.misc[0], cap, lane);
+    for (int i = 0; i < kPerWave; ++i) {
+        const int b = wave + i * kLutWaves;
+        nvalid[i] = 0;
+        gblock[i] = 0;
+        if (b < nb) {
+            while (b >= s.pfx[pi + 1]) ++pi;                  // b < TB = pfx[nprobe]
+            const int bl = b - s.pfx[pi];
+            gblock[i] = (uint32_t)(s.blk[pi] + bl);
+            nvalid[i] = s.len[pi] - bl * kBlockVecs;
+            const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock[i] * kBlockVecs * MP);
+#pragma unroll
+            for (int c = 0; c < C; ++c) w[i][c] = blk[c * kWave + lane];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        if (nvalid[i] > 0) {                                  // uniform per wave
+            float dist;
+            if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w[i]), off4);
+            else dist = block_dist_generic<C>(w[i], s.lut, lane_m);
+            append_candidates(lane < nvalid[i], __float_as_uint(dist), gblock[i] * kBlockVecs + lane, s.cand, &s.misc[0], cap,
+                              lane);
+        }
     }
     __syncthreads();
     const int n = min((int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]), cap);
@@ -998,6 +1034,21 @@ int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
         default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");           \
     }
 
+int launch_select(const piperag_index *ix, int nq, int nprobe, hipStream_t st) {
+    const int nlist = ix->p.nlist;
+    const int stage = nlist <= kSelMaxLdsRow;
+    const size_t lds = stage ? sizeof(uint32_t) * (size_t)nlist : 0;
+    static size_t configured = 32 * 1024;
+    if (lds > configured) {
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, nlist, nprobe, stage, ix->ws_probe,
+                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
+    return PIPERAG_OK;
+}
+
 int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
     constexpr int QT = 4;
     const int d = ix->p.d, nlist = ix->p.nlist;
@@ -1062,10 +1113,9 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
         const int v = e ? atoi(e) : 0;
         return v > 0 && v <= 2 * kTargetScanWGs ? v : kTargetScanWGs;
     }();
-    if (!probes)
-        hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(256), 0, st, ix->ws_D, ix->p.nlist, nprobe, ix->ws_probe,
-                           ix->ws_probe_d, pstride, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
-    else
+    if (!probes) {
+        if ((rc = launch_select(ix, nq, nprobe, st)) != PIPERAG_OK) return rc;
+    } else
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
                            ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
     hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, ix->ws_seg0,
@@ -1131,8 +1181,8 @@ int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int
     PR_CHECK_HIP(hipSetDevice(ix->device));
     const int rc = launch_coarse(ix, queries_dev, nq, st);
     if (rc != PIPERAG_OK) return rc;
-    hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(256), 0, st, ix->ws_D, ix->p.nlist, nprobe, ix->ws_probe,
-                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
+    const int rc2 = launch_select(ix, nq, nprobe, st);
+    if (rc2 != PIPERAG_OK) return rc2;
     PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ix->ws_probe, sizeof(int32_t) * ix->p.max_nprobe,
                                   sizeof(int32_t) * nprobe, nq, hipMemcpyDeviceToDevice, st));
     if (out_dist_dev)

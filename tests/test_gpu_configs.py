@@ -19,7 +19,7 @@ torch = pytest.importorskip("torch")
 LARGE = set(filter(None, os.environ.get("PIPERAG_LARGE", "").split(",")))
 
 
-def run_config(name, slice_rows, batches):
+def run_config(name, slice_rows, batches, max_check=64):
     import paper_2403_05676_amd as pkg
     import bench
     pkg.load_library()
@@ -59,11 +59,14 @@ def run_config(name, slice_rows, batches):
         probes, pd = ix.ivf_coarse(q, nprobe)
         od, oi = ix.ivfpq_search(q, nprobe, cfg.k)
         torch.cuda.synchronize()
+        scanned, nbytes = ix.search_stats()
         probes = probes.cpu().numpy()
         ex_p = parity.check_probes(probes, pd.cpu().numpy(), qh, coarse, nprobe)
-        hidx = bench.host_copy(ix, coarse, pq, lists=np.unique(probes))
-        ex_k, rel = parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), hidx, qh, probes, cfg.k)
-        scanned, nbytes = ix.search_stats()
+        print(f"[{name}] nq={nq} nprobe={nprobe}: probe sets checked ({ex_p} differ at ties)", flush=True)
+        nchk = min(nq, max_check)                  # the oracle re-scans these queries' lists on the host
+        hidx = bench.host_copy(ix, coarse, pq, lists=np.unique(probes[:nchk]))
+        print(f"[{name}] host copy of {len(np.unique(probes[:nchk]))} probed lists ({hidx.ntotal} vectors)", flush=True)
+        ex_k, rel = parity.check_topk(od.cpu().numpy()[:nchk], oi.cpu().numpy()[:nchk], hidx, qh[:nchk], probes[:nchk], cfg.k)
         assert scanned == int(lens[probes].sum())
         # throughput of this launch configuration (scan stage, HIP events)
         ix.set_stage_timing(True)
@@ -91,9 +94,9 @@ def test_cfg2_full_size():
 
 @pytest.mark.skipif("cfg3" not in LARGE, reason="set PIPERAG_LARGE=cfg3 (builds 268 M vectors, minutes)")
 def test_cfg3_full_size():
-    run_config("cfg3", 8192, [(64, 64)])
+    run_config("cfg3", 8192, [(64, 64)], max_check=16)
 
 
 @pytest.mark.skipif("cfg4" not in LARGE, reason="set PIPERAG_LARGE=cfg4 (builds 1.07 G vectors, tens of minutes)")
 def test_cfg4_full_size():
-    run_config("cfg4", 8192, [(1, 128), (16, 128), (256, 128)])
+    run_config("cfg4", 8192, [(1, 128), (16, 128), (256, 128)], max_check=8)
