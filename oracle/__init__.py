@@ -184,6 +184,25 @@ def search_with_probes(index: Index, q: np.ndarray, probes: np.ndarray, k: int):
     return od, oi, scanned
 
 
+def scan_with_probes(index: Index, q_row: np.ndarray, probes_row: np.ndarray):
+    """Distance and id of every vector in one query's probed lists, in probe order, with no selection:
+    (dist [ncand] f32, ids [ncand] i64).  The arithmetic is that of search_with_probes."""
+    q_row = _f32(q_row).reshape(-1)
+    probes_row = np.ascontiguousarray(probes_row, dtype=np.int32).reshape(-1)
+    M, ksub, dsub = index.pq.shape
+    lens = np.diff(index.list_off)
+    ncand = int(lens[probes_row[probes_row >= 0]].sum())
+    od = np.empty(ncand, dtype=np.float32)
+    oi = np.empty(ncand, dtype=np.int64)
+    fn = _load().oracle_scan_with_probes
+    fn.restype = C.c_int64
+    got = fn(_p(q_row, C.c_float), C.c_int(q_row.shape[0]), _p(index.pq, C.c_float), C.c_int(M), C.c_int(ksub),
+             _p(index.list_off, C.c_int64), _p(index.codes, C.c_uint8), _p(index.ids, C.c_int64),
+             _p(probes_row, C.c_int32), C.c_int(probes_row.shape[0]), _p(od, C.c_float), _p(oi, C.c_int64))
+    assert got == ncand
+    return od, oi
+
+
 def search(index: Index, q: np.ndarray, nprobe: int, k: int):
     """(dist [nq,k] f32, ids [nq,k] i64, probes [nq,nprobe] i32, scanned [nq] i64)."""
     q = _f32(q)

@@ -229,6 +229,37 @@ void oracle_lut(const float *q, int64_t nq, int d, const float *pq, int M, int k
  * codes ([ntotal, M] bytes) and ids ([ntotal]).
  * probes: [nq, nprobe] list numbers (a negative entry is skipped).
  * scanned_out (optional, [nq]): number of vectors compared per query. */
+/* Scan of one query's probed lists: cstart[p] = number of candidates in probes before p (nprobe + 1
+ * entries, filled here); returns a malloc'd array of all candidates in probe order. */
+static cand_t *scan_probed_lists(const float *q_row, const float *pq, int M, int ksub, int dsub,
+                                 const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
+                                 const int32_t *probes, int nprobe, int64_t *cstart) {
+    double *lut = (double *)malloc(sizeof(double) * (size_t)M * (size_t)ksub);
+    build_lut(q_row, pq, M, ksub, dsub, lut);
+    cstart[0] = 0;
+    for (int p = 0; p < nprobe; ++p) {
+        const int32_t l = probes[p];
+        cstart[p + 1] = cstart[p] + (l < 0 ? 0 : list_off[l + 1] - list_off[l]);
+    }
+    const int64_t ncand = cstart[nprobe];
+    cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(ncand > 0 ? ncand : 1));
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < nprobe; ++p) {
+        const int32_t l = probes[p];
+        if (l < 0) continue;
+        const int64_t a = list_off[l], len = list_off[l + 1] - a;
+        for (int64_t i = 0; i < len; ++i) {
+            const uint8_t *code = codes + (a + i) * M;
+            double acc = 0.0;
+            for (int m = 0; m < M; ++m) acc += lut[m * ksub + code[m]];
+            cand[cstart[p] + i].d = (float)acc;
+            cand[cstart[p] + i].id = ids[a + i];
+        }
+    }
+    free(lut);
+    return cand;
+}
+
 void oracle_search_with_probes(const float *q, int64_t nq, int d, const float *pq, int M, int ksub,
                                const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
                                const int32_t *probes, int nprobe, int k, float *out_dist, int64_t *out_ids,
@@ -237,30 +268,10 @@ void oracle_search_with_probes(const float *q, int64_t nq, int d, const float *p
     int nthreads = oracle_num_threads();
 #pragma omp parallel for schedule(dynamic, 1) if (nq >= nthreads)
     for (int64_t qi = 0; qi < nq; ++qi) {
-        double *lut = (double *)malloc(sizeof(double) * (size_t)M * (size_t)ksub);
-        build_lut(q + qi * d, pq, M, ksub, dsub, lut);
-        /* candidate buffer: one slot per scanned vector, in probe order */
         int64_t *cstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nprobe + 1));
-        cstart[0] = 0;
-        for (int p = 0; p < nprobe; ++p) {
-            const int32_t l = probes[qi * nprobe + p];
-            cstart[p + 1] = cstart[p] + (l < 0 ? 0 : list_off[l + 1] - list_off[l]);
-        }
+        cand_t *cand = scan_probed_lists(q + qi * d, pq, M, ksub, dsub, list_off, codes, ids, probes + qi * nprobe,
+                                         nprobe, cstart);
         const int64_t ncand = cstart[nprobe];
-        cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(ncand > 0 ? ncand : 1));
-#pragma omp parallel for schedule(dynamic, 1)
-        for (int p = 0; p < nprobe; ++p) {
-            const int32_t l = probes[qi * nprobe + p];
-            if (l < 0) continue;
-            const int64_t a = list_off[l], len = list_off[l + 1] - a;
-            for (int64_t i = 0; i < len; ++i) {
-                const uint8_t *code = codes + (a + i) * M;
-                double acc = 0.0;
-                for (int m = 0; m < M; ++m) acc += lut[m * ksub + code[m]];
-                cand[cstart[p] + i].d = (float)acc;
-                cand[cstart[p] + i].id = ids[a + i];
-            }
-        }
         /* keep the k smallest by (dist, id): sorted insertion */
         cand_t *best = (cand_t *)malloc(sizeof(cand_t) * (size_t)k);
         int nb = 0;
@@ -276,8 +287,21 @@ void oracle_search_with_probes(const float *q, int64_t nq, int d, const float *p
             out_ids[qi * k + r] = r < nb ? best[r].id : -1;
         }
         if (scanned_out) scanned_out[qi] = ncand;
-        free(best); free(cand); free(cstart); free(lut);
+        free(best); free(cand); free(cstart);
     }
+}
+
+/* The same scan for one query, without the selection: distance and id of every candidate, in probe order
+ * (out arrays sized for the sum of the probed lists' lengths).  Returns the number of candidates. */
+int64_t oracle_scan_with_probes(const float *q_row, int d, const float *pq, int M, int ksub,
+                                const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
+                                const int32_t *probes, int nprobe, float *out_dist, int64_t *out_ids) {
+    int64_t *cstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nprobe + 1));
+    cand_t *cand = scan_probed_lists(q_row, pq, M, ksub, d / M, list_off, codes, ids, probes, nprobe, cstart);
+    const int64_t ncand = cstart[nprobe];
+    for (int64_t c = 0; c < ncand; ++c) { out_dist[c] = cand[c].d; out_ids[c] = cand[c].id; }
+    free(cand); free(cstart);
+    return ncand;
 }
 
 /* Full search: coarse quantiser, then the scan above. */

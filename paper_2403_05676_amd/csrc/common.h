@@ -88,7 +88,9 @@ struct piperag_index {
     int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
-    int32_t *ws_wgq;      // [2*kTargetScanWGs+max_nq] query of each scan workgroup
+    int4 *ws_desc;        // [2*kTargetScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
+    int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
+    int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
     float *ws_qn;         // [max_nq] squared norms of the queries
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]

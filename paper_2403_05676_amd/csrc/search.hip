@@ -208,12 +208,22 @@ __global__ __launch_bounds__(256) void coarse_mfma_kernel(const float *__restric
 // Stage 1: top-nprobe selection and scan plan.
 // ------------------------------------------------------------------------------------------------
 // Per-query part of the plan, run by the first wavefront of a workgroup: pfx[i] = number of 64-vector blocks
-// in the first i probed lists (i = 0..nprobe), *scanned = vectors in the probed lists, *thr = "no bound yet"
-// for the scan's shared threshold.  probe_at(i) gives the i-th probed list or -1.
+// in the first i probed lists (i = 0..nprobe), pblk[i] / plen[i] = first block and length of the i-th probed
+// list (0 for a skipped entry), *scanned = vectors in the probed lists, *thr = "no bound yet" for the scan's
+// shared threshold.  probe_at(i) gives the i-th probed list or -1.
+struct PlanOut {
+    int32_t *pfx, *pblk, *plen;
+    int64_t *scanned;
+    uint32_t *thr;
+};
+__device__ __forceinline__ PlanOut plan_of_query(const PlanOut &all, int qi, int probe_stride) {
+    return PlanOut{all.pfx + (size_t)qi * (probe_stride + 1), all.pblk + (size_t)qi * probe_stride,
+                   all.plen + (size_t)qi * probe_stride, all.scanned + qi, all.thr + qi};
+}
 template <class ProbeFn>
 __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restrict__ list_blk,
-                           const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx, int64_t *__restrict__ scanned,
-                           uint32_t *__restrict__ thr) {
+                           const int32_t *__restrict__ list_len, const PlanOut o) {
+    int32_t *pfx = o.pfx;
     if (threadIdx.x >= 64) return;
     const int lane = threadIdx.x;
     int32_t running = 0;
@@ -229,13 +239,17 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
             const int32_t o = __shfl_up(incl, off, 64);
             if (lane >= off) incl += o;
         }
-        if (i < nprobe) pfx[i] = running + incl - nb;
+        if (i < nprobe) {
+            pfx[i] = running + incl - nb;
+            o.pblk[i] = l >= 0 ? list_blk[l] : 0;
+            o.plen[i] = (int32_t)len;
+        }
         running += __shfl(incl, 63, 64);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) len += __shfl_xor(len, off, 64);
         vecs += len;
     }
-    if (lane == 0) { pfx[nprobe] = running; *scanned = vecs; *thr = 0xFFFFFFFFu; }
+    if (lane == 0) { pfx[nprobe] = running; *o.scanned = vecs; *o.thr = 0xFFFFFFFFu; }
 }
 
 // Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
@@ -249,9 +263,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float 
                                                                     int stage_row, int32_t *__restrict__ probe,
                                                                     float *__restrict__ probe_d, int probe_stride,
                                                                     const int32_t *__restrict__ list_blk,
-                                                                    const int32_t *__restrict__ list_len,
-                                                                    int32_t *__restrict__ pfx, int64_t *__restrict__ scanned,
-                                                                    uint32_t *__restrict__ thr) {
+                                                                    const int32_t *__restrict__ list_len, PlanOut plan) {
     extern __shared__ __align__(16) unsigned char sel_smem[];
     __shared__ unsigned s_hist[256];
     __shared__ unsigned long long s_state[8];
@@ -284,7 +296,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float 
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
     }
     auto probe_at = [&](int i) { return (int32_t)(s_keys[i] & 0xFFFFFFFFu); };
-    plan_query(probe_at, nprobe, list_blk, list_len, pfx + (size_t)qi * (probe_stride + 1), scanned + qi, thr + qi);
+    plan_query(probe_at, nprobe, list_blk, list_len, plan_of_query(plan, qi, probe_stride));
 }
 
 // Probe lists given by the caller: entries outside 0..nlist-1 and repeats of an earlier entry become -1
@@ -292,8 +304,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float 
 __global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restrict__ src, int nprobe, int nlist,
                                                          int32_t *__restrict__ dst, int probe_stride,
                                                          const int32_t *__restrict__ list_blk,
-                                                         const int32_t *__restrict__ list_len, int32_t *__restrict__ pfx,
-                                                         int64_t *__restrict__ scanned, uint32_t *__restrict__ thr) {
+                                                         const int32_t *__restrict__ list_len, PlanOut plan) {
     const int qi = blockIdx.x;
     const int32_t *row = src + (size_t)qi * nprobe;
     int32_t *out = dst + (size_t)qi * probe_stride;
@@ -306,17 +317,19 @@ __global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restri
     }
     __syncthreads();
     auto probe_at = [&](int i) { return out[i]; };
-    plan_query(probe_at, nprobe, list_blk, list_len, pfx + (size_t)qi * (probe_stride + 1), scanned + qi, thr + qi);
+    plan_query(probe_at, nprobe, list_blk, list_len, plan_of_query(plan, qi, probe_stride));
 }
 
 // Shares the scan workgroups out over the queries (one workgroup): query q gets
 // S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
 // per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
 // the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
-// use, at most max(target, nq)); wg_q[w] = query of workgroup w.  A workgroup gets at least kMinBlocksPerWG
-// blocks (unless its query has fewer), so that small searches are not spread over needlessly many workgroups.
+// use, at most max(target, nq)); desc[w] = (query, first block, end block, 0) of workgroup w, blocks counted
+// along the query's concatenated probed lists; desc of spare workgroups has query -1.  A workgroup gets at
+// least kMinBlocksPerWG blocks (unless its query has fewer), so that small searches are not spread over
+// needlessly many workgroups.
 __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
-                                                    int target, int32_t *__restrict__ seg0, int32_t *__restrict__ wg_q) {
+                                                    int target, int max_wg, int32_t *__restrict__ seg0, int4 *__restrict__ desc) {
     __shared__ long long s_total;
     __shared__ int32_t s_scan[256];
     __shared__ int32_t s_carry;
@@ -356,13 +369,16 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
     if (tid == 0) seg0[nq] = s_carry;
     __syncthreads();
     const int total_wg = s_carry;
-    for (int w = tid; w < total_wg; w += 256) {            // query of workgroup w: last q with seg0[q] <= w
-        int lo = 0, hi = nq;
+    for (int w = tid; w < max_wg; w += 256) {
+        if (w >= total_wg) { desc[w] = int4{-1, 0, 0, 0}; continue; }
+        int lo = 0, hi = nq;                               // query of workgroup w: last q with seg0[q] <= w
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (seg0[mid] <= w) lo = mid; else hi = mid;
         }
-        wg_q[w] = lo;
+        const int seg = w - seg0[lo], S = seg0[lo + 1] - seg0[lo];
+        const long long tb = pfx[(size_t)lo * (probe_stride + 1) + nprobe];
+        desc[w] = int4{lo, (int)(tb * seg / S), (int)(tb * (seg + 1) / S), 0};
     }
 }
 
@@ -372,15 +388,13 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 struct ScanArgs {
     const uint8_t *codes;
     const float *lut;          // [nq][256][Mp]
-    const int32_t *probe;      // [nq][probe_stride]
-    const int32_t *pfx;        // [nq][probe_stride+1]
-    const int32_t *list_blk;
-    const int32_t *list_len;
+    const int32_t *pfx;        // [nq][probe_stride+1] block prefix sums of the probed lists
+    const int32_t *pblk;       // [nq][probe_stride] first block of each probed list
+    const int32_t *plen;       // [nq][probe_stride] length of each probed list
     uint64_t *part;            // [workgroups][KW] partial results
     uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
-    const int32_t *seg0;       // [nq+1] first workgroup of each query
-    const int32_t *wg_q;       // [workgroups] query of each workgroup
-    int nq, nprobe, probe_stride, k, KW;
+    const int4 *desc;          // [workgroups] (query, first block, end block, 0); query -1: spare
+    int nprobe, probe_stride, k, KW;
 #ifdef PIPERAG_TRACE
     unsigned long long *trace;   // [workgroups][8] timestamps
     int flags;                   // experiments: 1 = no appends, 2 = no table lookups
@@ -573,27 +587,91 @@ __device__ uint32_t wg_prune(const ScanLds s, int n, int k) {
     return T;
 }
 
-// Copies the query's probe tables into LDS (block prefix sums, first block and length of each probed list).
-__device__ __forceinline__ void stage_probe_tables(const ScanArgs &a, const ScanLds &s, int qi) {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int32_t *pf = a.pfx + (size_t)qi * (a.probe_stride + 1);
-    for (int i = tid; i <= a.nprobe; i += nt) s.pfx[i] = pf[i];
-    for (int i = tid; i < a.nprobe; i += nt) {
-        const int32_t l = a.probe[(size_t)qi * a.probe_stride + i];
-        s.blk[i] = l >= 0 ? a.list_blk[l] : 0;
-        s.len[i] = l >= 0 ? a.list_len[l] : 0;
+// Fresh read of a workgroup counter in LDS.  The pointer is cast to the LDS address space first: a volatile
+// read through a generic pointer would be a flat load, which has to wait for every global load in flight
+// (the prefetched code blocks) before its value can be used.
+__device__ __forceinline__ unsigned lds_peek(const unsigned *p) {
+    return *(const volatile __attribute__((address_space(3))) unsigned *)p;
+}
+
+// Copy of one query's table (256 x MP floats, contiguous) from global memory into LDS, in two halves so that
+// it overlaps other loads: lut_copy_begin() issues the loads, lut_copy_end() completes them; a barrier then
+// makes the table visible to the workgroup.  Tables that end below 64 KiB of LDS go straight from global
+// memory to LDS (each wave-wide load moves 64 x 16 bytes to consecutive LDS addresses, without passing
+// through registers; its LDS base is a 16-bit wave-uniform offset); larger ones are copied through registers
+// at the end.
+template <int NTHREADS, int MP>
+__device__ __forceinline__ void lut_copy_begin(const float *__restrict__ src, float *dst) {
+    if constexpr (kKsub * MP * 4 <= 65536) {
+        typedef __attribute__((address_space(3))) unsigned char lds_byte;
+        typedef __attribute__((address_space(1))) const unsigned char global_byte;
+        constexpr int kPieces = kKsub * MP / 4 / NTHREADS;       // 16-byte pieces per thread
+        const int tid = threadIdx.x;
+        lds_byte *base = (lds_byte *)dst + (tid & ~63) * 16;     // wave-uniform; the hardware adds 16 bytes per lane
+        global_byte *g = (global_byte *)src + (size_t)tid * 16;
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            __builtin_amdgcn_global_load_lds(g + (size_t)i * NTHREADS * 16, base + i * NTHREADS * 16, 16, 0, 0);
     }
-    if (tid == 0) { s.misc[0] = 0; s.misc[3] = 0; }
+}
+template <int NTHREADS, int MP>
+__device__ __forceinline__ void lut_copy_end(const float *__restrict__ src, float *dst) {
+    if constexpr (kKsub * MP * 4 <= 65536) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's direct loads have landed
+    } else {
+        constexpr int kPieces = kKsub * MP / 4 / NTHREADS;
+        const float4 *s4 = reinterpret_cast<const float4 *>(src);
+        float4 *d4 = reinterpret_cast<float4 *>(dst);
+        constexpr int kChunk = kPieces % 4 == 0 ? 4 : 2;        // pieces in flight per thread
+        static_assert(kPieces % kChunk == 0, "whole chunks");
+        for (int i0 = 0; i0 < kPieces; i0 += kChunk) {
+            float4 v[kChunk];
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) v[i] = s4[threadIdx.x + (i0 + i) * NTHREADS];
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) d4[threadIdx.x + (i0 + i) * NTHREADS] = v[i];
+        }
+    }
+}
+
+// The query's probe tables (block prefix sums, first block and length of each probed list) go to LDS in two
+// halves, loads into registers and stores to LDS, so that other loads can be issued in between.
+template <int NTHREADS>
+struct ProbeTableRegs {
+    static constexpr int kIter = kMaxNprobe / NTHREADS;
+    int32_t pf[kIter], pb[kIter], pl[kIter], pf_last;
+};
+template <int NTHREADS>
+__device__ __forceinline__ void load_probe_tables(const ScanArgs &a, int qi, ProbeTableRegs<NTHREADS> &r) {
+    const int tid = threadIdx.x;
+    const int32_t *pf = a.pfx + (size_t)qi * (a.probe_stride + 1);
+    const int32_t *pb = a.pblk + (size_t)qi * a.probe_stride, *pl = a.plen + (size_t)qi * a.probe_stride;
+#pragma unroll
+    for (int j = 0; j < ProbeTableRegs<NTHREADS>::kIter; ++j) {
+        const int i = tid + j * NTHREADS;
+        const bool ok = i < a.nprobe;
+        r.pf[j] = ok ? pf[i] : 0; r.pb[j] = ok ? pb[i] : 0; r.pl[j] = ok ? pl[i] : 0;
+    }
+    r.pf_last = pf[a.nprobe];
+}
+template <int NTHREADS>
+__device__ __forceinline__ void store_probe_tables(const ScanArgs &a, const ScanLds &s, const ProbeTableRegs<NTHREADS> &r) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < ProbeTableRegs<NTHREADS>::kIter; ++j) {
+        const int i = tid + j * NTHREADS;
+        if (i < a.nprobe) { s.pfx[i] = r.pf[j]; s.blk[i] = r.pb[j]; s.len[i] = r.pl[j]; }
+    }
+    if (tid == 0) { s.pfx[a.nprobe] = r.pf_last; s.misc[0] = 0; s.misc[3] = 0; }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage 2: lookup tables + priming of the bound.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2.
-// One workgroup (512 threads) per query builds the table in LDS in the scan layout [j][Mp] (rows of padding
-// sub-quantisers m >= M are zero) from the centre-major copy of the codebook pqT[j][m][t] - a wave takes four
-// j at a time and its lanes the sub-quantisers, so both the global reads and the LDS writes are contiguous -
-// and writes it to lut[q].  It then scans the first kPrimeBlocks blocks of the query's probed lists (the
-// closest lists come first) with that table and sets thr[q] to a distance that at least k of those vectors
-// reach: the scan proper starts with a useful bound instead of accepting everything.
+// Stage 2: lookup tables + priming of the bound.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2,
+// stored in the scan layout lut[q][j][Mp] (rows of padding sub-quantisers m >= M are zero), built from the
+// centre-major copy of the codebook pqT[j][m][t] by four workgroups per query (the codebook read, 768 KiB at
+// d = 768, is what the build costs, so it is spread over several compute units).  A second kernel scans the
+// first kPrimeBlocks blocks of each query's probed lists with its table and sets thr[q] to a distance that at
+// least k of those vectors reach: the scan proper starts with a useful bound instead of accepting everything.
 // ------------------------------------------------------------------------------------------------
 constexpr int kLutThreads = 512;
 constexpr int kLutWaves = kLutThreads / kWave;
@@ -631,41 +709,54 @@ __device__ __forceinline__ float lut_entry(const float *__restrict__ qs, const f
     return acc;
 }
 
-template <int C, int DSUB>
-__global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__restrict__ q, const float *__restrict__ pqT,
-                                                                int d, int M, int dsub, float *__restrict__ lut_out,
-                                                                ScanArgs a) {
-    constexpr int MP = 16 * C;
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int cap = kPrimeBlocks * kBlockVecs;
-    const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
-    float *s_q = reinterpret_cast<float *>(s.len + a.nprobe);      // [d] the query
+// Table build: workgroup (x, q) computes the rows j = 64x .. 64x+63 of query q's table, a wave 16 of them, 8 at
+// a time so that their loads overlap; lane <-> sub-quantiser, so the reads of pqT[j][m][.] and the writes of
+// lut[q][j][m] are contiguous.  grid = (4, nq), 256 threads.
+template <int DSUB>
+__global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict__ q, const float *__restrict__ pqT, int d, int M,
+                                                        int dsub, int Mp, float *__restrict__ lut_out) {
+    extern __shared__ __align__(16) unsigned char lsmem[];
+    float *s_q = reinterpret_cast<float *>(lsmem);      // [d] the query
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qi = blockIdx.x;
-    const bool lut_at_zero =
-        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
-    stage_probe_tables(a, s, qi);
-    for (int t = tid; t < d; t += kLutThreads) s_q[t] = q[(size_t)qi * d + t];
+    const int qi = blockIdx.y;
+    for (int t = tid; t < d; t += 256) s_q[t] = q[(size_t)qi * d + t];
     __syncthreads();
-    // table: lane <-> sub-quantiser, wave <-> centre (8 centres at a time, so that their loads overlap)
-    for (int m = lane; m < MP; m += kWave) {
+    float *out = lut_out + (size_t)qi * kKsub * Mp;
+    for (int m = lane; m < Mp; m += kWave) {
         const float *qs = s_q + m * dsub;
-        for (int j0 = wave * 8; j0 < kKsub; j0 += kLutWaves * 8) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int j0 = blockIdx.x * 64 + wave * 16 + it * 8;
             float e[8];
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj)
                 e[jj] = m < M ? lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub) : 0.f;
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) s.lut[(j0 + jj) * MP + m] = e[jj];
+            for (int jj = 0; jj < 8; ++jj) out[(size_t)(j0 + jj) * Mp + m] = e[jj];
         }
     }
+}
+
+// Priming of the bound: one workgroup (512 threads) per query stages the query's table in LDS, scans the first
+// kPrimeBlocks blocks of the query's probed lists (the closest lists come first) and sets thr[q] to a distance
+// that at least k of those vectors reach.
+template <int C>
+__global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
+    constexpr int MP = 16 * C;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int cap = kPrimeBlocks * kBlockVecs;
+    const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = blockIdx.x;
+    const bool lut_at_zero =
+        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
+    // the table starts on its way to LDS first (it depends on nothing else), then the probe tables; every wave
+    // then requests all its blocks, waits for the table, and works through the blocks
+    ProbeTableRegs<kLutThreads> tables;
+    load_probe_tables(a, qi, tables);
+    lut_copy_begin<kLutThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
+    store_probe_tables(a, s, tables);
     __syncthreads();
-    {
-        float4 *dst = reinterpret_cast<float4 *>(lut_out + (size_t)qi * kKsub * MP);
-        const float4 *src = reinterpret_cast<const float4 *>(s.lut);
-        for (int i = tid; i < kKsub * MP / 4; i += kLutThreads) dst[i] = src[i];
-    }
-    // priming scan: every wave first requests all its blocks, then works through them
     const int TB = s.pfx[a.nprobe];
     const int nb = min(TB, kPrimeBlocks);
     const int lane_m = lane % MP;
@@ -691,6 +782,8 @@ __global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__r
             for (int c = 0; c < C; ++c) w[i][c] = blk[c * kWave + lane];
         }
     }
+    lut_copy_end<kLutThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
         if (nvalid[i] > 0) {                                  // uniform per wave
@@ -702,7 +795,7 @@ __global__ __launch_bounds__(kLutThreads) void lut_prime_kernel(const float *__r
         }
     }
     __syncthreads();
-    const int n = min((int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]), cap);
+    const int n = min((int)lds_peek(&s.misc[0]), cap);
     if (n > a.k) {                          // uniform
         const uint32_t T = wg_prune(s, n, a.k);
         if (tid == 0) a.thr[qi] = T;        // plan_query set "no bound"; the scan only lowers it from here
@@ -747,9 +840,9 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x;
-    if (wg >= a.seg0[a.nq]) return;                         // spare workgroup (uniform exit)
-    const int qi = a.wg_q[wg];
-    const int seg = wg - a.seg0[qi], S = a.seg0[qi + 1] - a.seg0[qi];
+    const int4 desc = a.desc[wg];                            // (query, first block, end block, 0)
+    if (desc.x < 0) return;                                  // spare workgroup (uniform exit)
+    const int qi = desc.x, b_begin = desc.y, b_end = desc.z;
     const bool lut_at_zero =
         reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
 #ifdef PIPERAG_TRACE
@@ -758,14 +851,15 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     unsigned long long tflush = 0;
     if (tid == 0) tr[0] = wall_clock64();
 #endif
-    stage_probe_tables(a, s, qi);          // first: the first code loads depend on them
+    // the query's table starts on its way to LDS first (it depends on nothing else), then the probe tables
+    ProbeTableRegs<kScanThreads> tables;
+    load_probe_tables(a, qi, tables);
+    lut_copy_begin<kScanThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
+    store_probe_tables(a, s, tables);
     __syncthreads();
 
     uint32_t thr = 0xFFFFFFFFu;     // best known bound on the k-th best distance (bits)
-    const int TB = s.pfx[a.nprobe];
-    const int b_begin = (int)((int64_t)TB * seg / S), b_end = (int)((int64_t)TB * (seg + 1) / S);
-    // a wave checks the count before every block and appends at most 64 keys per block
-    const int trigger = cap - kScanThreads;
+    const int trigger = cap - kScanWaves * NSETS * kBlockVecs;
     const int lane_m = lane % MP;
     uint32_t off4[16];
     make_off4(off4, lane);
@@ -773,19 +867,25 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     int b_next = b_begin + wave;    // next block this wave will request
     int pi = 0;                     // probe whose list holds b_next (advanced monotonically)
 
+    // Every call issues the same number of loads, whether or not the wave still has a block to fetch (a wave
+    // out of blocks re-reads a few bytes of block 0, which always exists): the compiler can then count the
+    // loads in flight exactly and lets NSETS - 1 later requests stay in flight while one block is worked on.
     struct Meta { uint32_t gblock; int nvalid; uint32_t tg; bool valid; };
+    const uint4 *idle = reinterpret_cast<const uint4 *>(a.codes);
     auto issue = [&](uint4 (&w)[C], Meta &m) {
         m.valid = b_next < b_end;
-        if (!m.valid) return;
-        while (b_next >= s.pfx[pi + 1]) ++pi;                 // b_next < TB = pfx[nprobe], so pi stays < nprobe
-        const int bl = b_next - s.pfx[pi];
-        m.gblock = (uint32_t)(s.blk[pi] + bl);
-        m.nvalid = s.len[pi] - bl * kBlockVecs;               // >= 1; lanes >= nvalid hold padding
-        const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP);
+        const uint4 *src = idle;
+        if (m.valid) {
+            while (b_next >= s.pfx[pi + 1]) ++pi;             // b_next < TB = pfx[nprobe], so pi stays < nprobe
+            const int bl = b_next - s.pfx[pi];
+            m.gblock = (uint32_t)(s.blk[pi] + bl);
+            m.nvalid = s.len[pi] - bl * kBlockVecs;           // >= 1; lanes >= nvalid hold padding
+            src = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP) + lane;
+            b_next += kScanWaves;
+        }
 #pragma unroll
-        for (int c = 0; c < C; ++c) w[c] = blk[c * kWave + lane];
+        for (int c = 0; c < C; ++c) w[c] = src[c * kWave];
         m.tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        b_next += kScanWaves;
     };
     auto process = [&](const uint4 (&w)[C], const Meta &m) {
         float dist;
@@ -812,46 +912,35 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     Meta meta[NSETS];
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i]);
-    {   // the query's table, while the first code blocks are on their way
-        const float4 *src = reinterpret_cast<const float4 *>(a.lut + (size_t)qi * kKsub * MP);
-        float4 *dst = reinterpret_cast<float4 *>(s.lut);
-        constexpr int kPer = kKsub * MP / 4 / kScanThreads;     // 16-byte pieces per thread (4*C)
-#pragma unroll
-        for (int i0 = 0; i0 < kPer; i0 += 8) {
-            float4 tmp[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) if (i0 + i < kPer) tmp[i] = src[tid + (i0 + i) * kScanThreads];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) if (i0 + i < kPer) dst[tid + (i0 + i) * kScanThreads] = tmp[i];
-        }
-    }
+    lut_copy_end<kScanThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
     __syncthreads();
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[1] = wall_clock64();
 #endif
     bool announced = false;         // this wave has told the others that it is out of blocks
     for (;;) {
-        bool hold = false, any = false;
+        // the count is looked at once per NSETS blocks; until every wave has looked again, each of them appends
+        // at most NSETS * 64 keys, which is the room the trigger leaves
+        const bool hold = (int)lds_peek(&s.misc[0]) > trigger;
+        bool any = false;           // this wave still holds a requested block
 #pragma unroll
-        for (int i = 0; i < NSETS; ++i) {
-            if (meta[i].valid) {
-                any = true;
-                if (!hold) hold = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]) > trigger;
-                if (!hold) {
-                    process(w[i], meta[i]);
-                    issue(w[i], meta[i]);
-                }
+        for (int i = 0; i < NSETS; ++i) any |= meta[i].valid;
+        if (!hold && any) {
+#pragma unroll
+            for (int i = 0; i < NSETS; ++i) {
+                if (meta[i].valid) process(w[i], meta[i]);
+                issue(w[i], meta[i]);
             }
+            continue;
         }
-        if (!hold && any) continue;
         // buffer nearly full, or this wave is out of blocks: meet the other waves
         if (!any && !announced) {
             announced = true;
             if (lane == 0) atomicAdd(&s.misc[3], 1u);
         }
         __syncthreads();
-        const int n = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]);
-        const int ndone = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[3]);
+        const int n = (int)lds_peek(&s.misc[0]);
+        const int ndone = (int)lds_peek(&s.misc[3]);
         __syncthreads();            // nobody appends again before everybody has read the two counters
         if (n > trigger) {          // uniform: all threads read the same values between the barriers
 #ifdef PIPERAG_TRACE
@@ -870,11 +959,11 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 #ifdef PIPERAG_TRACE
     if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)(b_end - b_begin); tr[7] = tflush; }
 #endif
-    int n = min((int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]), cap);
+    int n = min((int)lds_peek(&s.misc[0]), cap);
     if (n > KW) {                   // uniform
         const uint32_t T = wg_prune(s, n, k);
         if (tid == 0) atomicMin(&a.thr[qi], T);
-        n = (int)*reinterpret_cast<volatile unsigned *>(&s.misc[0]);
+        n = (int)lds_peek(&s.misc[0]);
     }
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[3] = wall_clock64();
@@ -986,26 +1075,35 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-template <int C, int DSUB>
-int launch_lut_prime_d(const piperag_index *ix, const float *q, int nq, const ScanArgs &a, hipStream_t st) {
-    const size_t lds = scan_lds_bytes(ix->Mp, kPrimeBlocks * kBlockVecs, a.nprobe) + sizeof(float) * ix->p.d;
-    PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "table kernel needs %zu bytes of LDS", lds);
-    static size_t configured = 0;
-    if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&lut_prime_kernel<C, DSUB>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
+template <int DSUB>
+void launch_lut_build_d(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
+    hipLaunchKernelGGL((lut_build_kernel<DSUB>), dim3(4, nq), dim3(256), sizeof(float) * ix->p.d, st, q, ix->pqT, ix->p.d, ix->p.M,
+                       ix->dsub, ix->Mp, ix->ws_lut);
+}
+
+void launch_lut_build(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
+    switch (ix->dsub) {                      // common slice widths get their loads unrolled at compile time
+        case 4: launch_lut_build_d<4>(ix, q, nq, st); break;
+        case 6: launch_lut_build_d<6>(ix, q, nq, st); break;
+        case 8: launch_lut_build_d<8>(ix, q, nq, st); break;
+        case 12: launch_lut_build_d<12>(ix, q, nq, st); break;
+        case 16: launch_lut_build_d<16>(ix, q, nq, st); break;
+        default: launch_lut_build_d<0>(ix, q, nq, st); break;
     }
-    hipLaunchKernelGGL((lut_prime_kernel<C, DSUB>), dim3(nq), dim3(kLutThreads), lds, st, q, ix->pqT, ix->p.d, ix->p.M, ix->dsub,
-                       ix->ws_lut, a);
-    return PIPERAG_OK;
 }
 
 template <int C>
-int launch_lut_prime(const piperag_index *ix, const float *q, int nq, const ScanArgs &a, hipStream_t st) {
-    if (C == 4 && ix->p.M == 64 && ix->dsub == 12) return launch_lut_prime_d<C == 4 ? 4 : C, C == 4 ? 12 : 0>(ix, q, nq, a, st);
-    if (C == 4 && ix->p.M == 64 && ix->dsub == 6) return launch_lut_prime_d<C == 4 ? 4 : C, C == 4 ? 6 : 0>(ix, q, nq, a, st);
-    return launch_lut_prime_d<C, 0>(ix, q, nq, a, st);
+int launch_prime(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
+    const size_t lds = scan_lds_bytes(ix->Mp, kPrimeBlocks * kBlockVecs, a.nprobe);
+    PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "priming kernel needs %zu bytes of LDS", lds);
+    static size_t configured = 0;
+    if (lds > configured) {
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&prime_kernel<C>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    hipLaunchKernelGGL((prime_kernel<C>), dim3(nq), dim3(kLutThreads), lds, st, a);
+    return PIPERAG_OK;
 }
 
 template <int C>
@@ -1034,6 +1132,8 @@ int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
         default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");           \
     }
 
+PlanOut plan_bufs(const piperag_index *ix) { return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr}; }
+
 int launch_select(const piperag_index *ix, int nq, int nprobe, hipStream_t st) {
     const int nlist = ix->p.nlist;
     const int stage = nlist <= kSelMaxLdsRow;
@@ -1045,7 +1145,7 @@ int launch_select(const piperag_index *ix, int nq, int nprobe, hipStream_t st) {
         configured = lds;
     }
     hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, nlist, nprobe, stage, ix->ws_probe,
-                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
+                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix));
     return PIPERAG_OK;
 }
 
@@ -1117,14 +1217,14 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
         if ((rc = launch_select(ix, nq, nprobe, st)) != PIPERAG_OK) return rc;
     } else
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
-                           ix->list_blk, ix->list_len, ix->ws_pfx, ix->ws_scanned, ix->ws_thr);
-    hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, ix->ws_seg0,
-                       ix->ws_wgq);
+                           ix->list_blk, ix->list_len, plan_bufs(ix));
+    const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
+    hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, ix->ws_seg0,
+                       ix->ws_desc);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
-    const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
-    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_probe, ix->ws_pfx, ix->list_blk, ix->list_len, ix->ws_part, ix->ws_thr,
-               ix->ws_seg0, ix->ws_wgq, nq, nprobe, pstride, k, KW};
+    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
+               nprobe, pstride, k, KW};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
@@ -1133,7 +1233,8 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     { const char *e = getenv("PIPERAG_DEBUG_FLAGS"); a.flags = e ? atoi(e) : 0; }
     g_trace_buf = trace_buf; g_trace_n = G;
 #endif
-    PR_DISPATCH_C(launch_lut_prime, ix, q, nq, a, st)
+    launch_lut_build(ix, q, nq, st);
+    PR_DISPATCH_C(launch_prime, ix, nq, a, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
     const size_t lds = scan_lds_bytes(ix->Mp, KW + kCandRoom, nprobe);

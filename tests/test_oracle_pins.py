@@ -274,3 +274,24 @@ def test_index_file_layout(tmp_path):
     raw = path.read_bytes()
     assert raw[:8] == b"PRAGIVF1"
     assert len(raw) == 64 + 4 * (4 * 16 + 4 * 256 * 4) + 8 * 4 + 300 * 4 + 8 * 300
+
+
+def test_scan_with_probes_lists_every_candidate_once_and_its_k_best_are_the_search_result():
+    """The all-candidates tap and the search share one scan: sorting the tap's output by (distance, id) and
+    cutting at k must reproduce search_with_probes, and the candidate count is the sum of the list lengths."""
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((3000, 32)).astype(np.float32)
+    coarse = x[:16].copy()                                     # any centres and codebooks do for this property
+    pq = rng.standard_normal((8, 256, 4)).astype(np.float32)
+    index = oracle.make_index(x, coarse, pq)
+    q = rng.standard_normal((5, 32)).astype(np.float32)
+    probes, _ = oracle.coarse_search(q, index.coarse, 4)
+    probes[2, 1] = -1                                          # a skipped probe
+    od, oi, scanned = oracle.search_with_probes(index, q, probes, 20)
+    lens = np.diff(index.list_off)
+    for qi in range(5):
+        ad, ai = oracle.scan_with_probes(index, q[qi], probes[qi])
+        assert len(ad) == scanned[qi] == lens[probes[qi][probes[qi] >= 0]].sum()
+        assert len(set(ai.tolist())) == len(ai)
+        order = np.lexsort((ai, ad))[:20]
+        assert np.array_equal(ai[order], oi[qi]) and np.array_equal(ad[order], od[qi])
