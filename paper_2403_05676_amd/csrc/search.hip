@@ -329,7 +329,8 @@ __global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restri
 // least kMinBlocksPerWG blocks (unless its query has fewer), so that small searches are not spread over
 // needlessly many workgroups.
 __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
-                                                    int target, int max_wg, int32_t *__restrict__ seg0, int4 *__restrict__ desc) {
+                                                    int target, int max_wg, int32_t *__restrict__ seg0, int4 *__restrict__ desc,
+                                                    uint32_t *__restrict__ ctr) {
     __shared__ long long s_total;
     __shared__ int32_t s_scan[256];
     __shared__ int32_t s_carry;
@@ -377,8 +378,9 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
             if (seg0[mid] <= w) lo = mid; else hi = mid;
         }
         const int seg = w - seg0[lo], S = seg0[lo + 1] - seg0[lo];
-        const long long tb = pfx[(size_t)lo * (probe_stride + 1) + nprobe];
-        desc[w] = int4{lo, (int)(tb * seg / S), (int)(tb * (seg + 1) / S), 0};
+        desc[w] = int4{lo, seg, S, 0};
+        // every wave of the query's workgroups starts on the chunk of its own number; the counter hands out the rest
+        if (seg == 0) ctr[(size_t)lo * kCtrStride] = (uint32_t)S * kScanWaves;
     }
 }
 
@@ -393,7 +395,8 @@ struct ScanArgs {
     const int32_t *plen;       // [nq][probe_stride] length of each probed list
     uint64_t *part;            // [workgroups][KW] partial results
     uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
-    const int4 *desc;          // [workgroups] (query, first block, end block, 0); query -1: spare
+    const int4 *desc;          // [workgroups] (query, number among the query's workgroups, their count, 0); query -1: spare
+    uint32_t *ctr;             // [nq * kCtrStride] next chunk of each query's blocks to hand out
     int nprobe, probe_stride, k, KW;
 #ifdef PIPERAG_TRACE
     unsigned long long *trace;   // [workgroups][8] timestamps
@@ -407,6 +410,7 @@ constexpr int kKeepSlack = 64;                        // pruning keeps between k
 constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack
 constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
 constexpr int kPrimeBlocks = 32;                      // blocks of the closest lists scanned to prime the bound
+constexpr int kChunkBlocks = 4;                       // consecutive blocks a scan wave takes at a time
 
 // LDS carve-up shared by the priming and the scan kernel (all dynamic, so that the table starts at address 0)
 struct ScanLds {
@@ -498,44 +502,42 @@ __device__ __forceinline__ void append_candidates(bool pass, uint32_t dbits, uin
     }
 }
 
-// Prunes the candidate buffer s_cand[0..n), n > k: keeps every key whose distance is <= T, where T is chosen
-// so that between k and k + kKeepSlack keys remain (exactly k in the rare fall-back), and returns T (distance
-// bits).  Nothing that could be among the k best is dropped, and no sorting is done.  T is found by bucket
-// counting on the distance bits over [min, max], narrowed to one bucket per round.  Whole workgroup (at
-// least kScanThreads threads), called with all threads at the same point; *s.misc (the count) becomes the
-// number kept.
-__device__ uint32_t wg_prune(const ScanLds s, int n, int k) {
+// Prunes the candidate buffer s_cand[0..n), n > k: keeps every key <= T, where the key T is chosen so that
+// between k and k + kKeepSlack keys remain, and returns T.  Keys are (distance bits << 32 | slot) and all
+// different, so nothing that could be among the k best by (distance, slot) is dropped; no sorting is done.  T
+// is found by bucket counting over [min key, max key], narrowed to one of 256 buckets per round: the first
+// rounds split by distance, and only if more than the slack allows share one distance do later rounds split
+// by slot (8 rounds reach single keys).  Whole workgroup (at least kScanThreads threads), called with all
+// threads at the same point; *s.misc (the count) becomes the number kept.
+__device__ uint64_t wg_prune(const ScanLds s, int n, int k) {
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     uint64_t mine[kCandPerThread];
-    uint32_t dmin = 0xFFFFFFFFu, dmax = 0;
+    uint64_t kmin = ~0ull, kmax = 0;
 #pragma unroll
     for (int e = 0; e < kCandPerThread; ++e) {
         const int i = tid + e * nt;
         mine[e] = i < n ? s.cand[i] : kSentinel;
-        if (i < n) { const uint32_t d = (uint32_t)(mine[e] >> 32); dmin = min(dmin, d); dmax = max(dmax, d); }
+        if (i < n) { kmin = min(kmin, mine[e]); kmax = max(kmax, mine[e]); }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        dmin = min(dmin, (uint32_t)__shfl_xor(dmin, off, 64));
-        dmax = max(dmax, (uint32_t)__shfl_xor(dmax, off, 64));
+        kmin = min(kmin, (uint64_t)__shfl_xor((unsigned long long)kmin, off, 64));
+        kmax = max(kmax, (uint64_t)__shfl_xor((unsigned long long)kmax, off, 64));
     }
-    if (tid == 0) { s.misc[1] = 0xFFFFFFFFu; s.misc[2] = 0; }
+    if (tid == 0) { s.state[3] = ~0ull; s.state[4] = 0; }
     for (int i = tid; i < 256; i += nt) s.hist[i] = 0;
     __syncthreads();
-    if (lane == 0) { atomicMin(&s.misc[1], dmin); atomicMax(&s.misc[2], dmax); }
+    if (lane == 0) { atomicMin(&s.state[3], (unsigned long long)kmin); atomicMax(&s.state[4], (unsigned long long)kmax); }
     __syncthreads();
-    uint32_t lo = s.misc[1], hi = s.misc[2];
+    uint64_t lo = s.state[3], hi = s.state[4];
     unsigned need = (unsigned)k, kept_below = 0;
-    bool accepted = false;
-    uint32_t T = hi;
-    for (int round = 0; round < 4 && !accepted; ++round) {
-        const uint32_t width = hi - lo;
-        const int sh = width < 256 ? 0 : (24 - __clz(width));            // (width >> sh) <= 255
+    uint64_t T = hi;
+    for (int round = 0; round < 8; ++round) {
+        const uint64_t width = hi - lo;
+        const int sh = width < 256 ? 0 : (56 - __clzll((long long)width));   // (width >> sh) <= 255
 #pragma unroll
-        for (int e = 0; e < kCandPerThread; ++e) {
-            const uint32_t d = (uint32_t)(mine[e] >> 32);
-            if (mine[e] != kSentinel && d >= lo && d <= hi) atomicAdd(&s.hist[(d - lo) >> sh], 1u);
-        }
+        for (int e = 0; e < kCandPerThread; ++e)
+            if (mine[e] != kSentinel && mine[e] >= lo && mine[e] <= hi) atomicAdd(&s.hist[(unsigned)((mine[e] - lo) >> sh)], 1u);
         __syncthreads();
         if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
             unsigned h[4], sum = 0;
@@ -561,28 +563,18 @@ __device__ uint32_t wg_prune(const ScanLds s, int n, int k) {
         __syncthreads();
         const unsigned bucket = (unsigned)s.state[0], before = (unsigned)s.state[1], inb = (unsigned)s.state[2];
         __syncthreads();
-        const uint32_t blo = lo + (bucket << sh);
-        const uint32_t edge = min(hi, blo + ((sh > 0 ? (1u << sh) : 1u) - 1u));
-        if (kept_below + before + inb <= (unsigned)(k + kKeepSlack)) {   // keeping the whole bucket is within the slack
-            T = edge;
-            accepted = true;
-        } else if (sh == 0) {
-            break;                                                       // too many equal distances: exact fall-back
-        } else {
-            kept_below += before; need -= before; lo = blo; hi = edge;   // look inside the bucket
-        }
-    }
-    uint64_t Tkey = ((uint64_t)T << 32) | 0xFFFFFFFFull;
-    if (!accepted) {                        // exact selection on (distance, slot) keys: keeps exactly k
-        auto key_at = [&](int i) { return s.cand[i]; };
-        Tkey = block_select_kth(key_at, n, k, s.hist, s.state);
-        T = (uint32_t)(Tkey >> 32);
+        const uint64_t blo = lo + ((uint64_t)bucket << sh);
+        const uint64_t edge = min(hi, blo + (((uint64_t)1 << sh) - 1u));
+        T = edge;
+        // keeping the whole bucket is within the slack (always so once a bucket is a single key)
+        if (kept_below + before + inb <= (unsigned)(k + kKeepSlack) || sh == 0) break;
+        kept_below += before; need -= before; lo = blo; hi = edge;       // look inside the bucket
     }
     if (tid == 0) s.misc[0] = 0;
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < kCandPerThread; ++e)
-        if (mine[e] <= Tkey && mine[e] != kSentinel) s.cand[atomicAdd(&s.misc[0], 1u)] = mine[e];
+        if (mine[e] <= T && mine[e] != kSentinel) s.cand[atomicAdd(&s.misc[0], 1u)] = mine[e];
     __syncthreads();
     return T;
 }
@@ -797,7 +789,7 @@ __global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
     __syncthreads();
     const int n = min((int)lds_peek(&s.misc[0]), cap);
     if (n > a.k) {                          // uniform
-        const uint32_t T = wg_prune(s, n, a.k);
+        const uint32_t T = (uint32_t)(wg_prune(s, n, a.k) >> 32);
         if (tid == 0) a.thr[qi] = T;        // plan_query set "no bound"; the scan only lowers it from here
     }
 }
@@ -840,9 +832,9 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x;
-    const int4 desc = a.desc[wg];                            // (query, first block, end block, 0)
+    const int4 desc = a.desc[wg];                            // (query, number among its workgroups, their count, 0)
     if (desc.x < 0) return;                                  // spare workgroup (uniform exit)
-    const int qi = desc.x, b_begin = desc.y, b_end = desc.z;
+    const int qi = desc.x;
     const bool lut_at_zero =
         reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
 #ifdef PIPERAG_TRACE
@@ -858,30 +850,50 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     store_probe_tables(a, s, tables);
     __syncthreads();
 
-    uint32_t thr = 0xFFFFFFFFu;     // best known bound on the k-th best distance (bits)
-    const int trigger = cap - kScanWaves * NSETS * kBlockVecs;
+    // Best known bound on the k-th best key: the workgroup's own (a key, from its last pruning) or the query's
+    // (a distance, which admits every slot).  A bound with a slot part matters when many vectors share the
+    // k-th best distance: without it all of them would pass and be pruned away again and again.
+    uint64_t thr = ~0ull;
+    const int trigger = cap - kScanThreads;
     const int lane_m = lane % MP;
     uint32_t off4[16];
     make_off4(off4, lane);
 
-    int b_next = b_begin + wave;    // next block this wave will request
-    int pi = 0;                     // probe whose list holds b_next (advanced monotonically)
+    // The query's blocks (numbered along its probed lists) are handed out in chunks of kChunkBlocks to the
+    // waves of all its workgroups: the first chunk of a wave is the one of its own number, later ones come from
+    // the query's counter, asked for one chunk ahead so that the answer is there when it is needed.  A slow
+    // workgroup (pruning, a busy memory channel) simply takes fewer chunks.
+    const int TB = s.pfx[a.nprobe];                          // blocks of this query
+    // (the zero below is lane-dependent as far as the compiler can tell: an address it knows to be the same in
+    // all lanes makes it combine the lanes' additions and fetch the answer at once, which would wait for every
+    // load in flight)
+    uint32_t *ctr = a.ctr + (size_t)qi * kCtrStride + __builtin_amdgcn_mbcnt_lo(0u, 0u);
+    int pi = 0;                     // probe whose list holds the block looked up last (chunks only move forward)
+    auto ask_chunk = [&]() -> uint32_t {
+        uint32_t c = 0;
+        if (lane == 0) c = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return c;                   // lane 0 holds the answer once the load counter says so
+    };
 
-    // Every call issues the same number of loads, whether or not the wave still has a block to fetch (a wave
-    // out of blocks re-reads a few bytes of block 0, which always exists): the compiler can then count the
-    // loads in flight exactly and lets NSETS - 1 later requests stay in flight while one block is worked on.
+    // Every call issues the same number of loads, whether or not block b exists (beyond the end a wave re-reads
+    // a few bytes of block 0, which always exists): the compiler can then count the loads in flight exactly
+    // and lets NSETS - 1 later requests stay in flight while one block is worked on.
     struct Meta { uint32_t gblock; int nvalid; uint32_t tg; bool valid; };
     const uint4 *idle = reinterpret_cast<const uint4 *>(a.codes);
-    auto issue = [&](uint4 (&w)[C], Meta &m) {
-        m.valid = b_next < b_end;
+    auto issue = [&](uint4 (&w)[C], Meta &m, int b) {
+        m.valid = b < TB;
         const uint4 *src = idle;
         if (m.valid) {
-            while (b_next >= s.pfx[pi + 1]) ++pi;             // b_next < TB = pfx[nprobe], so pi stays < nprobe
-            const int bl = b_next - s.pfx[pi];
+            for (;;) {              // lanes look at the next 64 prefix sums at once; b < TB = pfx[nprobe] bounds pi
+                const int32_t e = s.pfx[min(pi + 1 + lane, a.nprobe)];
+                const int adv = __popcll(__ballot(b >= e));
+                pi += adv;
+                if (adv < kWave) break;
+            }
+            const int bl = b - s.pfx[pi];
             m.gblock = (uint32_t)(s.blk[pi] + bl);
             m.nvalid = s.len[pi] - bl * kBlockVecs;           // >= 1; lanes >= nvalid hold padding
             src = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP) + lane;
-            b_next += kScanWaves;
         }
 #pragma unroll
         for (int c = 0; c < C; ++c) w[c] = src[c * kWave];
@@ -900,44 +912,32 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
         else dist = block_dist_generic<C>(w, s.lut, lane_m);
         const uint32_t dbits = __float_as_uint(dist);
-        thr = min(thr, m.tg);
-        bool pass = (lane < m.nvalid) && (dbits <= thr);
+        thr = min(thr, ((uint64_t)m.tg << 32) | 0xFFFFFFFFull);
+        const uint32_t slot = m.gblock * kBlockVecs + lane;
+        bool pass = (lane < m.nvalid) && ((((uint64_t)dbits << 32) | slot) <= thr);
 #ifdef PIPERAG_TRACE
         if (a.flags & 1) pass = false;
 #endif
-        append_candidates(pass, dbits, m.gblock * kBlockVecs + lane, s.cand, &s.misc[0], cap, lane);
+        append_candidates(pass, dbits, slot, s.cand, &s.misc[0], cap, lane);
     };
 
     uint4 w[NSETS][C];
     Meta meta[NSETS];
+    int cb = (desc.y * kScanWaves + wave) * kChunkBlocks;    // first block of the chunk being requested
+    uint32_t pending = ask_chunk();
 #pragma unroll
-    for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i]);
+    for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i], cb + i);
     lut_copy_end<kScanThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
     __syncthreads();
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[1] = wall_clock64();
 #endif
-    bool announced = false;         // this wave has told the others that it is out of blocks
-    for (;;) {
-        // the count is looked at once per NSETS blocks; until every wave has looked again, each of them appends
-        // at most NSETS * 64 keys, which is the room the trigger leaves
-        const bool hold = (int)lds_peek(&s.misc[0]) > trigger;
-        bool any = false;           // this wave still holds a requested block
-#pragma unroll
-        for (int i = 0; i < NSETS; ++i) any |= meta[i].valid;
-        if (!hold && any) {
-#pragma unroll
-            for (int i = 0; i < NSETS; ++i) {
-                if (meta[i].valid) process(w[i], meta[i]);
-                issue(w[i], meta[i]);
-            }
-            continue;
-        }
-        // buffer nearly full, or this wave is out of blocks: meet the other waves
-        if (!any && !announced) {
-            announced = true;
-            if (lane == 0) atomicAdd(&s.misc[3], 1u);
-        }
+    // An episode is a meeting of all waves of the workgroup: every wave joins every episode (from wherever it
+    // is in its loop), the two counters are read between two barriers (nobody appends in between), and the
+    // buffer is pruned if it is nearly full.  A wave asks for an episode by waiting in one: when the buffer is
+    // nearly full (the others notice at their next block) or when it has run out of blocks.  Returns the
+    // number of waves that are out of blocks.
+    auto episode = [&]() -> int {
         __syncthreads();
         const int n = (int)lds_peek(&s.misc[0]);
         const int ndone = (int)lds_peek(&s.misc[3]);
@@ -946,23 +946,49 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 #ifdef PIPERAG_TRACE
             const unsigned long long tf0 = wall_clock64();
 #endif
-            const uint32_t T = wg_prune(s, min(n, cap), k);
+            const uint64_t T = wg_prune(s, min(n, cap), k);
             thr = min(thr, T);
-            if (tid == 0) atomicMin(&a.thr[qi], T);
+            if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
 #ifdef PIPERAG_TRACE
             tflush += wall_clock64() - tf0;
             ++nflush;
 #endif
         }
-        if (ndone == kScanWaves) break;
+        return ndone;
+    };
+    // One turn of the loop works through kChunkBlocks blocks; request number NSETS + j (counted from the wave's
+    // first) is made at step j, so the step at which the next chunk begins is the same in every turn.
+    static_assert(kChunkBlocks % NSETS == 0, "a chunk is a whole number of rounds over the register sets");
+    for (;;) {
+        bool any = false;           // this wave still holds a requested block
+#pragma unroll
+        for (int i = 0; i < NSETS; ++i) any |= meta[i].valid;
+        if (!any) break;            // chunks only move forward: nothing valid in flight means nothing is left
+#pragma unroll
+        for (int j = 0; j < kChunkBlocks; ++j) {
+            const int i = j % NSETS, pos = (NSETS + j) % kChunkBlocks;   // position of the request within its chunk
+            if (pos == 0) {
+                cb = (int)min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / kChunkBlocks - 1u) * kChunkBlocks;
+                pending = ask_chunk();
+            }
+            if (meta[i].valid) {
+                // the count is looked at before every block; a wave appends at most 64 keys per block
+                while ((int)lds_peek(&s.misc[0]) > trigger) episode();
+                process(w[i], meta[i]);
+            }
+            issue(w[i], meta[i], cb + pos);
+        }
     }
+    // out of blocks: tell the others, and keep joining their episodes until every wave is out of blocks
+    if (lane == 0) atomicAdd(&s.misc[3], 1u);
+    while (episode() != kScanWaves) {}
 #ifdef PIPERAG_TRACE
-    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)(b_end - b_begin); tr[7] = tflush; }
+    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)TB; tr[7] = tflush; }
 #endif
     int n = min((int)lds_peek(&s.misc[0]), cap);
     if (n > KW) {                   // uniform
-        const uint32_t T = wg_prune(s, n, k);
-        if (tid == 0) atomicMin(&a.thr[qi], T);
+        const uint64_t T = wg_prune(s, n, k);
+        if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
         n = (int)lds_peek(&s.misc[0]);
     }
 #ifdef PIPERAG_TRACE
@@ -1220,11 +1246,11 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
                            ix->list_blk, ix->list_len, plan_bufs(ix));
     const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
     hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, ix->ws_seg0,
-                       ix->ws_desc);
+                       ix->ws_desc, ix->ws_ctr);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
     ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
-               nprobe, pstride, k, KW};
+               ix->ws_ctr, nprobe, pstride, k, KW};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));

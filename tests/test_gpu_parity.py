@@ -353,3 +353,26 @@ def test_long_lists_exercise_the_in_loop_candidate_pruning():
     for k in (1, 100, 128):                     # ~29 blocks per workgroup, 16 per round: pruned in the first round
         run_search_parity(pkg, ix, oidx, q, 4, k)
     run_search_parity(pkg, ix, oidx, q[:1], 2, 100)
+
+
+def test_many_vectors_with_identical_codes_tie_at_the_kth_distance():
+    # a database of few distinct vectors, each repeated thousands of times: far more than k candidates share
+    # every distance, so the bound on the k-th best distance alone never excludes them (ties are cut by slot)
+    pkg = P()
+    rng = np.random.default_rng(5)
+    base = rng.standard_normal((48, 64)).astype(np.float32)
+    x = base[rng.integers(0, 48, size=150000)]
+    q = (base[:12] + 0.05 * rng.standard_normal((12, 64))).astype(np.float32)
+    coarse = base[:4].copy()
+    pq = np.ascontiguousarray(rng.standard_normal((8, 256, 8)).astype(np.float32))
+    for m in range(8):
+        pq[m, :48] = base[:, 8 * m:8 * m + 8]              # every distinct vector is encoded exactly
+    oidx = oracle.make_index(x, coarse, pq)
+    assert len(np.unique(oidx.codes, axis=0)) <= 48
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=4, max_k=128)
+    for k in (1, 100, 128):
+        ex_p, ex_k, _ = run_search_parity(pkg, ix, oidx, q, 4, k)
+        # which of the tied vectors are returned is decided by position, not id: most queries are "excused"
+    od, oi = ix.ivfpq_search(dev(q), 4, 100)
+    od2, oi2 = ix.ivfpq_search(dev(q), 4, 100)
+    assert torch.equal(od, od2) and torch.equal(oi, oi2)   # and the choice is deterministic
