@@ -152,6 +152,55 @@ def stored_traffic(workload):
     return None
 
 
+def exact_knn(g, cfg, torch, q, k, tile_rows=262144):
+    """Harness only (not the library, not the oracle): exact squared-L2 top-k of the queries over the whole
+    synthetic database, regenerated tile by tile and compared with torch matrix products."""
+    nq = q.shape[0]
+    best_d = torch.full((nq, k), float("inf"), device="cuda")
+    best_i = torch.full((nq, k), -1, dtype=torch.int64, device="cuda")
+    qn = (q * q).sum(1, keepdim=True)
+    buf = torch.empty((min(tile_rows, cfg.N), cfg.d), dtype=torch.float32, device="cuda")
+    for a in range(0, cfg.N, tile_rows):
+        n = min(tile_rows, cfg.N - a)
+        x = g.database(a, n, out=buf)[:n]
+        dist = qn + (x * x).sum(1)[None, :] - 2.0 * (q @ x.T)
+        d, i = torch.topk(dist, min(k, n), dim=1, largest=False)
+        cd, ci = torch.cat([best_d, d], 1), torch.cat([best_i, i + a], 1)
+        best_d, sel = torch.topk(cd, k, dim=1, largest=False)
+        best_i = torch.gather(ci, 1, sel)
+    return best_i
+
+
+def nprobe_sweep(args, pkg, cfg, torch):
+    """Latency against nprobe (single query and batch of 8, p50 of `reps` searches per point, with the linear
+    fit latency = a + b * nprobe of Section 3.3's performance model) and recall@k of 1,000 queries against the
+    exact neighbours, for nprobe = 1, 2, 4, ... up to the configuration's nprobe."""
+    nprobes = [p for p in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if p <= cfg.nprobe]
+    ix, g, info = build_index(pkg, cfg, torch, max_nq=64, max_nprobe=max(nprobes))
+    nrec = 1000
+    q = g.queries(nrec)
+    p50_1, fit_1 = ix.latency_profile(q[:1].contiguous(), nprobes, cfg.k, reps=50)
+    p50_8, fit_8 = ix.latency_profile(q[:8].contiguous(), nprobes, cfg.k, reps=50)
+    log("[sweep] exact neighbours of the recall queries (torch harness)")
+    truth = exact_knn(g, cfg, torch, q, cfg.k).cpu().numpy()
+    rows = []
+    for j, p in enumerate(nprobes):
+        hits = 0
+        for a in range(0, nrec, 64):
+            _, oi = ix.ivfpq_search(q[a:a + 64].contiguous(), p, cfg.k)
+            got = oi.cpu().numpy()
+            hits += sum(len(np.intersect1d(got[r], truth[a + r])) for r in range(got.shape[0]))
+        rows.append({"nprobe": p, "p50_ms_nq1": float(p50_1[j]), "p50_ms_nq8": float(p50_8[j]), "recall": hits / (nrec * cfg.k)})
+        log(f"[sweep] nprobe {p}: {rows[-1]}")
+    print(f"| nprobe | p50 ms (nq=1) | p50 ms (nq=8) | recall@{cfg.k} |")
+    print("|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['nprobe']} | {r['p50_ms_nq1']:.4f} | {r['p50_ms_nq8']:.4f} | {r['recall']:.4f} |")
+    print(json.dumps({"workload": cfg.name, "k": cfg.k, "recall_queries": nrec, "reps": 50, "rows": rows,
+                      "fit_nq1_ms": {"a": float(fit_1[0]), "b": float(fit_1[1])},
+                      "fit_nq8_ms": {"a": float(fit_8[0]), "b": float(fit_8[1])}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +211,8 @@ def main():
     ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB copy kernel three times (reference for the HBM traffic counters)")
+    ap.add_argument("--nprobe-sweep", action="store_true",
+                    help="instead of the bench line: latency and recall against nprobe on the chosen workload (meant for cfg2)")
     ap.add_argument("--summarize", metavar="DIR", help="write a text summary of rocprofv3 CSV output found under DIR and exit")
     ap.add_argument("--command", default="", help="with --summarize: the command line that produced DIR")
     args = ap.parse_args()
@@ -179,6 +230,9 @@ def main():
     pkg.load_library()                      # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = gen.CONFIGS[args.workload]
+    if args.nprobe_sweep:
+        nprobe_sweep(args, pkg, cfg, torch)
+        return
     log(f"[bench] building {cfg.name}: N={cfg.N} d={cfg.d} nlist={cfg.nlist} M={cfg.M}")
     ix, g, info = build_index(pkg, cfg, torch, max_nq=max(cfg.nq, 1))
     log(f"[bench] train {info['train_s']:.1f}s encode {info['encode_s']:.1f}s finalize {info['finalize_s']:.1f}s")

@@ -20,7 +20,8 @@ constexpr int kScanThreads = 256;  // 4 waves per scan workgroup
 constexpr int kScanWaves = kScanThreads / kWave;
 constexpr int kTargetScanWGs = 512;    // scan workgroups per search call: two per compute unit, all resident at once
 constexpr int kMaxSegments = 1024;
-constexpr int kCtrStride = 32;         // counters of different queries sit 128 bytes apart
+constexpr int kCtrStride = 32;         // chunk counters sit 128 bytes apart
+constexpr int kCtrPerQuery = 16;       // at most this many chunk counters share out one query's blocks
 constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
 constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
@@ -90,7 +91,7 @@ struct piperag_index {
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
     int4 *ws_desc;        // [2*kTargetScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
-    uint32_t *ws_ctr;     // [max_nq*kCtrStride] next chunk of blocks of each query (one counter per 128 bytes)
+    uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
     int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
     float *ws_qn;         // [max_nq] squared norms of the queries

@@ -214,7 +214,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_pfx, (size_t)p.max_nq * (p.max_nprobe + 1))) ||
         (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) || (rc = dev_alloc(&ix->ws_thr, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_desc, 2 * (size_t)kTargetScanWGs + p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
+        (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
         (rc = dev_alloc(&ix->ws_part, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||

@@ -378,9 +378,14 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
             if (seg0[mid] <= w) lo = mid; else hi = mid;
         }
         const int seg = w - seg0[lo], S = seg0[lo + 1] - seg0[lo];
-        desc[w] = int4{lo, seg, S, 0};
-        // every wave of the query's workgroups starts on the chunk of its own number; the counter hands out the rest
-        if (seg == 0) ctr[(size_t)lo * kCtrStride] = (uint32_t)S * kScanWaves;
+        // The query's chunks are dealt to P counters (chunk c belongs to counter c mod P) and its waves likewise
+        // (wave g of the query draws from counter g mod P), so that the additions of a query with many
+        // workgroups do not all queue up at one address.  Every wave starts on the chunk of its own number;
+        // counter p then hands out P * v + p for v = the number of starting chunks it covers, and up.
+        const int W = S * kScanWaves, P = min(kCtrPerQuery, max(1, S / 4));
+        desc[w] = int4{lo, seg, S, P};
+        if (seg == 0)
+            for (int c = 0; c < P; ++c) ctr[((size_t)lo * kCtrPerQuery + c) * kCtrStride] = (uint32_t)((W - c + P - 1) / P);
     }
 }
 
@@ -395,9 +400,10 @@ struct ScanArgs {
     const int32_t *plen;       // [nq][probe_stride] length of each probed list
     uint64_t *part;            // [workgroups][KW] partial results
     uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
-    const int4 *desc;          // [workgroups] (query, number among the query's workgroups, their count, 0); query -1: spare
-    uint32_t *ctr;             // [nq * kCtrStride] next chunk of each query's blocks to hand out
+    const int4 *desc;          // [workgroups] (query, number among the query's workgroups, their count, counters in use); query -1: spare
+    uint32_t *ctr;             // [nq * kCtrPerQuery * kCtrStride] chunk counters of each query
     int nprobe, probe_stride, k, KW;
+    int cap;                   // scan only: slots of the workgroup's candidate buffer
 #ifdef PIPERAG_TRACE
     unsigned long long *trace;   // [workgroups][8] timestamps
     int flags;                   // experiments: 1 = no appends, 2 = no table lookups
@@ -407,7 +413,8 @@ struct ScanArgs {
 typedef const __attribute__((address_space(3))) float *lds_cfptr;
 
 constexpr int kKeepSlack = 64;                        // pruning keeps between k and k + kKeepSlack candidates
-constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack
+constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack, at most
+constexpr int kCandRoomMin = 512;                     // and at least (the scan needs more than kScanThreads)
 constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
 constexpr int kPrimeBlocks = 32;                      // blocks of the closest lists scanned to prime the bound
 constexpr int kChunkBlocks = 4;                       // consecutive blocks a scan wave takes at a time
@@ -827,12 +834,11 @@ template <int C, int NSETS>
 __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     constexpr int MP = 16 * C;
     extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
-    const int k = a.k, KW = a.KW;
-    const int cap = KW + kCandRoom;
+    const int k = a.k, KW = a.KW, cap = a.cap;
     const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x;
-    const int4 desc = a.desc[wg];                            // (query, number among its workgroups, their count, 0)
+    const int4 desc = a.desc[wg];                            // (query, number among its workgroups, their count, counters)
     if (desc.x < 0) return;                                  // spare workgroup (uniform exit)
     const int qi = desc.x;
     const bool lut_at_zero =
@@ -867,7 +873,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // (the zero below is lane-dependent as far as the compiler can tell: an address it knows to be the same in
     // all lanes makes it combine the lanes' additions and fetch the answer at once, which would wait for every
     // load in flight)
-    uint32_t *ctr = a.ctr + (size_t)qi * kCtrStride + __builtin_amdgcn_mbcnt_lo(0u, 0u);
+    const int wave_of_query = desc.y * kScanWaves + wave, nctr = desc.w, my_ctr = wave_of_query % nctr;
+    uint32_t *ctr = a.ctr + ((size_t)qi * kCtrPerQuery + my_ctr) * kCtrStride + __builtin_amdgcn_mbcnt_lo(0u, 0u);
     int pi = 0;                     // probe whose list holds the block looked up last (chunks only move forward)
     auto ask_chunk = [&]() -> uint32_t {
         uint32_t c = 0;
@@ -923,7 +930,7 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 
     uint4 w[NSETS][C];
     Meta meta[NSETS];
-    int cb = (desc.y * kScanWaves + wave) * kChunkBlocks;    // first block of the chunk being requested
+    int cb = wave_of_query * kChunkBlocks;                   // first block of the chunk being requested
     uint32_t pending = ask_chunk();
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i], cb + i);
@@ -968,7 +975,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         for (int j = 0; j < kChunkBlocks; ++j) {
             const int i = j % NSETS, pos = (NSETS + j) % kChunkBlocks;   // position of the request within its chunk
             if (pos == 0) {
-                cb = (int)min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / kChunkBlocks - 1u) * kChunkBlocks;
+                const uint32_t v = min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / (kChunkBlocks * kCtrPerQuery) - 1u);
+                cb = (int)(v * nctr + my_ctr) * kChunkBlocks;
                 pending = ask_chunk();
             }
             if (meta[i].valid) {
@@ -1250,7 +1258,7 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
     ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
-               ix->ws_ctr, nprobe, pstride, k, KW};
+               ix->ws_ctr, nprobe, pstride, k, KW, 0};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
@@ -1263,7 +1271,15 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     PR_DISPATCH_C(launch_prime, ix, nq, a, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
-    const size_t lds = scan_lds_bytes(ix->Mp, KW + kCandRoom, nprobe);
+    // Candidate slots: as many as kCandRoom beyond the keys kept, but fewer if that lets two workgroups share a
+    // compute unit's 160 KiB of LDS (long probe tables would otherwise push the second one out).
+    int room = kCandRoom;
+    {
+        const size_t half = 80 * 1024, fixed = scan_lds_bytes(ix->Mp, KW, nprobe);
+        if (fixed + 8 * (size_t)kCandRoom > half && fixed + 8 * (size_t)kCandRoomMin <= half) room = (int)((half - fixed) / 8);
+    }
+    a.cap = KW + room;
+    const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
     PR_DISPATCH_C(launch_scan, a, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
