@@ -91,6 +91,8 @@ struct piperag_index {
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
     int4 *ws_desc;        // [2*kTargetScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
+    uint64_t *ws_part2;   // same shape as ws_part: keys kept by groups of scan workgroups (merge inside the scan kernel)
+    uint32_t *ws_done;    // [2*kTargetScanWGs+2*max_nq] counters of that merge
     uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
     int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list

@@ -217,6 +217,8 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
         (rc = dev_alloc(&ix->ws_part, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
+        (rc = dev_alloc(&ix->ws_part2, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
+        (rc = dev_alloc(&ix->ws_done, 2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->ws_qn, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
@@ -288,7 +290,7 @@ void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
     void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
-                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_out_d, ix->ws_out_i, ix->flag};
+                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restri
 // needlessly many workgroups.
 __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
                                                     int target, int max_wg, int32_t *__restrict__ seg0, int4 *__restrict__ desc,
-                                                    uint32_t *__restrict__ ctr) {
+                                                    uint32_t *__restrict__ ctr, uint32_t *__restrict__ done) {
     __shared__ long long s_total;
     __shared__ int32_t s_scan[256];
     __shared__ int32_t s_carry;
@@ -370,6 +370,7 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
     if (tid == 0) seg0[nq] = s_carry;
     __syncthreads();
     const int total_wg = s_carry;
+    for (int w = tid; w < max_wg + nq; w += 256) done[w] = 0;   // merge counters: per group of workgroups, then per query
     for (int w = tid; w < max_wg; w += 256) {
         if (w >= total_wg) { desc[w] = int4{-1, 0, 0, 0}; continue; }
         int lo = 0, hi = nq;                               // query of workgroup w: last q with seg0[q] <= w
@@ -404,6 +405,14 @@ struct ScanArgs {
     uint32_t *ctr;             // [nq * kCtrPerQuery * kCtrStride] chunk counters of each query
     int nprobe, probe_stride, k, KW;
     int cap;                   // scan only: slots of the workgroup's candidate buffer
+    // scan only, merge inside the scan kernel (fan > 0): the last workgroup to finish of every `fan` consecutive
+    // workgroups of a query reduces their keys to k, and the last such group of the query produces the result
+    int fan;
+    uint64_t *part2;           // [workgroups][KW] keys kept by the groups
+    uint32_t *done;            // [workgroups + nq] finished workgroups per group, finished groups per query (zeroed by the plan)
+    const int64_t *ids;
+    float *out_d;
+    int64_t *out_i;
 #ifdef PIPERAG_TRACE
     unsigned long long *trace;   // [workgroups][8] timestamps
     int flags;                   // experiments: 1 = no appends, 2 = no table lookups
@@ -815,6 +824,99 @@ __global__ __launch_bounds__(256) void lut_tap_kernel(const float *__restrict__ 
     out[((size_t)qi * M + m) * kKsub + j] = acc;
 }
 
+// Keys that one workgroup writes and another reads within the same launch go through device-scope atomic
+// stores and loads (they bypass the per-XCD caching that is not coherent across the chip), ordered by
+// publish_keys(): wait until this thread's stores are acknowledged, then meet the workgroup; a counter
+// increment after that tells the others.  No cache-wide write-back or invalidation is involved (a full fence
+// by every finishing workgroup costs far more than the merge itself).
+__device__ __forceinline__ void store_key(uint64_t *p, uint64_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint64_t load_key(const uint64_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void publish_keys() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): loads and stores of this thread are complete
+    __syncthreads();
+}
+
+// Reduction of `count` partial key arrays (KW slots each, consecutive in src; unused slots hold kSentinel) by
+// one workgroup: the keys within the bound are gathered into s_keys (the caller guarantees count * KW <=
+// room there) and the k smallest selected.  FINAL = false: they are written to dst[0..KW) (unsorted, padded
+// with kSentinel).  FINAL = true: ids are looked up and the results written to out_d / out_i, sorted by
+// (distance, id) and padded with (+inf, -1); s_d / s_id: power-of-two >= k slots.
+template <bool FINAL>
+__device__ void reduce_partials(const uint64_t *__restrict__ src, int count, int KW, int k, uint32_t bound, uint64_t *s_keys,
+                                unsigned *s_hist, unsigned long long *s_state, unsigned *s_count, uint64_t *__restrict__ dst,
+                                const int64_t *__restrict__ ids, uint32_t *s_d, int64_t *s_id, float *__restrict__ out_d,
+                                int64_t *__restrict__ out_i) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int n = count * KW;
+    const int k2 = max(2, 1 << (32 - __clz(k - 1)));
+    if (FINAL)
+        for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
+    if (tid == 0) *s_count = 0;
+    __syncthreads();
+    for (int i0 = tid; i0 < n; i0 += 8 * nt) {                   // 8 loads in flight per thread, then the appends
+        uint64_t key[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) key[j] = i0 + j * nt < n ? load_key(src + i0 + j * nt) : kSentinel;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound) s_keys[atomicAdd(s_count, 1u)] = key[j];
+    }
+    __syncthreads();
+    const int found = (int)*s_count;
+    __syncthreads();
+    uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
+    if (found > k) {
+        auto key_at = [&](int i) { return s_keys[i]; };
+        T = block_select_kth(key_at, found, k, s_hist, s_state);
+    }
+    if (tid == 0) *s_count = 0;
+    __syncthreads();
+    for (int i = tid; i < found; i += nt) {
+        const uint64_t key = s_keys[i];
+        if (key <= T) {                                          // min(found, k) keys qualify (keys are distinct)
+            const unsigned slot = atomicAdd(s_count, 1u);
+            if (FINAL) { s_d[slot] = (uint32_t)(key >> 32); s_id[slot] = ids[(uint32_t)key]; }
+            else store_key(dst + slot, key);
+        }
+    }
+    __syncthreads();
+    const int cnt = (int)*s_count;
+    if (!FINAL) {
+        for (int i = cnt + tid; i < KW; i += nt) store_key(dst + i, kSentinel);
+        return;
+    }
+    // bitonic sort of (distance bits, id) pairs; up to 128 of them are sorted by one wavefront, whose lanes run
+    // in lockstep and need no workgroup barriers between the steps
+    const bool one_wave = k2 <= 2 * kWave;
+    for (int size = 2; size <= k2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            if (one_wave) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); else __syncthreads();
+            for (int i = tid; i < (k2 >> 1) && (!one_wave || tid < kWave); i += nt) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint32_t da = s_d[lo], db = s_d[hi];
+                const int64_t ia = s_id[lo], ib = s_id[hi];
+                const bool gt = da > db || (da == db && ia > ib);
+                if (gt == up) { s_d[lo] = db; s_d[hi] = da; s_id[lo] = ib; s_id[hi] = ia; }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < k; i += nt) {
+        out_d[i] = i < cnt ? __uint_as_float(s_d[i]) : __builtin_inff();
+        out_i[i] = i < cnt ? s_id[i] : -1;
+    }
+}
+
+// Room for keys when the table and candidate areas of the scan kernel's LDS are reused for the reduction above
+// (after s_id and s_d for the final step).
+__host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
+    const int k2 = k <= 2 ? 2 : 1 << (32 - __builtin_clz((unsigned)(k - 1)));
+    return (1024 * Mp + 8 * cap - 12 * k2) / 8;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Stage 3: scan of the probed lists with candidate selection.
 // The probed lists of a query, concatenated in probe order, form a sequence of 64-vector blocks; the plan
@@ -1003,10 +1105,46 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     if (tid == 0) tr[3] = wall_clock64();
 #endif
     uint64_t *out = a.part + (size_t)wg * KW;
-    for (int i = tid; i < KW; i += kScanThreads) out[i] = i < n ? s.cand[i] : kSentinel;
+    for (int i = tid; i < KW; i += kScanThreads) store_key(out + i, i < n ? s.cand[i] : kSentinel);
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[4] = wall_clock64();
 #endif
+    if (a.fan <= 0) return;         // the merge kernel takes over
+    // Merge inside this kernel.  A workgroup's keys are published before it adds itself to its group's counter;
+    // whoever sees the count complete may read them all.
+    const int seg = desc.y, S = desc.z, wg0 = wg - seg;          // wg0: the query's first workgroup
+    const int r = seg / a.fan, gsize = min(a.fan, S - r * a.fan), R = (S + a.fan - 1) / a.fan;
+    const int k2 = max(2, 1 << (32 - __clz(k - 1)));
+    int64_t *s_id = reinterpret_cast<int64_t *>(smem);
+    uint32_t *s_d = reinterpret_cast<uint32_t *>(s_id + k2);
+    uint64_t *s_keys = reinterpret_cast<uint64_t *>(smem + 12 * (size_t)k2);
+    float *res_d = a.out_d + (size_t)qi * k;
+    int64_t *res_i = a.out_i + (size_t)qi * k;
+    publish_keys();
+    if (tid == 0) s.misc[4] = atomicAdd(&a.done[wg0 + r], 1u);
+    __syncthreads();
+#ifdef PIPERAG_TRACE
+    if (tid == 0 && (a.flags & 4)) tr[5] = wall_clock64();
+#endif
+    if (s.misc[4] != (unsigned)(gsize - 1)) return;              // uniform
+    uint32_t bound = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (R == 1) {
+        reduce_partials<true>(a.part + (size_t)wg0 * KW, S, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, a.ids,
+                              s_d, s_id, res_d, res_i);
+#ifdef PIPERAG_TRACE
+        if (tid == 0 && (a.flags & 4)) tr[6] = wall_clock64();
+#endif
+        return;
+    }
+    reduce_partials<false>(a.part + (size_t)(wg0 + r * a.fan) * KW, gsize, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0],
+                           a.part2 + (size_t)(wg0 + r) * KW, nullptr, nullptr, nullptr, nullptr, nullptr);
+    publish_keys();
+    if (tid == 0) s.misc[4] = atomicAdd(&a.done[gridDim.x + qi], 1u);
+    __syncthreads();
+    if (s.misc[4] != (unsigned)(R - 1)) return;                  // uniform
+    bound = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    reduce_partials<true>(a.part2 + (size_t)wg0 * KW, R, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, a.ids, s_d,
+                          s_id, res_d, res_i);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1254,11 +1392,11 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
                            ix->list_blk, ix->list_len, plan_bufs(ix));
     const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
     hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, ix->ws_seg0,
-                       ix->ws_desc, ix->ws_ctr);
+                       ix->ws_desc, ix->ws_ctr, ix->ws_done);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
     ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
-               ix->ws_ctr, nprobe, pstride, k, KW, 0};
+               ix->ws_ctr, nprobe, pstride, k, KW};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
@@ -1279,13 +1417,23 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
         if (fixed + 8 * (size_t)kCandRoom > half && fixed + 8 * (size_t)kCandRoomMin <= half) room = (int)((half - fixed) / 8);
     }
     a.cap = KW + room;
+    // The merge runs inside the scan kernel when two levels of reduction in its LDS cover any number of
+    // workgroups a query can get; otherwise (very large k with short codes) the merge kernel does it.
+    const int fan = reduce_room_keys(ix->Mp, a.cap, k) / KW;
+    // It pays when a query is spread over many workgroups (one merge workgroup per query would then have to
+    // read thousands of keys alone); with few workgroups per query the separate kernel's 1024 threads are as
+    // fast and keep the scan kernel's tail short.
+    const bool fused = fan >= 2 && (long long)fan * fan >= G && nq * 16 <= target_wgs;
+    a.fan = fused ? fan : 0;
+    a.part2 = ix->ws_part2; a.done = ix->ws_done; a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
     const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
     PR_DISPATCH_C(launch_scan, a, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[4], st));
-    hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, ix->ws_seg0, KW, k, ix->ids, ix->ws_thr, out_d,
-                       out_i);
+    if (!fused)
+        hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, ix->ws_seg0, KW, k, ix->ids, ix->ws_thr,
+                           out_d, out_i);
     if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[5], st)); ix->ev_valid = true; }
     ix->last_nq = nq;
     PR_CHECK_HIP(hipGetLastError());

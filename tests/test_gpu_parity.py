@@ -353,6 +353,9 @@ def test_long_lists_exercise_the_in_loop_candidate_pruning():
     for k in (1, 100, 128):                     # ~29 blocks per workgroup, 16 per round: pruned in the first round
         run_search_parity(pkg, ix, oidx, q, 4, k)
     run_search_parity(pkg, ix, oidx, q[:1], 2, 100)
+    # one query spread over more than a hundred workgroups: their keys are merged in two levels
+    run_search_parity(pkg, ix, oidx, q[:1], 4, 100)
+    run_search_parity(pkg, ix, oidx, q[:2], 4, 1)
 
 
 def test_many_vectors_with_identical_codes_tie_at_the_kth_distance():
