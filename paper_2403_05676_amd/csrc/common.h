@@ -28,7 +28,9 @@ constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);   // squared row norms
-void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st);   // bf16 hi / lo parts
+// bf16 hi / lo parts of n rows of d values in the encoder's chunk-major layout; each part holds split_bf16_elems(n, d) elements
+void split_bf16(const float *src, int64_t n, int d, uint16_t *hi, uint16_t *lo, hipStream_t st);
+size_t split_bf16_elems(int64_t n, int d);
 
 #define PR_CHECK_HIP(expr)                                                                     \
     do {                                                                                       \
@@ -65,7 +67,7 @@ struct piperag_index {
     // trained parameters (device)
     float *centroids;  // [nlist*d]
     float *cnorm;      // [nlist] squared norms of the centres
-    uint16_t *cent_hi, *cent_lo;   // [nlist*d] bf16 split of the centres for the encoder (NULL when the shape rules it out)
+    uint16_t *cent_hi, *cent_lo;   // bf16 split of the centres for the encoder, chunk-major (NULL when the shape rules it out)
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize

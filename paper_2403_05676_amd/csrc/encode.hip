@@ -14,7 +14,6 @@ namespace piperag {
 int check_can_add(piperag_index *ix, int64_t n);
 int append_ids(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStream_t st);
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);
-void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st);
 }  // namespace piperag
 
 namespace {
@@ -240,70 +239,90 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const float *__restric
 }
 
 // rows of x (stride ldx floats) against K centres; 16-byte loads only when every row start is 16-byte aligned
-// bf16 hi / lo parts of an fp32 array (see mfma_bf16x3.h).
-__global__ void split_bf16_kernel(const float *__restrict__ src, int64_t n, uint16_t *__restrict__ hi, uint16_t *__restrict__ lo) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float v = src[i];
-    const __bf16 h = (__bf16)v;
-    const __bf16 l = (__bf16)(v - (float)h);
-    hi[i] = __builtin_bit_cast(uint16_t, h);
-    lo[i] = __builtin_bit_cast(uint16_t, l);
+// bf16 hi / lo parts of an fp32 matrix (n rows of d values, stride ld) in the chunk-major layout of
+// mfma_bf16x3.h; one thread per (row, chunk of 8 values), padding rows and chunks are written as zeros.
+__global__ void split_bf16_kernel(const float *__restrict__ src, int64_t n, int d, int64_t ld, int64_t rows_pad, int nchunks,
+                                  uint16_t *__restrict__ hi, uint16_t *__restrict__ lo) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rows_pad * nchunks) return;
+    const int64_t row = e / nchunks;
+    const int c = (int)(e % nchunks);
+    uint16_t h[8], l[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int k = c * 8 + t;
+        const float v = (row < n && k < d) ? src[row * ld + k] : 0.f;
+        const __bf16 vh = (__bf16)v;
+        const __bf16 vl = (__bf16)(v - (float)vh);
+        h[t] = __builtin_bit_cast(uint16_t, vh);
+        l[t] = __builtin_bit_cast(uint16_t, vl);
+    }
+    const size_t o = ((size_t)c * rows_pad + row) * 8;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { hi[o + t] = h[t]; lo[o + t] = l[t]; }
 }
 
-// Nearest-centre assignment with the split-bf16 tile product: 256 rows of x per workgroup against the centres
-// 128 at a time; per row the smallest |c|^2 - 2 <x, c> and its centre (lower index on equal values) are
-// kept in LDS by the lane that owns the row in each of the two column halves.  d % 8 == 0, 16-byte aligned rows.
-__global__ __launch_bounds__(256) void assign_bf16x3_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
-                                                            const uint16_t *__restrict__ chi, const uint16_t *__restrict__ clo,
+// Nearest-centre assignment with the split-bf16 tile product: 128 vectors per workgroup against the centres 256
+// at a time.  The centres are the tile's A operand, so a lane holds, for each of its two vector columns, 64
+// centres of the tile in its own registers: the running best (|c|^2 - 2 <x, c>, centre) of a column is kept
+// per lane and compared register by register in ascending centre order (a strict "<" keeps the lower index on
+// equal values); lanes and waves that share a column are combined once at the end.
+__global__ __launch_bounds__(256, 2) void assign_bf16x3_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
+                                                            const uint16_t *__restrict__ xhi, const uint16_t *__restrict__ xlo,
+                                                            int64_t x_rp, const uint16_t *__restrict__ chi,
+                                                            const uint16_t *__restrict__ clo, int64_t c_rp,
                                                             const float *__restrict__ cnorm, int K,
                                                             int32_t *__restrict__ out_idx, float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char bsmem[];
-    float *s_bv = reinterpret_cast<float *>(bsmem + Bf16x3Tile::kLdsBytes);       // [256 rows][2 column halves]
-    int *s_bj = reinterpret_cast<int *>(s_bv + 2 * Bf16x3Tile::kRowsA);
-    const int tid = threadIdx.x, lane = tid & 63, wc = (tid >> 6) & 1;
-    const bool owner = (lane & 31) == 0;
-    const int64_t row0 = (int64_t)blockIdx.x * Bf16x3Tile::kRowsA;
-    if (owner) {
+    float *s_cn = reinterpret_cast<float *>(bsmem + Bf16x3Tile::kLdsBytes);        // [2][256] centre norms of a tile (+inf: no centre)
+    float *s_bv = s_cn + 2 * Bf16x3Tile::kRowsA;                                    // [128 vectors][2 wave rows]
+    int *s_bj = reinterpret_cast<int *>(s_bv + 2 * Bf16x3Tile::kRowsB);
+    const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 7;
+    const int64_t row0 = (int64_t)blockIdx.x * Bf16x3Tile::kRowsB;
+    const int nchunks = Bf16x3Tile::chunks_pad(d);
+    float bv[2] = {__builtin_inff(), __builtin_inff()};
+    int bc[2] = {0, 0};
+    int tile = 0;
+    for (int j0 = 0; j0 < K; j0 += Bf16x3Tile::kRowsA, ++tile) {
+        float *cn = s_cn + (tile & 1) * Bf16x3Tile::kRowsA;    // read after the barriers inside run(); rewritten two tiles later
+        cn[tid] = j0 + tid < K ? cnorm[j0 + tid] : __builtin_inff();
+        acc16_t acc[4][2];
+        Bf16x3Tile::run(chi, clo, c_rp, j0, xhi, xlo, x_rp, row0, nchunks, bsmem, acc);
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = Bf16x3Tile::acc_row(bi, r);
-                s_bv[row * 2 + wc] = __builtin_inff();
-                s_bj[row * 2 + wc] = 0;
+            for (int g = 0; g < 4; ++g) {
+                const int r0 = Bf16x3Tile::acc_row(bi, 4 * g);                     // rows r0 .. r0+3 are registers 4g .. 4g+3
+                const float4 nn = *reinterpret_cast<const float4 *>(cn + r0);
+                const float nv[4] = {nn.x, nn.y, nn.z, nn.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int bj = 0; bj < 2; ++bj) {
+                        const float v = nv[t] - 2.f * acc[bi][bj][4 * g + t];
+                        if (v < bv[bj]) { bv[bj] = v; bc[bj] = j0 + r0 + t; }
+                    }
             }
     }
-    for (int j0 = 0; j0 < K; j0 += Bf16x3Tile::kRowsB) {
-        acc16_t acc[4][2];
-        Bf16x3Tile::run(x, n, ldx, row0, chi, clo, K, d, j0, d, bsmem, acc);
-        const int c0 = j0 + Bf16x3Tile::acc_col(0), c1 = j0 + Bf16x3Tile::acc_col(1);
-        const float n0 = c0 < K ? cnorm[c0] : __builtin_inff(), n1 = c1 < K ? cnorm[c1] : __builtin_inff();
+    // lanes l and l + 32 hold the same columns (different centres), then the two wave rows
 #pragma unroll
-        for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float v0 = n0 - 2.f * acc[bi][0][r], v1 = n1 - 2.f * acc[bi][1][r];
-                float v = v0;
-                int c = c0;
-                if (v1 < v0) { v = v1; c = c1; }
-#pragma unroll
-                for (int off = 1; off < 32; off <<= 1) {      // over the 32 lanes (columns) of this half-wave
-                    const float ov = __shfl_xor(v, off, 64);
-                    const int oc = __shfl_xor(c, off, 64);
-                    if (ov < v || (ov == v && oc < c)) { v = ov; c = oc; }
-                }
-                if (owner) {
-                    const int row = Bf16x3Tile::acc_row(bi, r);
-                    if (v < s_bv[row * 2 + wc]) { s_bv[row * 2 + wc] = v; s_bj[row * 2 + wc] = c; }
-                }
-            }
+    for (int bj = 0; bj < 2; ++bj) {
+        const float ov = __shfl_xor(bv[bj], 32, 64);
+        const int oc = __shfl_xor(bc[bj], 32, 64);
+        if (ov < bv[bj] || (ov == bv[bj] && oc < bc[bj])) { bv[bj] = ov; bc[bj] = oc; }
+        if (lane < 32) {
+            const int col = Bf16x3Tile::acc_col(bj);
+            s_bv[col * 2 + wr] = bv[bj];
+            s_bj[col * 2 + wr] = bc[bj];
+        }
     }
     __syncthreads();
-    if (row0 + tid < n) {                 // 256 threads, 256 rows
+    if (tid < Bf16x3Tile::kRowsB && row0 + tid < n) {
         float v = s_bv[tid * 2];
         int j = s_bj[tid * 2];
-        if (s_bv[tid * 2 + 1] < v) { v = s_bv[tid * 2 + 1]; j = s_bj[tid * 2 + 1]; }   // equal values: the lower half holds the lower index
+        const float v1 = s_bv[tid * 2 + 1];
+        const int j1 = s_bj[tid * 2 + 1];
+        if (v1 < v || (v1 == v && j1 < j)) { v = v1; j = j1; }
         out_idx[row0 + tid] = j;
         if (out_dist) {
             float xn = 0.f;
@@ -319,13 +338,15 @@ __global__ __launch_bounds__(256) void assign_bf16x3_kernel(const float *__restr
 // chi / clo: bf16 split of the centres (u16 [K*d] each) or NULL.  The matrix-core paths are taken when the shape
 // pays for them and allows 16-byte loads: split-bf16 first, fp32 MFMA second; otherwise the direct-form VALU
 // kernel runs.
+void launch_split(const float *src, int64_t n, int d, int64_t ld, uint16_t *hi, uint16_t *lo, hipStream_t st);
+
 int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, const float *cnorm, const uint16_t *chi,
                   const uint16_t *clo, int K, int32_t *out_idx, float *out_dist, hipStream_t st) {
     const int vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(cent) % 16 == 0);
     const bool mfma = vec4 && cnorm != nullptr && K >= 128 && d >= 64;
-    const bool bf16 = mfma && chi != nullptr && clo != nullptr && d % 8 == 0;
-    constexpr size_t kBfLds = Bf16x3Tile::kLdsBytes + 4 * sizeof(float) * Bf16x3Tile::kRowsA;
+    const bool bf16 = cnorm != nullptr && K >= 128 && d >= 64 && chi != nullptr && clo != nullptr;
+    constexpr size_t kBfLds = Bf16x3Tile::kLdsBytes + sizeof(float) * (2 * Bf16x3Tile::kRowsA + 4 * Bf16x3Tile::kRowsB);
     if (bf16) {
         static bool configured = false;
         if (!configured) {
@@ -333,14 +354,30 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBfLds));
             configured = true;
         }
+        // the vectors are split slice by slice into a scratch area that lives in stream order
+        const int64_t slice = std::max<int64_t>(Bf16x3Tile::kRowPad, ((int64_t)1 << 28) / ((int64_t)Bf16x3Tile::chunks_pad(d) * 8) /
+                                                                         Bf16x3Tile::kRowPad * Bf16x3Tile::kRowPad);
+        const int64_t cap_rows = std::min(slice, Bf16x3Tile::rows_pad(n));
+        const size_t part = Bf16x3Tile::part_elems(cap_rows, d);
+        uint16_t *xs = nullptr;
+        PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&xs), 2 * part * sizeof(uint16_t), st));
+        const int nchunks = Bf16x3Tile::chunks_pad(d);
+        const int64_t c_rp = Bf16x3Tile::rows_pad(K);
+        for (int64_t a = 0; a < n; a += slice) {
+            const int64_t cnt = std::min(slice, n - a), rp = Bf16x3Tile::rows_pad(cnt);
+            launch_split(x + a * ldx, cnt, d, ldx, xs, xs + part, st);
+            hipLaunchKernelGGL(assign_bf16x3_kernel, dim3((unsigned)((cnt + Bf16x3Tile::kRowsB - 1) / Bf16x3Tile::kRowsB)), dim3(256),
+                               kBfLds, st, x + a * ldx, cnt, d, ldx, xs, xs + part, rp, chi, clo, c_rp, cnorm, K, out_idx + a,
+                               out_dist ? out_dist + a : nullptr);
+            (void)nchunks;
+        }
+        PR_CHECK_HIP(hipFreeAsync(xs, st));
+        return PIPERAG_OK;
     }
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
-        if (bf16)
-            hipLaunchKernelGGL(assign_bf16x3_kernel, dim3((unsigned)((cnt + Bf16x3Tile::kRowsA - 1) / Bf16x3Tile::kRowsA)), dim3(256),
-                               kBfLds, st, x + a * ldx, cnt, d, ldx, chi, clo, cnorm, K, out_idx + a, out_dist ? out_dist + a : nullptr);
-        else if (mfma)
+        if (mfma)
             hipLaunchKernelGGL(assign_mfma_kernel, dim3((unsigned)((cnt + AssignTile::kRowsA - 1) / AssignTile::kRowsA)), dim3(256), 0,
                                st, x + a * ldx, cnt, d, ldx, cent, cnorm, K, out_idx + a, out_dist ? out_dist + a : nullptr);
         else
@@ -350,8 +387,13 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
     return PIPERAG_OK;
 }
 
-void launch_split(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st) {
-    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, n, hi, lo);
+// Splits n rows of d values (stride ld) into the chunk-major bf16 hi / lo parts; each part holds
+// Bf16x3Tile::part_elems(n, d) elements.
+void launch_split(const float *src, int64_t n, int d, int64_t ld, uint16_t *hi, uint16_t *lo, hipStream_t st) {
+    const int64_t rp = Bf16x3Tile::rows_pad(n);
+    const int nchunks = Bf16x3Tile::chunks_pad(d);
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((rp * nchunks + 255) / 256)), dim3(256), 0, st, src, n, d, ld, rp, nchunks, hi,
+                       lo);
 }
 
 void launch_rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) {
@@ -394,7 +436,8 @@ __global__ void zero_kernel(unsigned long long *__restrict__ p, int64_t n) {
 
 namespace piperag {
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) { launch_rownorm(a, n, d, lda, out, st); }
-void split_bf16(const float *src, int64_t n, uint16_t *hi, uint16_t *lo, hipStream_t st) { launch_split(src, n, hi, lo, st); }
+void split_bf16(const float *src, int64_t n, int d, uint16_t *hi, uint16_t *lo, hipStream_t st) { launch_split(src, n, d, d, hi, lo, st); }
+size_t split_bf16_elems(int64_t n, int d) { return Bf16x3Tile::part_elems(n, d); }
 }  // namespace piperag
 
 namespace {
@@ -468,9 +511,9 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
         set_error("out of device memory in piperag_kmeans");
         return done(PIPERAG_ERR_OOM);
     }
-    const bool use_split = K >= 128 && d >= 64 && d % 8 == 0;
-    if (use_split && (hipMalloc((void **)&chi, sizeof(uint16_t) * (size_t)K * d) != hipSuccess ||
-                      hipMalloc((void **)&clo, sizeof(uint16_t) * (size_t)K * d) != hipSuccess)) {
+    const bool use_split = K >= 128 && d >= 64;
+    if (use_split && (hipMalloc((void **)&chi, sizeof(uint16_t) * Bf16x3Tile::part_elems(K, d)) != hipSuccess ||
+                      hipMalloc((void **)&clo, sizeof(uint16_t) * Bf16x3Tile::part_elems(K, d)) != hipSuccess)) {
         set_error("out of device memory in piperag_kmeans");
         return done(PIPERAG_ERR_OOM);
     }
@@ -481,7 +524,7 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     const int64_t nsum = (int64_t)K * d;
     for (int it = 0; it < iters; ++it) {
         launch_rownorm(centroids_out_dev, K, d, d, cnorm, st);
-        if (use_split) launch_split(centroids_out_dev, (int64_t)K * d, chi, clo, st);
+        if (use_split) launch_split(centroids_out_dev, K, d, d, chi, clo, st);
         const int rca = launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, chi, clo, K, assign, adist, st);
         if (rca != PIPERAG_OK) return done(rca);
         hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, (unsigned long long *)sum, nsum);

@@ -229,9 +229,10 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         set_error("upload of trained parameters failed");
         return fail(PIPERAG_ERR_HIP);
     }
-    if (p.nlist >= 128 && p.d >= 64 && p.d % 8 == 0) {
-        if ((rc = dev_alloc(&ix->cent_hi, ncent)) || (rc = dev_alloc(&ix->cent_lo, ncent))) return fail(rc);
-        split_bf16(ix->centroids, (int64_t)ncent, ix->cent_hi, ix->cent_lo, nullptr);
+    if (p.nlist >= 128 && p.d >= 64) {
+        const size_t nsplit = split_bf16_elems(p.nlist, p.d);
+        if ((rc = dev_alloc(&ix->cent_hi, nsplit)) || (rc = dev_alloc(&ix->cent_lo, nsplit))) return fail(rc);
+        split_bf16(ix->centroids, p.nlist, p.d, ix->cent_hi, ix->cent_lo, nullptr);
     }
     rownorm(ix->centroids, p.nlist, p.d, p.d, ix->cnorm, nullptr);
     if (hipStreamSynchronize(nullptr) != hipSuccess) { set_error("centre norms failed"); return fail(PIPERAG_ERR_HIP); }

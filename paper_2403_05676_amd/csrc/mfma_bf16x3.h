@@ -2,15 +2,22 @@
 // the bf16 matrix cores.  Every fp32 value v is written as hi + lo with hi = bf16(v) and lo = bf16(v - hi)
 // (16 significant bits together); <a, b> ~ <a_hi, b_hi> + <a_hi, b_lo> + <a_lo, b_hi>, accumulated in fp32
 // by three v_mfma_f32_32x32x16_bf16 per 32 x 32 block and 16 depth values.  The dropped lo*lo term and the
-// rounding of lo are 2^-16 relative per product.  Used by the encoder's list assignment, where the centres'
-// split is precomputed once and the vectors are split on the fly.
+// rounding of lo are 2^-16 relative per product.  Used by the encoder's list assignment.
 //
-// Shape: workgroup = 4 waves as 2 x 2; a wave owns 128 rows of A x 64 rows of B = 4 x 2 blocks; the
-// workgroup tile is 256 rows of A (fp32 in memory) by 128 rows of B (pre-split bf16 in memory).  Depth step
-// 16.  LDS holds, per operand part, [depth half][row][8 bf16] so that the 32 lanes of a half-wave read 32
-// consecutive 16-byte groups; lanes 0-31 take depth values 0-7 of the step and lanes 32-63 values 8-15, for
-// A and B alike, which is all a sum over the depth needs.  Two steps are in flight: one in registers, one in
-// the second LDS buffer.
+// Operands are split beforehand into the "chunk-major" layout below, so that what a workgroup needs for one
+// depth step is a few contiguous kilobytes (every cache line fetched is used whole; with row-major operands a
+// 16-value step touches a quarter of each line and the tile product is bound by L2 traffic, not by the matrix
+// cores):
+//   element (row, k) of a part (hi or lo) sits at ((k / 8) * rows_pad + row) * 8 + k % 8,
+// rows_pad = rows rounded up to kRowPad, the number of 8-value chunks rounded up to even; padding holds zeros,
+// so the tile product needs no bounds checks.
+//
+// Shape: workgroup = 4 waves as 2 x 2; the tile is 256 rows of A by 128 rows of B; a wave owns 128 x 64 = 4 x 2
+// blocks.  The accumulator of a block keeps 16 rows of one column per lane, so A should be the operand over
+// which the caller reduces (the centres, for an arg-min): the reduction then runs over a lane's own registers.
+// Depth step 16 = two chunks; lanes 0-31 take the first chunk of the step and lanes 32-63 the second, for A and
+// B alike, which is all a sum over the depth needs.  LDS holds [chunk of the step][row][8 bf16] per part, the
+// same order as in memory.  Two steps are in flight: one in registers, one in the second LDS buffer.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -22,28 +29,21 @@ typedef float acc16_t __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 struct Bf16x3Tile {
-    static constexpr int kRowsA = 256, kRowsB = 128, kTileK = 16;
+    static constexpr int kRowsA = 256, kRowsB = 128, kTileK = 16, kRowPad = 256;
     static constexpr int kPartA = 2 * kRowsA * 16, kPartB = 2 * kRowsB * 16;          // bytes of one hi or lo part per step
     static constexpr size_t kLdsBytes = 2 * (2 * (size_t)kPartA + 2 * (size_t)kPartB);  // double-buffered
 
-    // Splits 8 floats into their bf16 hi and lo parts.
-    __device__ static __forceinline__ void split8(const float4 &u, const float4 &v, bf16x8_t &hi, bf16x8_t &lo) {
-        const float f[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const __bf16 h = (__bf16)f[i];
-            hi[i] = h;
-            lo[i] = (__bf16)(f[i] - (float)h);
-        }
-    }
+    __host__ __device__ static int64_t rows_pad(int64_t rows) { return (rows + kRowPad - 1) / kRowPad * kRowPad; }
+    __host__ __device__ static int chunks_pad(int d) { return ((d + 7) / 8 + 1) / 2 * 2; }
+    // elements (uint16) of one part of a split matrix
+    __host__ __device__ static size_t part_elems(int64_t rows, int d) { return (size_t)chunks_pad(d) * (size_t)rows_pad(rows) * 8; }
 
-    // Rows a_row0.. of A (fp32, na rows, stride lda) against rows b_row0.. of B given as split bf16 matrices
-    // b_hi / b_lo (nb rows, stride ldb elements).  Rows beyond na / nb and depth beyond d count as zero.
-    // d % 8 == 0; A rows 16-byte aligned, B rows 16-byte aligned.  acc[bi][bj]: block rows 32*bi.., columns 32*bj..
-    // of this wave's 128 x 64 patch; same register layout as the fp32 tile product.
-    __device__ static void run(const float *__restrict__ A, int64_t na, int64_t lda, int64_t a_row0,
-                               const uint16_t *__restrict__ b_hi, const uint16_t *__restrict__ b_lo, int64_t nb, int64_t ldb,
-                               int64_t b_row0, int d, unsigned char *s_mem, acc16_t (&acc)[4][2]) {
+    // Rows a_row0 .. +255 of A against rows b_row0 .. +127 of B over the whole depth; both row ranges lie within
+    // the padded matrices.  a_rp / b_rp: padded row counts; nchunks: chunks_pad(d).
+    // acc[bi][bj]: block rows 32*bi.., columns 32*bj.. of this wave's 128 x 64 patch.
+    __device__ static void run(const uint16_t *__restrict__ a_hi, const uint16_t *__restrict__ a_lo, int64_t a_rp, int64_t a_row0,
+                               const uint16_t *__restrict__ b_hi, const uint16_t *__restrict__ b_lo, int64_t b_rp, int64_t b_row0,
+                               int nchunks, unsigned char *s_mem, acc16_t (&acc)[4][2]) {
         const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
         const int wr = wave >> 1, wc = wave & 1;
         unsigned char *sAh[2] = {s_mem, s_mem + kPartA * 2 + kPartB * 2};
@@ -57,45 +57,35 @@ struct Bf16x3Tile {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
-        // per step: A has 256 rows x 2 depth halves = 512 items of 8 floats (2 per thread); B has 128 x 2 = 256
-        // items of 8 bf16 per part (1 per thread)
-        struct Regs { float4 a[2][2]; uint4 bh, bl; };
+        // per step and part: A is 2 chunks x 256 rows = 512 pieces of 16 bytes (2 per thread: chunk p, row tid),
+        // B is 2 x 128 = 256 pieces (1 per thread: chunk tid / 128, row tid % 128); LDS offset = piece * 16
+        struct Regs { uint4 ah[2], al[2], bh, bl; };
         const uint4 zero4 = {0u, 0u, 0u, 0u};
-        auto fetch = [&](Regs &rg, int k0) {
+        const uint4 *pa_hi = reinterpret_cast<const uint4 *>(a_hi) + a_row0 + tid;
+        const uint4 *pa_lo = reinterpret_cast<const uint4 *>(a_lo) + a_row0 + tid;
+        const uint4 *pb_hi = reinterpret_cast<const uint4 *>(b_hi) + (int64_t)(tid >> 7) * b_rp + b_row0 + (tid & 127);
+        const uint4 *pb_lo = reinterpret_cast<const uint4 *>(b_lo) + (int64_t)(tid >> 7) * b_rp + b_row0 + (tid & 127);
+        auto fetch = [&](Regs &rg, int c0) {            // c0: first chunk of the step
+            if (c0 < nchunks) {                         // uniform
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int item = tid + p * 256, row = item >> 1, half = item & 1;
-                const int64_t gr = a_row0 + row;
-                const int k = k0 + half * 8;
-                const bool ok = gr < na && k < d;
-                rg.a[p][0] = ok ? *reinterpret_cast<const float4 *>(A + gr * lda + k) : float4{0.f, 0.f, 0.f, 0.f};
-                rg.a[p][1] = ok ? *reinterpret_cast<const float4 *>(A + gr * lda + k + 4) : float4{0.f, 0.f, 0.f, 0.f};
-            }
-            {
-                const int row = tid >> 1, half = tid & 1;
-                const int64_t gr = b_row0 + row;
-                const int k = k0 + half * 8;
-                const bool ok = gr < nb && k < d;
-                rg.bh = ok ? *reinterpret_cast<const uint4 *>(b_hi + gr * ldb + k) : zero4;
-                rg.bl = ok ? *reinterpret_cast<const uint4 *>(b_lo + gr * ldb + k) : zero4;
+                for (int p = 0; p < 2; ++p) {
+                    rg.ah[p] = pa_hi[(int64_t)(c0 + p) * a_rp];
+                    rg.al[p] = pa_lo[(int64_t)(c0 + p) * a_rp];
+                }
+                rg.bh = pb_hi[(int64_t)c0 * b_rp];
+                rg.bl = pb_lo[(int64_t)c0 * b_rp];
+            } else {
+                rg.ah[0] = rg.ah[1] = rg.al[0] = rg.al[1] = rg.bh = rg.bl = zero4;
             }
         };
         auto stash = [&](const Regs &rg, int buf) {
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const int item = tid + p * 256, row = item >> 1, half = item & 1;
-                bf16x8_t hi, lo;
-                split8(rg.a[p][0], rg.a[p][1], hi, lo);
-                const int off = (half * kRowsA + row) * 16;
-                *reinterpret_cast<bf16x8_t *>(sAh[buf] + off) = hi;
-                *reinterpret_cast<bf16x8_t *>(sAl[buf] + off) = lo;
+                *reinterpret_cast<uint4 *>(sAh[buf] + (p * kRowsA + tid) * 16) = rg.ah[p];
+                *reinterpret_cast<uint4 *>(sAl[buf] + (p * kRowsA + tid) * 16) = rg.al[p];
             }
-            {
-                const int row = tid >> 1, half = tid & 1;
-                const int off = (half * kRowsB + row) * 16;
-                *reinterpret_cast<uint4 *>(sBh[buf] + off) = rg.bh;
-                *reinterpret_cast<uint4 *>(sBl[buf] + off) = rg.bl;
-            }
+            *reinterpret_cast<uint4 *>(sBh[buf] + tid * 16) = rg.bh;
+            *reinterpret_cast<uint4 *>(sBl[buf] + tid * 16) = rg.bl;
         };
         const int half = lane >> 5, l32 = lane & 31;
         auto multiply = [&](int buf) {
@@ -122,20 +112,20 @@ struct Bf16x3Tile {
         };
 
         // Steps beyond the depth fetch zeros, so the pipeline needs no tail cases.
-        const int nsteps = (d + kTileK - 1) / kTileK;
+        const int nsteps = nchunks / 2;
         Regs r0, r1;
         fetch(r0, 0);
-        fetch(r1, kTileK);
+        fetch(r1, 2);
         __syncthreads();                 // the previous user of the LDS buffers is done
         stash(r0, 0);
         __syncthreads();
         for (int s = 0; s < nsteps; s += 2) {
-            fetch(r0, (s + 2) * kTileK);
+            fetch(r0, 2 * (s + 2));
             multiply(0);
             stash(r1, 1);
             __syncthreads();
             if (s + 1 < nsteps) {
-                fetch(r1, (s + 3) * kTileK);
+                fetch(r1, 2 * (s + 3));
                 multiply(1);
                 stash(r0, 0);
                 __syncthreads();
@@ -143,7 +133,7 @@ struct Bf16x3Tile {
         }
     }
 
-    // Row (within the workgroup tile) and column of accumulator register r of block (bi, bj) for this lane.
+    // Row of A and row of B (both within the workgroup tile) of accumulator register r of block (bi, bj) for this lane.
     __device__ static __forceinline__ int acc_row(int bi, int r) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         return (wave >> 1) * 128 + bi * 32 + (r % 4) + 4 * (lane >> 5) + 8 * (r / 4);
