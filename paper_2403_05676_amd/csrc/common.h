@@ -18,8 +18,12 @@ constexpr int kMaxK = 1024;
 constexpr int kMaxNprobe = 1024;
 constexpr int kScanThreads = 256;  // 4 waves per scan workgroup
 constexpr int kScanWaves = kScanThreads / kWave;
-constexpr int kTargetScanWGs = 512;    // scan workgroups per search call: two per compute unit, all resident at once
+constexpr int kTargetScanWGs = 512;    // scan workgroups per search call: two per compute unit, all resident at once ...
+constexpr int kMaxScanWGs = 2048;      // ... or, for large batches, about 8 per query up to this many: a query then has enough
+                                       // workgroups to share its blocks evenly, and late workgroups fill in behind early finishers
 constexpr int kMaxSegments = 1024;
+constexpr int kCoarseMaxParts = 4;     // parts the coarse quantiser's depth may be split into
+constexpr int kCoarseSplitMaxLists = 8192;   // ... for indexes of up to this many lists (the workspace holds that many partial rows)
 constexpr int kCtrStride = 32;         // chunk counters sit 128 bytes apart
 constexpr int kCtrPerQuery = 16;       // at most this many chunk counters share out one query's blocks
 constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
@@ -86,22 +90,23 @@ struct piperag_index {
     uint8_t *rb_codes;  // read-back scratch for piperag_ivf_get_list (allocated on first use)
     int64_t *rb_ids;
     // search workspace
-    float *ws_D;          // [max_nq*nlist]
+    float *ws_D;          // [parts][max_nq*nlist] coarse distances, or partial inner products (parts = kCoarseMaxParts up to kCoarseSplitMaxLists lists, else 1)
     int32_t *ws_probe;    // [max_nq*max_nprobe]
     float *ws_probe_d;    // [max_nq*max_nprobe]
     int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
-    int4 *ws_desc;        // [2*kTargetScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
+    int4 *ws_desc;        // [kMaxScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
     uint64_t *ws_part2;   // same shape as ws_part: keys kept by groups of scan workgroups (merge inside the scan kernel)
-    uint32_t *ws_done;    // [2*kTargetScanWGs+2*max_nq] counters of that merge
+    uint32_t *ws_done;    // [kMaxScanWGs+2*max_nq] counters of that merge
+    uint32_t *ws_tb;      // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
     uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
     int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
     float *ws_qn;         // [max_nq] squared norms of the queries
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
-    uint64_t *ws_part;    // [(2*kTargetScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results
+    uint64_t *ws_part;    // [(kMaxScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results
     float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
     int64_t *ws_out_i;    // [max_nq*max_k]
     int *flag;            // [1] device flag for argument checks
@@ -109,5 +114,9 @@ struct piperag_index {
     // stage timing
     bool timing;
     hipEvent_t ev[PIPERAG_NSTAGES + 1];
+    // the table build depends only on the queries: it runs on a stream of the index's own, beside the coarse
+    // quantiser, forked from and joined to the caller's stream with these two events
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_join;
     bool ev_valid;
 };

@@ -208,23 +208,24 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     if ((rc = dev_alloc(&ix->centroids, ncent)) || (rc = dev_alloc(&ix->pq, npq)) ||
         (rc = dev_alloc(&ix->st_list, (size_t)ix->cap)) || (rc = dev_alloc(&ix->st_codes, (size_t)ix->cap * p.M)) ||
         (rc = dev_alloc(&ix->st_ids, (size_t)ix->cap)) || (rc = dev_alloc(&ix->list_blk, (size_t)p.nlist + 1)) ||
-        (rc = dev_alloc(&ix->list_len, (size_t)p.nlist)) || (rc = dev_alloc(&ix->ws_D, (size_t)p.max_nq * p.nlist)) ||
+        (rc = dev_alloc(&ix->list_len, (size_t)p.nlist)) || (rc = dev_alloc(&ix->ws_D, (size_t)p.max_nq * p.nlist * (p.nlist <= kCoarseSplitMaxLists ? kCoarseMaxParts : 1))) ||
         (rc = dev_alloc(&ix->ws_probe, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_probe_d, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_pfx, (size_t)p.max_nq * (p.max_nprobe + 1))) ||
         (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) || (rc = dev_alloc(&ix->ws_thr, (size_t)p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_desc, 2 * (size_t)kTargetScanWGs + p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
+        (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_desc, (size_t)kMaxScanWGs + p.max_nq)) ||
+        (rc = dev_alloc(&ix->ws_tb, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
-        (rc = dev_alloc(&ix->ws_part, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
-        (rc = dev_alloc(&ix->ws_part2, (2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
-        (rc = dev_alloc(&ix->ws_done, 2 * (size_t)kTargetScanWGs + 2 * (size_t)p.max_nq)) ||
+        (rc = dev_alloc(&ix->ws_part, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
+        (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
+        (rc = dev_alloc(&ix->ws_done, (size_t)kMaxScanWGs + 2 * (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->ws_qn, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
         return fail(rc);
-    if (hipMemcpy(ix->centroids, cent_host, ncent * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+    if (hipMemset(ix->ws_tb, 0, sizeof(uint32_t) * ((size_t)p.max_nq + 1)) != hipSuccess ||   // arrival counter starts at zero
+        hipMemcpy(ix->centroids, cent_host, ncent * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ix->pq, pq_host, npq * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
         set_error("upload of trained parameters failed");
         return fail(PIPERAG_ERR_HIP);
@@ -248,6 +249,12 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     }
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (hipEventCreate(&ix->ev[e]) != hipSuccess) { set_error("hipEventCreate failed"); return fail(PIPERAG_ERR_HIP); }
+    if (hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming) != hipSuccess) {
+        set_error("creating the side stream failed");
+        return fail(PIPERAG_ERR_HIP);
+    }
     *out = ix;
     return PIPERAG_OK;
 }
@@ -291,10 +298,13 @@ void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
     void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
-                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
+                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);
+    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+    if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
+    if (ix->side) (void)hipStreamDestroy(ix->side);
     delete ix;
 }
 

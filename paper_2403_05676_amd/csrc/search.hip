@@ -182,25 +182,28 @@ __global__ __launch_bounds__(256) void coarse_rowwise_kernel(const float *__rest
     }
 }
 
-// Coarse distances on the matrix cores for batches: D[q][j] = |q|^2 + |c_j|^2 - 2 <q, c_j> (clamped at 0), a
-// 64-query x 64-centre tile per workgroup with the fp32 MFMA tile product.  The lanes of a half-wave hold 32
-// consecutive centres of one query, so the rows of D are written in contiguous runs.  Requires d % 4 == 0
-// and 16-byte aligned rows.  grid = (ceil(nlist / 64), ceil(nq / 64)).
+// Coarse quantiser on the matrix cores for batches: the inner products <q, c_j>, a 64-query x 64-centre tile per
+// workgroup with the fp32 MFMA tile product.  When that gives too few workgroups to fill the chip, the depth is
+// split over blockIdx.z and every part writes its own partial products P[z][q][j] (summed in a fixed order by
+// the selection kernel, which also adds the norms: D = |q|^2 + |c_j|^2 - 2 <q, c_j>, clamped at 0).  The
+// lanes of a half-wave hold 32 consecutive centres of one query, so rows are written in contiguous runs.
+// Requires d % 4 == 0, dper % 32 == 0 and 16-byte aligned rows.
+// grid = (ceil(nlist / 64), ceil(nq / 64), parts).
 using CoarseTile = MfmaTile<2, 2, 1, 1, 32>;
 
-__global__ __launch_bounds__(256) void coarse_mfma_kernel(const float *__restrict__ q, int nq, const float *__restrict__ qn,
-                                                          const float *__restrict__ cent, const float *__restrict__ cn,
-                                                          int nlist, int d, float *__restrict__ D) {
+__global__ __launch_bounds__(256) void coarse_mfma_kernel(const float *__restrict__ q, int nq, const float *__restrict__ cent,
+                                                          int nlist, int d, int dper, float *__restrict__ P) {
     __shared__ __align__(16) float s_mem[CoarseTile::kLdsFloats];
     const int64_t c0 = (int64_t)blockIdx.x * CoarseTile::kRowsB, q0 = (int64_t)blockIdx.y * CoarseTile::kRowsA;
+    const int dbeg = blockIdx.z * dper, dlen = min(dper, d - dbeg);
     mfma_acc_t acc[1][1];
-    CoarseTile::run(q, nq, d, q0, cent, nlist, d, c0, d, s_mem, acc);
+    CoarseTile::run(q + dbeg, nq, d, q0, cent + dbeg, nlist, d, c0, dlen, s_mem, acc);
     const int64_t col = c0 + CoarseTile::acc_col(0);
-    const float cnv = col < nlist ? cn[col] : 0.f;
+    float *out = P + (size_t)blockIdx.z * nq * nlist;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int64_t row = q0 + CoarseTile::acc_row(0, r);
-        if (row < nq && col < nlist) D[row * nlist + col] = fmaxf(0.f, qn[row] + cnv - 2.f * acc[0][0][r]);
+        if (row < nq && col < nlist) out[row * nlist + col] = acc[0][0][r];
     }
 }
 
@@ -252,6 +255,93 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
     if (lane == 0) { pfx[nprobe] = running; *o.scanned = vecs; *o.thr = 0xFFFFFFFFu; }
 }
 
+// Shares the scan workgroups out over the queries (one workgroup): query q gets
+// S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
+// per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
+// the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
+// use, at most max(target, nq)); desc[w] = (query, first block, end block, 0) of workgroup w, blocks counted
+// along the query's concatenated probed lists; desc of spare workgroups has query -1.  A workgroup gets at
+// least kMinBlocksPerWG blocks (unless its query has fewer), so that small searches are not spread over
+// needlessly many workgroups.
+struct ShareOut {
+    int32_t *seg0;
+    int4 *desc;
+    uint32_t *ctr, *done;
+};
+
+// The sharing itself, by the first 256 threads of the calling workgroup (all of its threads must call it: it
+// has barriers).  blocks_of(q) = number of blocks of query q.
+template <class BlocksOf>
+__device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, ShareOut o) {
+    __shared__ long long s_total;
+    __shared__ int32_t s_scan[256];
+    __shared__ int32_t s_carry;
+    const int tid = threadIdx.x;
+    const bool act = tid < 256;
+    if (tid == 0) { s_total = 0; s_carry = 0; }
+    __syncthreads();
+    long long mine = 0;
+    if (act)
+        for (int q = tid; q < nq; q += 256) mine += blocks_of(q);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+    if (act && (tid & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&s_total), (unsigned long long)mine);
+    __syncthreads();
+    // sum of ceil(TB_q / per) <= total / per + nq, so dividing by (target - nq) keeps the sum within target
+    const long long denom = max(1, target - nq);
+    const long long per = max((long long)kMinBlocksPerWG, (s_total + denom - 1) / denom);
+    for (int q0 = 0; q0 < nq; q0 += 256) {
+        const int q = q0 + tid;
+        int32_t sq = 0;
+        if (act && q < nq) {
+            const long long tb = blocks_of(q);
+            sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
+        }
+        if (act) s_scan[tid] = sq;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {          // Hillis-Steele inclusive scan
+            const int32_t add = act && tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            if (act) s_scan[tid] += add;
+            __syncthreads();
+        }
+        const int32_t base = s_carry;
+        if (act && q < nq) o.seg0[q] = base + s_scan[tid] - sq;
+        __syncthreads();
+        if (tid == 255) s_carry = base + s_scan[255];
+        __syncthreads();
+    }
+    if (tid == 0) o.seg0[nq] = s_carry;
+    __syncthreads();
+    const int total_wg = s_carry;
+    if (!act) return;
+    for (int w = tid; w < max_wg + nq; w += 256) o.done[w] = 0;   // merge counters: per group of workgroups, then per query
+    for (int w = tid; w < max_wg; w += 256) {
+        if (w >= total_wg) { o.desc[w] = int4{-1, 0, 0, 0}; continue; }
+        int lo = 0, hi = nq;                               // query of workgroup w: last q with seg0[q] <= w
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (o.seg0[mid] <= w) lo = mid; else hi = mid;
+        }
+        const int seg = w - o.seg0[lo], S = o.seg0[lo + 1] - o.seg0[lo];
+        // The query's chunks are dealt to P counters (chunk c belongs to counter c mod P) and its waves likewise
+        // (wave g of the query draws from counter g mod P), so that the additions of a query with many
+        // workgroups do not all queue up at one address.  Every wave starts on the chunk of its own number;
+        // counter p then hands out P * v + p for v = the number of starting chunks it covers, and up.
+        const int W = S * kScanWaves, P = min(kCtrPerQuery, max(1, S / 4));
+        o.desc[w] = int4{lo, seg, S, P};
+        if (seg == 0)
+            for (int c = 0; c < P; ++c) o.ctr[((size_t)lo * kCtrPerQuery + c) * kCtrStride] = (uint32_t)((W - c + P - 1) / P);
+    }
+}
+
+// As a kernel of its own (one workgroup of 256 threads), for plans made by copy_probes_kernel.
+__global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
+                                                    int target, int max_wg, ShareOut o) {
+    auto blocks_of = [&](int q) { return (long long)pfx[(size_t)q * (probe_stride + 1) + nprobe]; };
+    share_plan(blocks_of, nq, target, max_wg, o);
+}
+
 // Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
 // of 512 threads per query: selection of the nprobe-th smallest key (distance bits << 32 | list; distances
 // are >= 0 so their bit patterns order like the values), compaction, bitonic sort.  The row of D is staged in
@@ -259,25 +349,52 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
 constexpr int kSelThreads = 512;
 constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
 
-__global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float *__restrict__ D, int nlist, int nprobe,
+__global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__restrict__ D, int nparts,
+                                                                    const float *__restrict__ q, int d,
+                                                                    const float *__restrict__ cn, int nlist, int nprobe,
                                                                     int stage_row, int32_t *__restrict__ probe,
                                                                     float *__restrict__ probe_d, int probe_stride,
                                                                     const int32_t *__restrict__ list_blk,
-                                                                    const int32_t *__restrict__ list_len, PlanOut plan) {
+                                                                    const int32_t *__restrict__ list_len, PlanOut plan,
+                                                                    uint32_t *__restrict__ tb, uint32_t *__restrict__ arrived,
+                                                                    int target, int max_wg, ShareOut share) {
     extern __shared__ __align__(16) unsigned char sel_smem[];
+    __shared__ unsigned s_ticket;
     __shared__ unsigned s_hist[256];
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count;
-    const int qi = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *row = reinterpret_cast<const uint32_t *>(D + (size_t)qi * nlist);
+    __shared__ float s_qn;
+    const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
+    float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
+    const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
     for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
-    if (tid == 0) s_count = 0;
+    if (tid == 0) { s_count = 0; s_qn = 0.f; }
+    __syncthreads();
+    if (nparts > 0) {                                        // D holds partial inner products: the query's norm first
+        float part = 0.f;
+        for (int t = tid; t < d; t += kSelThreads) { const float v = q[(size_t)qi * d + t]; part += v * v; }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        // fixed order of additions: wave w adds in turn w
+        for (int w = 0; w < kSelThreads / kWave; ++w) {
+            if (tid == w * kWave) s_qn += part;
+            __syncthreads();
+        }
+    }
+    const float qn = s_qn;
+    auto dist_of = [&](int i) -> float {                      // distance to centre i from the parts, summed in order
+        float dot = grow[i];
+        for (int p = 1; p < nparts; ++p) dot += grow[(size_t)p * nq * nlist + i];
+        return fmaxf(0.f, qn + cn[i] - 2.f * dot);
+    };
     if (stage_row) {
         uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
-        for (int i = tid; i < nlist; i += kSelThreads) s_row[i] = row[i];
+        for (int i = tid; i < nlist; i += kSelThreads) s_row[i] = nparts > 0 ? __float_as_uint(dist_of(i)) : row[i];
         row = s_row;
+    } else if (nparts > 0) {                                 // too long for LDS: the distances replace part 0 in place
+        for (int i = tid; i < nlist; i += kSelThreads) grow[i] = dist_of(i);
     }
     __syncthreads();
     auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
@@ -296,7 +413,22 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const float 
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
     }
     auto probe_at = [&](int i) { return (int32_t)(s_keys[i] & 0xFFFFFFFFu); };
-    plan_query(probe_at, nprobe, list_blk, list_len, plan_of_query(plan, qi, probe_stride));
+    const PlanOut mine = plan_of_query(plan, qi, probe_stride);
+    plan_query(probe_at, nprobe, list_blk, list_len, mine);
+    // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
+    // workgroup publishes its query's number of blocks with a device-scope store, waits for it to complete and
+    // adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_store(&tb[qi], (uint32_t)mine.pfx[nprobe], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+        s_ticket = atomicAdd(arrived, 1u);
+    }
+    __syncthreads();
+    if (s_ticket != gridDim.x - 1) return;                  // uniform
+    auto blocks_of = [&](int q) { return (long long)__hip_atomic_load(&tb[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    share_plan(blocks_of, (int)gridDim.x, target, max_wg, share);
+    if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Probe lists given by the caller: entries outside 0..nlist-1 and repeats of an earlier entry become -1
@@ -318,76 +450,6 @@ __global__ __launch_bounds__(64) void copy_probes_kernel(const int32_t *__restri
     __syncthreads();
     auto probe_at = [&](int i) { return out[i]; };
     plan_query(probe_at, nprobe, list_blk, list_len, plan_of_query(plan, qi, probe_stride));
-}
-
-// Shares the scan workgroups out over the queries (one workgroup): query q gets
-// S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
-// per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
-// the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
-// use, at most max(target, nq)); desc[w] = (query, first block, end block, 0) of workgroup w, blocks counted
-// along the query's concatenated probed lists; desc of spare workgroups has query -1.  A workgroup gets at
-// least kMinBlocksPerWG blocks (unless its query has fewer), so that small searches are not spread over
-// needlessly many workgroups.
-__global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ pfx, int probe_stride, int nprobe, int nq,
-                                                    int target, int max_wg, int32_t *__restrict__ seg0, int4 *__restrict__ desc,
-                                                    uint32_t *__restrict__ ctr, uint32_t *__restrict__ done) {
-    __shared__ long long s_total;
-    __shared__ int32_t s_scan[256];
-    __shared__ int32_t s_carry;
-    const int tid = threadIdx.x;
-    if (tid == 0) { s_total = 0; s_carry = 0; }
-    __syncthreads();
-    long long mine = 0;
-    for (int q = tid; q < nq; q += 256) mine += pfx[(size_t)q * (probe_stride + 1) + nprobe];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
-    if ((tid & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&s_total), (unsigned long long)mine);
-    __syncthreads();
-    // sum of ceil(TB_q / per) <= total / per + nq, so dividing by (target - nq) keeps the sum within target
-    const long long denom = max(1, target - nq);
-    const long long per = max((long long)kMinBlocksPerWG, (s_total + denom - 1) / denom);
-    for (int q0 = 0; q0 < nq; q0 += 256) {
-        const int q = q0 + tid;
-        int32_t sq = 0;
-        if (q < nq) {
-            const long long tb = pfx[(size_t)q * (probe_stride + 1) + nprobe];
-            sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
-        }
-        s_scan[tid] = sq;
-        __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {          // Hillis-Steele inclusive scan
-            const int32_t add = tid >= off ? s_scan[tid - off] : 0;
-            __syncthreads();
-            s_scan[tid] += add;
-            __syncthreads();
-        }
-        const int32_t base = s_carry;
-        if (q < nq) seg0[q] = base + s_scan[tid] - sq;
-        __syncthreads();
-        if (tid == 255) s_carry = base + s_scan[255];
-        __syncthreads();
-    }
-    if (tid == 0) seg0[nq] = s_carry;
-    __syncthreads();
-    const int total_wg = s_carry;
-    for (int w = tid; w < max_wg + nq; w += 256) done[w] = 0;   // merge counters: per group of workgroups, then per query
-    for (int w = tid; w < max_wg; w += 256) {
-        if (w >= total_wg) { desc[w] = int4{-1, 0, 0, 0}; continue; }
-        int lo = 0, hi = nq;                               // query of workgroup w: last q with seg0[q] <= w
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (seg0[mid] <= w) lo = mid; else hi = mid;
-        }
-        const int seg = w - seg0[lo], S = seg0[lo + 1] - seg0[lo];
-        // The query's chunks are dealt to P counters (chunk c belongs to counter c mod P) and its waves likewise
-        // (wave g of the query draws from counter g mod P), so that the additions of a query with many
-        // workgroups do not all queue up at one address.  Every wave starts on the chunk of its own number;
-        // counter p then hands out P * v + p for v = the number of starting chunks it covers, and up.
-        const int W = S * kScanWaves, P = min(kCtrPerQuery, max(1, S / 4));
-        desc[w] = int4{lo, seg, S, P};
-        if (seg == 0)
-            for (int c = 0; c < P; ++c) ctr[((size_t)lo * kCtrPerQuery + c) * kCtrStride] = (uint32_t)((W - c + P - 1) / P);
-    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1306,29 +1368,45 @@ int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
 
 PlanOut plan_bufs(const piperag_index *ix) { return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr}; }
 
-int launch_select(const piperag_index *ix, int nq, int nprobe, hipStream_t st) {
+ShareOut share_bufs(const piperag_index *ix) { return ShareOut{ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_done}; }
+
+// Parts of the depth the matrix-core coarse quantiser is split into for this shape (0: the row-wise kernel
+// runs instead and writes finished distances).
+int coarse_parts(const piperag_index *ix, const float *q, int nq) {
+    const int d = ix->p.d, nlist = ix->p.nlist;
+    if (!(nq > 4 && d % 4 == 0 && d >= 64 && reinterpret_cast<uintptr_t>(q) % 16 == 0)) return 0;
+    const int tiles = ((nlist + CoarseTile::kRowsB - 1) / CoarseTile::kRowsB) * ((nq + CoarseTile::kRowsA - 1) / CoarseTile::kRowsA);
+    int parts = 1;
+    if (nlist <= kCoarseSplitMaxLists)
+        while (parts < kCoarseMaxParts && tiles * parts < 256 && d / (parts * 2) >= 64) parts *= 2;
+    return parts;
+}
+
+int launch_select(const piperag_index *ix, const float *q, int nq, int nprobe, int target, int max_wg, hipStream_t st) {
     const int nlist = ix->p.nlist;
     const int stage = nlist <= kSelMaxLdsRow;
-    const size_t lds = stage ? sizeof(uint32_t) * (size_t)nlist : 0;
-    static size_t configured = 32 * 1024;
+    const size_t lds = stage ? sizeof(float) * (size_t)nlist : 0;
+    static size_t configured = 0;
     if (lds > configured) {
         PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kSelMaxLdsRow)));
+        configured = sizeof(float) * kSelMaxLdsRow;
     }
-    hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, nlist, nprobe, stage, ix->ws_probe,
-                       ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix));
+    hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, coarse_parts(ix, q, nq), q, ix->p.d,
+                       ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len,
+                       plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target, max_wg, share_bufs(ix));
     return PIPERAG_OK;
 }
 
 int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
     constexpr int QT = 4;
     const int d = ix->p.d, nlist = ix->p.nlist;
-    if (nq > QT && d % 4 == 0 && d >= 64 && reinterpret_cast<uintptr_t>(q) % 16 == 0) {     // batches: matrix cores
-        rownorm(q, nq, d, d, ix->ws_qn, st);
+    const int parts = coarse_parts(ix, q, nq);
+    if (parts > 0) {                                         // batches: matrix cores
+        const int dper = (d / parts + 31) / 32 * 32;
         hipLaunchKernelGGL(coarse_mfma_kernel, dim3((nlist + CoarseTile::kRowsB - 1) / CoarseTile::kRowsB,
-                                                    (nq + CoarseTile::kRowsA - 1) / CoarseTile::kRowsA),
-                           dim3(256), 0, st, q, nq, ix->ws_qn, ix->centroids, ix->cnorm, nlist, d, ix->ws_D);
+                                                    (nq + CoarseTile::kRowsA - 1) / CoarseTile::kRowsA, parts),
+                           dim3(256), 0, st, q, nq, ix->centroids, nlist, d, dper, ix->ws_D);
         return PIPERAG_OK;
     }
     const int groups = std::min((nlist + 3) / 4, 2048);
@@ -1378,21 +1456,27 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     const int pstride = ix->p.max_nprobe;
     const bool tm = ix->timing;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
+    // fork: the tables need only the queries and are built beside the coarse quantiser and the selection
+    PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));
+    PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+    launch_lut_build(ix, q, nq, ix->side);
+    PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
     if (!probes && (rc = launch_coarse(ix, q, nq, st)) != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
-    static const int target_wgs = [] {                      // tuning override, read once
+    static const int wgs_override = [] {                    // tuning override, read once
         const char *e = getenv("PIPERAG_SCAN_WGS");
         const int v = e ? atoi(e) : 0;
-        return v > 0 && v <= 2 * kTargetScanWGs ? v : kTargetScanWGs;
+        return v > 0 && v <= kMaxScanWGs ? v : 0;
     }();
+    const int target_wgs = wgs_override ? wgs_override : std::min(kMaxScanWGs, std::max(kTargetScanWGs, 8 * nq));
+    const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
     if (!probes) {
-        if ((rc = launch_select(ix, nq, nprobe, st)) != PIPERAG_OK) return rc;
-    } else
+        if ((rc = launch_select(ix, q, nq, nprobe, target_wgs, G, st)) != PIPERAG_OK) return rc;
+    } else {
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
                            ix->list_blk, ix->list_len, plan_bufs(ix));
-    const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
-    hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, ix->ws_seg0,
-                       ix->ws_desc, ix->ws_ctr, ix->ws_done);
+        hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ix));
+    }
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
     ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
@@ -1405,7 +1489,7 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     { const char *e = getenv("PIPERAG_DEBUG_FLAGS"); a.flags = e ? atoi(e) : 0; }
     g_trace_buf = trace_buf; g_trace_n = G;
 #endif
-    launch_lut_build(ix, q, nq, st);
+    PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
     PR_DISPATCH_C(launch_prime, ix, nq, a, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
@@ -1472,7 +1556,7 @@ int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int
     PR_CHECK_HIP(hipSetDevice(ix->device));
     const int rc = launch_coarse(ix, queries_dev, nq, st);
     if (rc != PIPERAG_OK) return rc;
-    const int rc2 = launch_select(ix, nq, nprobe, st);
+    const int rc2 = launch_select(ix, queries_dev, nq, nprobe, kTargetScanWGs, std::max(kTargetScanWGs, (int)nq), st);
     if (rc2 != PIPERAG_OK) return rc2;
     PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ix->ws_probe, sizeof(int32_t) * ix->p.max_nprobe,
                                   sizeof(int32_t) * nprobe, nq, hipMemcpyDeviceToDevice, st));
