@@ -65,6 +65,18 @@ inline int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 // [chunk c < Mp/16][lane < 64][16 bytes]; byte t = 16*c + u of lane l is code byte (l + t) mod Mp of the
 // vector in slot 64*b + l (zero when that index is >= M).  One 16-byte load per lane per chunk is thus a
 // contiguous 1 KiB wavefront access, and at step t the 64 lanes look up 64 different sub-quantisers.
+// A search call seen before, and its captured graph once it has been seen twice.
+struct SearchGraph {
+    const float *q;
+    const int32_t *probes;
+    int32_t nq, nprobe, k;
+    float *out_d;
+    int64_t *out_i;
+    hipGraphExec_t exec;
+    uint64_t stamp;
+    int seen;
+};
+
 struct piperag_index {
     piperag_params p;
     int dsub, Mp, device;
@@ -118,5 +130,8 @@ struct piperag_index {
     // quantiser, forked from and joined to the caller's stream with these two events
     hipStream_t side;
     hipEvent_t ev_fork, ev_join;
+    hipStream_t cap_stream;       // capture stream for the search graphs
+    SearchGraph graphs[8];
+    uint64_t graph_clock;
     bool ev_valid;
 };

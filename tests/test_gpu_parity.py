@@ -379,3 +379,28 @@ def test_many_vectors_with_identical_codes_tie_at_the_kth_distance():
     od, oi = ix.ivfpq_search(dev(q), 4, 100)
     od2, oi2 = ix.ivfpq_search(dev(q), 4, 100)
     assert torch.equal(od, od2) and torch.equal(oi, oi2)   # and the choice is deterministic
+
+
+def test_repeated_calls_replay_a_captured_graph_with_fresh_inputs(cfg0):
+    # the third and later calls with the same buffers are graph replays: each must see the buffer's current
+    # contents, with eager work and synchronisation in between, and agree with a plain call on other buffers
+    cfg, x, q, oidx = cfg0
+    pkg = P()
+    ix = gpu_index_from_oracle(pkg, oidx)
+    rng = np.random.default_rng(11)
+    qbuf = torch.empty((8, cfg.d), dtype=torch.float32, device="cuda")
+    od = torch.empty((8, cfg.k), dtype=torch.float32, device="cuda")
+    oi = torch.empty((8, cfg.k), dtype=torch.int64, device="cuda")
+    for rep in range(6):
+        sel = rng.integers(0, q.shape[0], size=8)
+        qbuf.copy_(dev(q[sel]))
+        ix.ivfpq_search(qbuf, cfg.nprobe, cfg.k, od, oi)
+        junk = (torch.randn(1 << 16, device="cuda") * 2).sum()        # unrelated eager work between replays
+        torch.cuda.synchronize()
+        rd, ri = ix.ivfpq_search(dev(q[sel]), cfg.nprobe, cfg.k)      # fresh buffers: plain path
+        torch.cuda.synchronize()
+        assert torch.equal(od, rd) and torch.equal(oi, ri), f"replay {rep} differs from the plain call"
+        gl, _ = ix.ivf_coarse(qbuf, cfg.nprobe)
+        torch.cuda.synchronize()
+        parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), oidx, q[sel], gl.cpu().numpy(), cfg.k)
+        assert float(junk) == float(junk)
