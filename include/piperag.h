@@ -162,12 +162,23 @@ int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, i
 /* Per-stage timing of the retrieval latency model's terms (Section 3.2, S3: index scan + vector scan).
  * When enabled, every search call records HIP events around its stages on its stream;
  * piperag_stage_times synchronises on them and writes the most recent call's milliseconds:
- * [0] coarse distances, [1] top-nprobe selection and scan plan, [2] lookup-table build, [3] list scan
- * with k-selection, [4] merge and id gather.  Stages [0]+[1] are the index-scan term, [2]..[4] the
- * vector-scan term. */
+ * [0] coarse quantiser, [1] top-nprobe selection, scan plan and work sharing, [2] wait for the lookup
+ * tables (built on a side stream from the start of the call) and priming of the bound, [3] list scan with
+ * k-selection (includes the merge for batches of up to 32 queries), [4] merge and id gather.  Stages
+ * [0]+[1] are the index-scan term, [2]..[4] the vector-scan term. */
 #define PIPERAG_NSTAGES 5
 int piperag_set_stage_timing(piperag_index *index, int enable);
 int piperag_stage_times(const piperag_index *index, float *out_ms_host /* [PIPERAG_NSTAGES] */);
+
+/* Graph replay of repeated search calls (off by default).  For callers that issue one search at a time
+ * and wait for it (the paper's serving loop retrieves for one sequence between generation steps, Section
+ * 3.1): when enabled, a search call whose arguments (query, probe and output pointers, nq, nprobe, k)
+ * repeat an earlier call's is captured into a HIP graph the second time it is seen and replayed with a
+ * single launch from then on, which shortens the host side of the call.  The buffers' contents may change
+ * between calls; their addresses must stay valid while replay is enabled.  Up to 8 distinct calls are
+ * remembered (least recently used is dropped).  Back-to-back calls that are not waited for run faster
+ * without it.  Disabling destroys the cached graphs.  Stage timing bypasses replay. */
+int piperag_set_graph_replay(piperag_index *index, int enable);
 
 /* Number of vectors in the index. */
 int64_t piperag_ivf_ntotal(const piperag_index *index);

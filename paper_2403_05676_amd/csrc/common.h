@@ -131,6 +131,7 @@ struct piperag_index {
     hipStream_t side;
     hipEvent_t ev_fork, ev_join;
     hipStream_t cap_stream;       // capture stream for the search graphs
+    bool replay;                  // graph replay of repeated calls is enabled
     SearchGraph graphs[8];
     uint64_t graph_clock;
     bool ev_valid;

@@ -117,10 +117,13 @@ __device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_h
 // In-place ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
 __device__ void block_bitonic_sort_u64(uint64_t *keys, int n) {
     const int tid = threadIdx.x, nt = blockDim.x;
+    // up to 128 keys are sorted by one wavefront, whose lanes run in lockstep: no workgroup barriers between steps
+    const bool one_wave = n <= 2 * kWave;
+    __syncthreads();
     for (int size = 2; size <= n; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int i = tid; i < (n >> 1); i += nt) {
+            if (one_wave) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); else __syncthreads();
+            for (int i = tid; i < (n >> 1) && (!one_wave || tid < kWave); i += nt) {
                 const int lo = 2 * i - (i & (stride - 1));
                 const int hi = lo + stride;
                 const bool up = (lo & size) == 0;
@@ -297,18 +300,20 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
             const long long tb = blocks_of(q);
             sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
         }
-        if (act) s_scan[tid] = sq;
-        __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {          // Hillis-Steele inclusive scan
-            const int32_t add = act && tid >= off ? s_scan[tid - off] : 0;
-            __syncthreads();
-            if (act) s_scan[tid] += add;
-            __syncthreads();
+        int32_t incl = sq;                                 // inclusive scan: within the wave, then over the four waves
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t up = __shfl_up(incl, off, 64);
+            if ((tid & 63) >= off) incl += up;
         }
-        const int32_t base = s_carry;
-        if (act && q < nq) o.seg0[q] = base + s_scan[tid] - sq;
+        if (act && (tid & 63) == 63) s_scan[tid >> 6] = incl;
         __syncthreads();
-        if (tid == 255) s_carry = base + s_scan[255];
+        const int32_t base = s_carry;
+        int32_t before = 0;
+        for (int w = 0; w < (tid >> 6) && w < 4; ++w) before += s_scan[w];
+        if (act && q < nq) o.seg0[q] = base + before + incl - sq;
+        __syncthreads();
+        if (tid == 255) s_carry = base + before + incl;
         __syncthreads();
     }
     if (tid == 0) o.seg0[nq] = s_carry;
@@ -1521,11 +1526,12 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     return PIPERAG_OK;
 }
 
-// A search is about seven launches and four event operations; enqueueing them one by one costs the host
-// about 45 us, more than the device needs for a single query.  A call that repeats an earlier one (same
-// buffers, same sizes: a serving loop that refills its query buffer) is therefore captured into a graph the
-// second time it is seen and replayed with one launch from then on.  The graph holds only kernel nodes and
-// the fork / join of the table build.  Stage timing and PIPERAG_NO_GRAPH=1 keep the plain path.
+// A search is about six launches and four event operations; enqueueing them one by one costs the host about
+// 45 us, a large part of a single query's latency.  With replay enabled (piperag_set_graph_replay), a call
+// that repeats an earlier one (same buffers, same sizes: a serving loop that refills its query buffer) is
+// captured into a graph the second time it is seen and replayed with one launch from then on (measured: 8 us
+// less per waited-for call, but 10 us more per call in a back-to-back loop, hence opt-in).  The graph holds
+// only kernel nodes and the fork / join of the table build.  Stage timing keeps the plain path.
 int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int32_t *probes, int32_t nprobe, int32_t k,
                 float *out_d, int64_t *out_i, hipStream_t st) {
     piperag_index *ix = const_cast<piperag_index *>(cix);   // workspace, timing state and graph cache are mutable
@@ -1533,8 +1539,7 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     if (rc != PIPERAG_OK || nq == 0) return rc;
     PR_CHECK_HIP(hipSetDevice(ix->device));
     ix->last_nq = nq;
-    static const bool no_graph = [] { const char *e = getenv("PIPERAG_NO_GRAPH"); return e && atoi(e) != 0; }();
-    if (ix->timing || no_graph) return enqueue_search(ix, q, nq, probes, nprobe, k, out_d, out_i, st);
+    if (ix->timing || !ix->replay) return enqueue_search(ix, q, nq, probes, nprobe, k, out_d, out_i, st);
     SearchGraph *slot = nullptr, *oldest = &ix->graphs[0];
     for (SearchGraph &g : ix->graphs) {
         if (g.seen && g.q == q && g.probes == probes && g.nq == nq && g.nprobe == nprobe && g.k == k && g.out_d == out_d &&
@@ -1643,6 +1648,17 @@ int piperag_set_stage_timing(piperag_index *index, int enable) {
     PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     index->timing = enable != 0;
     index->ev_valid = false;
+    return PIPERAG_OK;
+}
+
+int piperag_set_graph_replay(piperag_index *index, int enable) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    index->replay = enable != 0;
+    if (!index->replay)
+        for (SearchGraph &g : index->graphs) {
+            if (g.exec) (void)hipGraphExecDestroy(g.exec);
+            g = SearchGraph{};
+        }
     return PIPERAG_OK;
 }
 

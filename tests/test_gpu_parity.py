@@ -387,6 +387,7 @@ def test_repeated_calls_replay_a_captured_graph_with_fresh_inputs(cfg0):
     cfg, x, q, oidx = cfg0
     pkg = P()
     ix = gpu_index_from_oracle(pkg, oidx)
+    ix.set_graph_replay(True)
     rng = np.random.default_rng(11)
     qbuf = torch.empty((8, cfg.d), dtype=torch.float32, device="cuda")
     od = torch.empty((8, cfg.k), dtype=torch.float32, device="cuda")
@@ -397,7 +398,7 @@ def test_repeated_calls_replay_a_captured_graph_with_fresh_inputs(cfg0):
         ix.ivfpq_search(qbuf, cfg.nprobe, cfg.k, od, oi)
         junk = (torch.randn(1 << 16, device="cuda") * 2).sum()        # unrelated eager work between replays
         torch.cuda.synchronize()
-        rd, ri = ix.ivfpq_search(dev(q[sel]), cfg.nprobe, cfg.k)      # fresh buffers: plain path
+        rd, ri = ix.ivfpq_search(dev(q[sel]), cfg.nprobe, cfg.k)      # fresh buffers: seen for the first time, plain path
         torch.cuda.synchronize()
         assert torch.equal(od, rd) and torch.equal(oi, ri), f"replay {rep} differs from the plain call"
         gl, _ = ix.ivf_coarse(qbuf, cfg.nprobe)
