@@ -201,6 +201,69 @@ def nprobe_sweep(args, pkg, cfg, torch):
                       "fit_nq8_ms": {"a": float(fit_8[0]), "b": float(fit_8[1])}}), flush=True)
 
 
+def overlap_demo(args, pkg, cfg, torch):
+    """Performance-model-driven retrieval (Section 3.2, S3) on one GPU: the latency line fitted by
+    piperag_latency_profile is inverted for the time a synthetic generation step takes, and the chosen search is
+    run on a second stream while that step runs on the first.  The generation step stands in for the decoder: per
+    token one pass over a weight matrix plus a read of a key/value cache that grows with the sequence length
+    (memory-bound, like decoding), so its duration T(C) grows linearly in the sequence length."""
+    cap = min(1024, cfg.nlist)
+    ix, g, info = build_index(pkg, cfg, torch, max_nq=1, max_nprobe=cap)
+    q1 = g.queries(1)
+    nprobes = [p for p in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if p <= cap]
+    p50, fit = ix.latency_profile(q1, nprobes, cfg.k, reps=50)
+    log(f"[overlap] latency fit: {fit[0]:.4f} ms + {fit[1] * 1e3:.3f} us * nprobe")
+    W = torch.randn((8192, 8192), dtype=torch.float32, device="cuda")             # 256 MiB of "weights"
+    x = torch.randn(8192, dtype=torch.float32, device="cuda")
+    kv = torch.randn((16384, 4096), dtype=torch.float32, device="cuda")           # 16 KiB of cache per position
+    out_d = torch.empty((1, cfg.k), dtype=torch.float32, device="cuda")
+    out_i = torch.empty((1, cfg.k), dtype=torch.int64, device="cuda")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def generate(L, tokens=2):
+        for _ in range(tokens):
+            torch.mv(W, x)
+            kv[:L].sum(dim=0)
+
+    def timed(fn_a, fn_b, reps=30):
+        ts = []
+        for r in range(reps + 5):
+            torch.cuda.synchronize()
+            e0, ea, eb = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            if fn_a:
+                with torch.cuda.stream(sa):
+                    sa.wait_event(e0); fn_a(); ea.record()
+            if fn_b:
+                with torch.cuda.stream(sb):
+                    sb.wait_event(e0); fn_b(); eb.record()
+            torch.cuda.synchronize()
+            ta = e0.elapsed_time(ea) if fn_a else 0.0
+            tb = e0.elapsed_time(eb) if fn_b else 0.0
+            if r >= 5:
+                ts.append((ta, tb))
+        return np.median(np.array(ts), axis=0)
+
+    rows = []
+    for L in (1024, 4096, 8192, 16384):
+        t_gen = float(timed(lambda: generate(L), None)[0])
+        nprobe, fits, pred = pkg.max_nprobe(fit, t_gen, cap)
+        search = lambda: ix.ivfpq_search(q1, nprobe, cfg.k, out_d, out_i)
+        t_ret = float(timed(None, search)[1])
+        both = timed(lambda: generate(L), search)
+        rows.append({"seq_len": L, "t_gen_ms": t_gen, "nprobe": nprobe, "fits": fits, "predicted_ret_ms": pred,
+                     "t_ret_alone_ms": t_ret, "t_gen_overlapped_ms": float(both[0]), "t_ret_overlapped_ms": float(both[1])})
+        log(f"[overlap] {rows[-1]}")
+    print("| sequence length | T(C) alone ms | nprobe chosen | predicted retrieval ms | retrieval alone ms | "
+          "T(C) with retrieval beside it ms | retrieval beside T(C) ms | hidden |")
+    print("|---|---|---|---|---|---|---|---|")
+    for r in rows:
+        hidden = r["t_ret_overlapped_ms"] <= r["t_gen_overlapped_ms"]
+        print(f"| {r['seq_len']} | {r['t_gen_ms']:.3f} | {r['nprobe']} | {r['predicted_ret_ms']:.3f} | {r['t_ret_alone_ms']:.3f} | "
+              f"{r['t_gen_overlapped_ms']:.3f} | {r['t_ret_overlapped_ms']:.3f} | {'yes' if hidden else 'no'} |")
+    print(json.dumps({"workload": cfg.name, "fit_ms": {"a": float(fit[0]), "b": float(fit[1])}, "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,6 +276,8 @@ def main():
                     help="also launch a plain 1 GiB copy kernel three times (reference for the HBM traffic counters)")
     ap.add_argument("--nprobe-sweep", action="store_true",
                     help="instead of the bench line: latency and recall against nprobe on the chosen workload (meant for cfg2)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="instead of the bench line: retrieval sized by the latency model, run beside a synthetic generation step")
     ap.add_argument("--summarize", metavar="DIR", help="write a text summary of rocprofv3 CSV output found under DIR and exit")
     ap.add_argument("--command", default="", help="with --summarize: the command line that produced DIR")
     args = ap.parse_args()
@@ -232,6 +297,9 @@ def main():
     cfg = gen.CONFIGS[args.workload]
     if args.nprobe_sweep:
         nprobe_sweep(args, pkg, cfg, torch)
+        return
+    if args.overlap:
+        overlap_demo(args, pkg, cfg, torch)
         return
     log(f"[bench] building {cfg.name}: N={cfg.N} d={cfg.d} nlist={cfg.nlist} M={cfg.M}")
     ix, g, info = build_index(pkg, cfg, torch, max_nq=max(cfg.nq, 1))

@@ -123,6 +123,31 @@ int piperag_latency_profile(const piperag_index *index, const float *queries_dev
                             const int32_t *nprobes_host, int32_t n_nprobes, int32_t k, int32_t reps,
                             float *out_p50_ms_host, float *out_fit_host, void *stream);
 
+/* ---- performance model (host arithmetic, no GPU work) -------------------------------------- */
+
+/* Inversion of the retrieval performance model (Section 3.2, S3: given the time T(C) it takes to generate
+ * the next token chunk, derive the maximal nprobe whose predicted retrieval latency stays within it).
+ * fit_host[2] = the line latency_ms = fit[0] + fit[1]*nprobe (as written by piperag_latency_profile);
+ * overhead_ms = the part of the retrieval latency outside the search (network, query encoding; >= 0).
+ * *out_nprobe = the largest nprobe in 1..nprobe_cap with overhead_ms + fit[0] + fit[1]*nprobe <= budget_ms;
+ * when even nprobe = 1 does not fit, *out_nprobe = 1 and *out_fits = 0 (a retrieval is always made),
+ * otherwise *out_fits = 1.  A slope <= 0 (latency does not grow with nprobe) gives nprobe_cap if nprobe = 1
+ * fits.  out_predicted_ms (optional) = the predicted latency at the chosen nprobe, overhead included.
+ * PIPERAG_ERR_ARG for NULL pointers, nprobe_cap < 1 or non-finite inputs. */
+int piperag_max_nprobe(const float *fit_host, float overhead_ms, float budget_ms, int32_t nprobe_cap,
+                       int32_t *out_nprobe, int32_t *out_fits, float *out_predicted_ms);
+
+/* End-to-end generation latency projected for faster retrieval or inference hardware (Appendix
+ * "Performance Modeling for Future Hardware").  inference_ms_host[c], retrieval_ms_host[c]: measured
+ * latency of generating token chunk c and of the retrieval issued for it, c = 0..nchunks-1; each is divided
+ * by its speed-up factor (> 0).  Sequential generation (the baseline that waits for every retrieval) takes
+ * the sum of all inference and retrieval times; pipelined generation takes inference + retrieval for the
+ * first chunk, where the pipeline is not yet active, and max(inference, retrieval) for every later chunk.
+ * Sums are accumulated in double precision in chunk order.  nchunks >= 1. */
+int piperag_project_latency(const float *inference_ms_host, const float *retrieval_ms_host, int32_t nchunks,
+                            float inference_speedup, float retrieval_speedup, double *out_sequential_ms,
+                            double *out_pipelined_ms);
+
 /* ---- stage taps (each step of the search path by itself, for checking) ------------------- */
 
 /* Coarse quantiser (the index-scan term of the latency model, Section 3.2, S3): the nprobe closest

@@ -8,6 +8,8 @@ anywhere, but any call fails loudly if the shared library has not been built.
 from .binding import (  # noqa: F401
     Index,
     kmeans,
+    max_nprobe,
+    project_latency,
     PiperagError,
     lib_path,
     load_library,

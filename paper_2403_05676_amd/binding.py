@@ -50,6 +50,8 @@ def load_library() -> C.CDLL:
         "piperag_ivf_save": [vp, C.c_char_p],
         "piperag_ivfpq_search": [vp, vp, i32, i32, i32, vp, vp, vp],
         "piperag_latency_profile": [vp, vp, i32, vp, i32, i32, i32, vp, vp, vp],
+        "piperag_max_nprobe": [vp, C.c_float, C.c_float, i32, vp, vp, vp],
+        "piperag_project_latency": [vp, vp, i32, C.c_float, C.c_float, vp, vp],
         "piperag_ivf_coarse": [vp, vp, i32, i32, vp, vp, vp],
         "piperag_ivf_lut": [vp, vp, i32, vp, vp],
         "piperag_ivfpq_search_probes": [vp, vp, i32, vp, i32, i32, vp, vp, vp],
@@ -88,6 +90,27 @@ def _dev(t: torch.Tensor, dtype: torch.dtype) -> int:
     if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
     return t.data_ptr()
+
+
+def max_nprobe(fit, budget_ms: float, nprobe_cap: int, overhead_ms: float = 0.0):
+    """piperag_max_nprobe: (nprobe, fits, predicted_ms)."""
+    f = np.ascontiguousarray(fit, dtype=np.float32)
+    assert f.shape == (2,)
+    npr, fits, pred = C.c_int32(), C.c_int32(), C.c_float()
+    _check(load_library().piperag_max_nprobe(f.ctypes.data, float(overhead_ms), float(budget_ms), int(nprobe_cap),
+                                             C.addressof(npr), C.addressof(fits), C.addressof(pred)))
+    return npr.value, bool(fits.value), pred.value
+
+
+def project_latency(inference_ms, retrieval_ms, inference_speedup: float = 1.0, retrieval_speedup: float = 1.0):
+    """piperag_project_latency: (sequential_ms, pipelined_ms)."""
+    ti = np.ascontiguousarray(inference_ms, dtype=np.float32)
+    tr = np.ascontiguousarray(retrieval_ms, dtype=np.float32)
+    assert ti.ndim == 1 and ti.shape == tr.shape
+    seq, pipe = C.c_double(), C.c_double()
+    _check(load_library().piperag_project_latency(ti.ctypes.data, tr.ctypes.data, ti.shape[0], float(inference_speedup),
+                                                  float(retrieval_speedup), C.addressof(seq), C.addressof(pipe)))
+    return seq.value, pipe.value
 
 
 def kmeans(x: torch.Tensor, K: int, init_rows: np.ndarray, iters: int = 10, return_inertia: bool = False):
