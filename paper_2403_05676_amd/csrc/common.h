@@ -85,6 +85,7 @@ struct piperag_index {
     float *cnorm;      // [nlist] squared norms of the centres
     uint16_t *cent_hi, *cent_lo;   // bf16 split of the centres for the encoder, chunk-major (NULL when the shape rules it out)
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
+    float *pq_norm;    // [M*256] squared norms of the codebook centres (for the encoder)
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize
     int64_t cap, nadded;

@@ -405,3 +405,14 @@ def test_repeated_calls_replay_a_captured_graph_with_fresh_inputs(cfg0):
         torch.cuda.synchronize()
         parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), oidx, q[sel], gl.cpu().numpy(), cfg.k)
         assert float(junk) == float(junk)
+
+
+def test_largest_nprobe_and_k():
+    # the limits of a search call: nprobe = 1024 of 1100 short lists, k = 1024, one query and a small batch
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(40000, 32, 1100, 8, seed=321, nq=5, iters=2)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=8, max_nprobe=1024, max_k=1024)
+    run_search_parity(pkg, ix, oidx, q, 1024, 1024)
+    run_search_parity(pkg, ix, oidx, q[:1], 1024, 100)
+    run_search_parity(pkg, ix, oidx, q, 1000, 1)
