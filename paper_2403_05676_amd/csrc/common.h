@@ -66,6 +66,9 @@ inline int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 // vector in slot 64*b + l (zero when that index is >= M).  One 16-byte load per lane per chunk is thus a
 // contiguous 1 KiB wavefront access, and at step t the 64 lanes look up 64 different sub-quantisers.
 // A search call seen before, and its captured graph once it has been seen twice.
+// depth rows of the encoder's codebook copy: the coordinates, one row of squared norms, rounded up to even
+inline int pqe_rows(int dsub) { return (dsub + 2) / 2 * 2; }
+
 struct SearchGraph {
     const float *q;
     const int32_t *probes;
@@ -85,7 +88,7 @@ struct piperag_index {
     float *cnorm;      // [nlist] squared norms of the centres
     uint16_t *cent_hi, *cent_lo;   // bf16 split of the centres for the encoder, chunk-major (NULL when the shape rules it out)
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
-    float *pq_norm;    // [M*256] squared norms of the codebook centres (for the encoder)
+    float *pqE;        // [M][pqe_rows(dsub)][256] the encoder's copy: pqE[m][t][j] = pq[m][j][t], row dsub = squared norms, then zeros
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
     // staging area, filled by add / add_encoded until finalize
     int64_t cap, nadded;

@@ -156,23 +156,19 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
 }
 
 // PQ encoding on the matrix cores: code[x][m] = argmin_j |x_m - P[m][j]|^2 = argmin_j (|P[m][j]|^2 - 2 <x_m, P[m][j]>).
-// One workgroup = 128 vectors, a wave = 32 of them; for each sub-quantiser the 256 centres (depth-major in LDS,
-// padded rows so that both the staging writes and the fragment reads are free of bank conflicts) are the row
-// operand of v_mfma_f32_32x32x2f32 and the wave's 32 vectors the column operand: 8 blocks of 32 centres x 32
-// vectors, dsub/2 instructions each.  A lane then holds 128 centres of one vector in its own registers and
-// keeps the running best in ascending centre order (strict "<": lower index on equal values); the two lanes
-// that share a vector are combined with one shuffle.  Codes are collected in LDS and written out as one
-// contiguous run.  dsub <= 32.
-constexpr int kPqLd = kKsub + 1;                     // padded row of the staged centres
-
+// One workgroup = 128 vectors, a wave = 32 of them; for each sub-quantiser the 256 centres are the row operand of
+// v_mfma_f32_32x32x2f32 and the wave's 32 vectors the column operand: 8 blocks of 32 centres x 32 vectors.  The
+// centres come from the depth-major copy pqE[m][t][j], whose row t = dsub holds the squared norms: with the
+// vectors entered as (-2 x_m, 1) the product is the quantity to minimise itself.  A lane then holds 128 centres
+// of one vector in its own registers and keeps the running best in ascending centre order (strict "<": lower
+// index on equal values); the two lanes that share a vector are combined with one shuffle.  Codes are
+// collected in LDS and written out as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
 __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__restrict__ x, int64_t n, int d,
-                                                             const float *__restrict__ pq, const float *__restrict__ pqn,
-                                                             int M, int dsub, uint8_t *__restrict__ out_codes) {
+                                                             const float *__restrict__ pqE, int M, int dsub, int T,
+                                                             uint8_t *__restrict__ out_codes) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int npairs = (dsub + 1) / 2;
-    float *sA = reinterpret_cast<float *>(smem);                  // [2*npairs][kPqLd]: sA[t][j] = P[m][j][t] (0 beyond dsub)
-    float *sN = sA + 2 * npairs * kPqLd;                          // [256] squared norms of the centres
-    uint8_t *code_s = reinterpret_cast<uint8_t *>(sN + kKsub);    // [128][M]
+    float *sA = reinterpret_cast<float *>(smem);                  // [T][256]
+    uint8_t *code_s = reinterpret_cast<uint8_t *>(sA + T * kKsub);   // [128][M]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int64_t row0 = (int64_t)blockIdx.x * 128;
     const int rows = (int)min<int64_t>(128, n - row0);
@@ -181,23 +177,19 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
     const bool live = myrow < n;
     for (int m = 0; m < M; ++m) {
         __syncthreads();                                          // the previous sub-quantiser's centres are no longer read
-        const float *pm = pq + (size_t)m * kKsub * dsub;
-        for (int e = tid; e < kKsub * dsub; e += 256) {
-            const int j = e / dsub, t = e - j * dsub;
-            sA[t * kPqLd + j] = pm[e];
-        }
-        if (dsub & 1) sA[dsub * kPqLd + tid] = 0.f;               // the odd depth's partner
-        sN[tid] = pqn[m * kKsub + tid];
+        const float4 *src = reinterpret_cast<const float4 *>(pqE + (size_t)m * T * kKsub);
+        for (int e = tid; e < T * kKsub / 4; e += 256) reinterpret_cast<float4 *>(sA)[e] = src[e];
         __syncthreads();
         mfma_acc_t acc[8];
 #pragma unroll
         for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bi][r] = 0.f;
-        for (int p = 0; p < npairs; ++p) {
+        for (int p = 0; p < T / 2; ++p) {
             const int t = 2 * p + half;                           // lanes 0-31: depth 2p, lanes 32-63: depth 2p + 1
-            const float bv = live && t < dsub ? xr[m * dsub + t] : 0.f;
-            const float *a = sA + t * kPqLd + l32;
+            float bv = t == dsub ? 1.f : 0.f;                     // the row of norms; padding rows are zero on both sides
+            if (t < dsub) bv = live ? -2.f * xr[m * dsub + t] : 0.f;
+            const float *a = sA + t * kKsub + l32;
 #pragma unroll
             for (int bi = 0; bi < 8; ++bi) acc[bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi * 32], bv, acc[bi], 0, 0, 0);
         }
@@ -206,13 +198,9 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
 #pragma unroll
         for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int j0 = bi * 32 + 4 * half + 8 * g;        // registers 4g .. 4g+3 are centres j0 .. j0+3
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float v = sN[j0 + u] - 2.f * acc[bi][4 * g + u];
-                    if (v < best) { best = v; bj = j0 + u; }
-                }
+            for (int r = 0; r < 16; ++r) {
+                const float v = acc[bi][r];
+                if (v < best) { best = v; bj = bi * 32 + (r % 4) + 4 * half + 8 * (r / 4); }   // ascending in bi, r
             }
         const float ov = __shfl_xor(best, 32, 64);
         const int oj = __shfl_xor(bj, 32, 64);
@@ -523,7 +511,8 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
         if (out_codes) {
             if (ix->dsub >= 4) {                                 // matrix cores
-                const size_t lds = sizeof(float) * ((size_t)2 * ((ix->dsub + 1) / 2) * kPqLd + kKsub) + (size_t)128 * p.M;
+                const int T = pqe_rows(ix->dsub);
+                const size_t lds = sizeof(float) * (size_t)T * kKsub + (size_t)128 * p.M;
                 static size_t configured = 0;
                 if (lds > configured) {
                     PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&pq_encode_mfma_kernel),
@@ -531,7 +520,7 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out
                     configured = lds;
                 }
                 hipLaunchKernelGGL(pq_encode_mfma_kernel, dim3((unsigned)((cnt + 127) / 128)), dim3(256), lds, st, x + a * p.d, cnt,
-                                   p.d, ix->pq, ix->pq_norm, p.M, ix->dsub, out_codes + (size_t)a * p.M);
+                                   p.d, ix->pqE, p.M, ix->dsub, T, out_codes + (size_t)a * p.M);
             } else {
                 const size_t lds = sizeof(float) * 2 * kKsub * ix->dsub + (size_t)256 * p.M;
                 static size_t configured = 0;

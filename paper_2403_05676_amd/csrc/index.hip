@@ -219,7 +219,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_part, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->ws_done, (size_t)kMaxScanWGs + 2 * (size_t)p.max_nq)) ||
-        (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->pq_norm, (size_t)p.M * kKsub)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
+        (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->pqE, (size_t)p.M * pqe_rows(ix->dsub) * kKsub)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->ws_qn, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
@@ -236,7 +236,6 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         split_bf16(ix->centroids, p.nlist, p.d, ix->cent_hi, ix->cent_lo, nullptr);
     }
     rownorm(ix->centroids, p.nlist, p.d, p.d, ix->cnorm, nullptr);
-    rownorm(ix->pq, (int64_t)p.M * kKsub, ix->dsub, ix->dsub, ix->pq_norm, nullptr);
     if (hipStreamSynchronize(nullptr) != hipSuccess) { set_error("centre norms failed"); return fail(PIPERAG_ERR_HIP); }
     {   // centre-major copy of the codebook
         std::vector<float> t(npq);
@@ -244,6 +243,24 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
             for (int j = 0; j < kKsub; ++j)
                 memcpy(&t[((size_t)j * p.M + m) * ix->dsub], &pq_host[((size_t)m * kKsub + j) * ix->dsub], sizeof(float) * ix->dsub);
         if (hipMemcpy(ix->pqT, t.data(), npq * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
+            set_error("upload of trained parameters failed");
+            return fail(PIPERAG_ERR_HIP);
+        }
+    }
+    {   // the encoder's copy of the codebook: depth-major, with the centres' squared norms as one more depth row
+        const int T = pqe_rows(ix->dsub);
+        std::vector<float> t((size_t)p.M * T * kKsub, 0.f);
+        for (int m = 0; m < p.M; ++m)
+            for (int j = 0; j < kKsub; ++j) {
+                const float *c = &pq_host[((size_t)m * kKsub + j) * ix->dsub];
+                float nn = 0.f;
+                for (int u = 0; u < ix->dsub; ++u) {
+                    t[((size_t)m * T + u) * kKsub + j] = c[u];
+                    nn += c[u] * c[u];
+                }
+                t[((size_t)m * T + ix->dsub) * kKsub + j] = nn;
+            }
+        if (hipMemcpy(ix->pqE, t.data(), t.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
             set_error("upload of trained parameters failed");
             return fail(PIPERAG_ERR_HIP);
         }
@@ -299,7 +316,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
-    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->pq_norm, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
+    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
                     ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
