@@ -93,6 +93,21 @@ int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const i
 int piperag_ivf_add_encoded(piperag_index *index, const int32_t *lists_dev, const uint8_t *codes_dev,
                             const int64_t *ids_dev, int64_t n, void *stream);
 
+/* Two-pass build, for databases whose per-vector staging area (M + 12 bytes per vector until finalize) would not
+ * fit beside the finished index: the caller presents the database twice, in the same order (any tiling).
+ *   pass 1  piperag_ivf_count(index, x_dev, n, stream)        assigns the n vectors to their lists, keeps the list
+ *                                                             numbers (4 bytes per vector) and counts the lists;
+ *           piperag_ivf_reserve(index, stream)                sizes the lists and allocates the index (synchronises);
+ *   pass 2  piperag_ivf_place(index, x_dev, n, ids_dev, stream)  computes the codes of the next n vectors and puts
+ *                                                             them, in order, straight into their lists;
+ *           piperag_ivf_finalize(index, stream)               as below; every counted vector must have been placed.
+ * The result is identical to that of piperag_ivf_add + finalize on the same sequence.  ids_dev NULL numbers the
+ * vectors by position.  A build uses either piperag_ivf_add / add_encoded or count / place, not both
+ * (PIPERAG_ERR_ARG).  Peak memory is the index plus 4 bytes per vector. */
+int piperag_ivf_count(piperag_index *index, const float *x_dev, int64_t n, void *stream);
+int piperag_ivf_reserve(piperag_index *index, void *stream);
+int piperag_ivf_place(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream);
+
 /* Groups everything added so far into inverted lists (inside a list: order of addition) and builds the
  * scan layout.  Synchronises `stream`; allocates.  Afterwards the index is searchable and closed to adds. */
 int piperag_ivf_finalize(piperag_index *index, void *stream);

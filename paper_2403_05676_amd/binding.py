@@ -47,6 +47,9 @@ def load_library() -> C.CDLL:
         "piperag_ivf_add": [vp, vp, i64, vp, vp],
         "piperag_ivf_add_encoded": [vp, vp, vp, vp, i64, vp],
         "piperag_ivf_finalize": [vp, vp],
+        "piperag_ivf_count": [vp, vp, i64, vp],
+        "piperag_ivf_reserve": [vp, vp],
+        "piperag_ivf_place": [vp, vp, i64, vp, vp],
         "piperag_ivf_save": [vp, C.c_char_p],
         "piperag_ivfpq_search": [vp, vp, i32, i32, i32, vp, vp, vp],
         "piperag_latency_profile": [vp, vp, i32, vp, i32, i32, i32, vp, vp, vp],
@@ -180,6 +183,16 @@ class Index:
         n = lists.shape[0]
         _check(load_library().piperag_ivf_add_encoded(self._h, _dev(lists, torch.int32), _dev(codes, torch.uint8),
                                                       _dev(ids, torch.int64) if ids is not None else None, n, _stream()))
+
+    def ivf_count(self, x: torch.Tensor) -> None:
+        _check(load_library().piperag_ivf_count(self._h, _dev(x, torch.float32), x.shape[0], _stream()))
+
+    def ivf_reserve(self) -> None:
+        _check(load_library().piperag_ivf_reserve(self._h, _stream()))
+
+    def ivf_place(self, x: torch.Tensor, ids: torch.Tensor | None = None) -> None:
+        _check(load_library().piperag_ivf_place(self._h, _dev(x, torch.float32), x.shape[0],
+                                                _dev(ids, torch.int64) if ids is not None else None, _stream()))
 
     def ivf_finalize(self) -> None:
         _check(load_library().piperag_ivf_finalize(self._h, _stream()))

@@ -90,11 +90,19 @@ struct piperag_index {
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
     float *pqE;        // [M][pqe_rows(dsub)][256] the encoder's copy: pqE[m][t][j] = pq[m][j][t], row dsub = squared norms, then zeros
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
-    // staging area, filled by add / add_encoded until finalize
+    // Build state.  One-pass build (add / add_encoded, then finalize): a staging area of list number, canonical
+    // code row and id per vector, allocated at the first add.  Two-pass build (count, reserve, place, finalize)
+    // for databases whose staging area would not fit beside the index: pass 1 keeps only the list numbers and
+    // counts the lists, reserve sizes the lists, pass 2 places every tile straight into the scan layout.
+    int build_mode;     // 0 nothing added yet, 1 one-pass, 2 two-pass
     int64_t cap, nadded;
-    int32_t *st_list;   // [cap]
-    uint8_t *st_codes;  // [cap*M] canonical rows
-    int64_t *st_ids;    // [cap]
+    int32_t *st_list;   // [cap] (both modes)
+    uint8_t *st_codes;  // [cap*M] canonical rows (one-pass)
+    int64_t *st_ids;    // [cap] (one-pass)
+    uint32_t *bd_counts;   // [nlist] list sizes counted in pass 1 (two-pass)
+    uint32_t *bd_cursor;   // [nlist] entries of each list placed so far (two-pass)
+    int64_t nplaced;       // vectors placed in pass 2
+    bool reserved;         // lists are sized, codes / ids allocated (two-pass)
     bool finalized;
     // scan layout (after finalize)
     int64_t ntotal, nblocks;
@@ -140,3 +148,12 @@ struct piperag_index {
     uint64_t graph_clock;
     bool ev_valid;
 };
+
+namespace piperag {
+// build plumbing shared by index.hip and encode.hip
+int begin_build(piperag_index *ix, int mode);     // allocates what the build mode needs at its first call; rejects mixing modes
+int place_tile(piperag_index *ix, const int32_t *lists_dev, const uint8_t *codes_dev, const int64_t *ids_dev, int64_t n, hipStream_t st);
+void fill_iota(int64_t *dst, int64_t n, int64_t first, hipStream_t st);
+void count_lists(const int32_t *lists, int64_t n, uint32_t *counts, hipStream_t st);
+}  // namespace piperag
+

@@ -632,4 +632,55 @@ int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const i
     return PIPERAG_OK;
 }
 
+int piperag_ivf_count(piperag_index *index, const float *x_dev, int64_t n, void *stream) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    PR_REQUIRE(n >= 0, PIPERAG_ERR_ARG, "n = %lld is negative", (long long)n);
+    PR_REQUIRE(!index->finalized && !index->reserved, PIPERAG_ERR_ARG, "count calls come before reserve");
+    PR_REQUIRE(index->nadded + n <= index->cap, PIPERAG_ERR_LIMIT, "counting %lld vectors after %lld exceeds the capacity %lld",
+               (long long)n, (long long)index->nadded, (long long)index->cap);
+    if (n == 0) return PIPERAG_OK;
+    PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
+    int rc = begin_build(index, 2);
+    if (rc != PIPERAG_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    PR_CHECK_HIP(hipSetDevice(index->device));
+    const piperag_params &p = index->p;
+    int32_t *lists = index->st_list + index->nadded;
+    rc = launch_assign(x_dev, n, p.d, p.d, index->centroids, index->cnorm, index->cent_hi, index->cent_lo, p.nlist, lists, nullptr, st);
+    if (rc != PIPERAG_OK) return rc;
+    count_lists(lists, n, index->bd_counts, st);
+    index->nadded += n;
+    PR_CHECK_HIP(hipGetLastError());
+    return PIPERAG_OK;
+}
+
+int piperag_ivf_place(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    PR_REQUIRE(n >= 0, PIPERAG_ERR_ARG, "n = %lld is negative", (long long)n);
+    PR_REQUIRE(!index->finalized && index->build_mode == 2 && index->reserved, PIPERAG_ERR_ARG, "place calls come after reserve");
+    PR_REQUIRE(index->nplaced + n <= index->nadded, PIPERAG_ERR_LIMIT, "placing %lld vectors after %lld exceeds the %lld counted",
+               (long long)n, (long long)index->nplaced, (long long)index->nadded);
+    if (n == 0) return PIPERAG_OK;
+    PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    PR_CHECK_HIP(hipSetDevice(index->device));
+    const piperag_params &p = index->p;
+    uint8_t *codes = nullptr;
+    int64_t *ids = nullptr;
+    PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&codes), (size_t)n * p.M, st));
+    if (!ids_dev) {
+        const hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ids), sizeof(int64_t) * (size_t)n, st);
+        if (e != hipSuccess) { (void)hipFreeAsync(codes, st); set_error("scratch allocation failed: %s", hipGetErrorString(e)); return PIPERAG_ERR_OOM; }
+        fill_iota(ids, n, index->nplaced, st);
+    }
+    int rc = encode_impl(index, x_dev, n, nullptr, codes, st);
+    if (rc == PIPERAG_OK) rc = place_tile(index, index->st_list + index->nplaced, codes, ids_dev ? ids_dev : ids, n, st);
+    (void)hipFreeAsync(codes, st);
+    if (ids) (void)hipFreeAsync(ids, st);
+    if (rc != PIPERAG_OK) return rc;
+    index->nplaced += n;
+    PR_CHECK_HIP(hipGetLastError());
+    return PIPERAG_OK;
+}
+
 }  // extern "C"

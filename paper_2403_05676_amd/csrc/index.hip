@@ -33,17 +33,30 @@ __global__ void hist_kernel(const int32_t *__restrict__ st_list, int64_t n, int6
     for (int64_t i = a + threadIdx.x; i < b; i += blockDim.x) atomicAdd(&H[(size_t)g * nlist + st_list[i]], 1u);
 }
 
-// Turns H into exclusive prefix sums over the chunks (per list) and writes the list lengths.
-__global__ void colscan_kernel(uint32_t *__restrict__ H, int G, int nlist, int32_t *__restrict__ list_len) {
+// Turns H into exclusive prefix sums over the chunks (per list).  Without a cursor the sums start at 0 and the
+// totals are written to list_len (the whole staging area at once); with a cursor they start at cursor[l], the
+// number of entries of list l placed by earlier tiles, and the cursor moves on by the tile's total.
+__global__ void colscan_kernel(uint32_t *__restrict__ H, int G, int nlist, int32_t *__restrict__ list_len,
+                               uint32_t *__restrict__ cursor) {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
-    uint32_t run = 0;
+    uint32_t run = cursor ? cursor[l] : 0;
     for (int g = 0; g < G; ++g) {
         const uint32_t c = H[(size_t)g * nlist + l];
         H[(size_t)g * nlist + l] = run;
         run += c;
     }
-    list_len[l] = (int32_t)run;
+    if (cursor) cursor[l] = run; else list_len[l] = (int32_t)run;
+}
+
+// counts[l] += number of entries with list l
+__global__ void count_lists_kernel(const int32_t *__restrict__ lists, int64_t n, uint32_t *__restrict__ counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) atomicAdd(&counts[lists[i]], 1u);
+}
+__global__ void counts_to_len_kernel(const uint32_t *__restrict__ counts, int nlist, int32_t *__restrict__ list_len) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l < nlist) list_len[l] = (int32_t)counts[l];
 }
 
 // list_blk[l] = sum over l' < l of ceil(len[l'] / 64); one workgroup, sequential over tiles of 1024 lists.
@@ -142,6 +155,11 @@ __global__ void gather_list_kernel(const uint8_t *__restrict__ codes, const int6
     }
 }
 
+__global__ void fill_u32_kernel(uint32_t *__restrict__ dst, size_t n, uint32_t v) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = v;
+}
+
 __global__ void iota_ids_kernel(int64_t *__restrict__ dst, int64_t n, int64_t first) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = first + i;
@@ -185,6 +203,8 @@ void free_staging(piperag_index *ix) {
     (void)hipFree(ix->st_list); ix->st_list = nullptr;
     (void)hipFree(ix->st_codes); ix->st_codes = nullptr;
     (void)hipFree(ix->st_ids); ix->st_ids = nullptr;
+    (void)hipFree(ix->bd_counts); ix->bd_counts = nullptr;
+    (void)hipFree(ix->bd_cursor); ix->bd_cursor = nullptr;
 }
 
 int create_impl(const piperag_params *params, const float *cent_host, const float *pq_host, piperag_index **out) {
@@ -206,8 +226,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     const piperag_params &p = ix->p;
     const size_t ncent = (size_t)p.nlist * p.d, npq = (size_t)p.M * kKsub * ix->dsub;
     if ((rc = dev_alloc(&ix->centroids, ncent)) || (rc = dev_alloc(&ix->pq, npq)) ||
-        (rc = dev_alloc(&ix->st_list, (size_t)ix->cap)) || (rc = dev_alloc(&ix->st_codes, (size_t)ix->cap * p.M)) ||
-        (rc = dev_alloc(&ix->st_ids, (size_t)ix->cap)) || (rc = dev_alloc(&ix->list_blk, (size_t)p.nlist + 1)) ||
+        (rc = dev_alloc(&ix->list_blk, (size_t)p.nlist + 1)) ||
         (rc = dev_alloc(&ix->list_len, (size_t)p.nlist)) || (rc = dev_alloc(&ix->ws_D, (size_t)p.max_nq * p.nlist * (p.nlist <= kCoarseSplitMaxLists ? kCoarseMaxParts : 1))) ||
         (rc = dev_alloc(&ix->ws_probe, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_probe_d, (size_t)p.max_nq * p.max_nprobe)) ||
@@ -292,6 +311,28 @@ int append_common(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStrea
 }  // namespace
 
 namespace piperag {
+int begin_build(piperag_index *ix, int mode) {
+    PR_REQUIRE(ix != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    PR_REQUIRE(!ix->finalized, PIPERAG_ERR_ARG, "index is finalized; no more vectors can be added");
+    if (ix->build_mode == mode) return PIPERAG_OK;
+    PR_REQUIRE(ix->build_mode == 0, PIPERAG_ERR_ARG, "one-pass (add) and two-pass (count / place) builds cannot be mixed");
+    PR_CHECK_HIP(hipSetDevice(ix->device));
+    int rc = dev_alloc(&ix->st_list, (size_t)ix->cap);
+    if (rc == PIPERAG_OK && mode == 1) rc = dev_alloc(&ix->st_codes, (size_t)ix->cap * ix->p.M);
+    if (rc == PIPERAG_OK && mode == 1) rc = dev_alloc(&ix->st_ids, (size_t)ix->cap);
+    if (rc == PIPERAG_OK && mode == 2) rc = dev_alloc(&ix->bd_counts, (size_t)ix->p.nlist);
+    if (rc == PIPERAG_OK && mode == 2) rc = dev_alloc(&ix->bd_cursor, (size_t)ix->p.nlist);
+    if (rc == PIPERAG_OK && mode == 2 &&
+        (hipMemset(ix->bd_counts, 0, sizeof(uint32_t) * ix->p.nlist) != hipSuccess ||
+         hipMemset(ix->bd_cursor, 0, sizeof(uint32_t) * ix->p.nlist) != hipSuccess)) {
+        set_error("clearing the list counters failed");
+        rc = PIPERAG_ERR_HIP;
+    }
+    if (rc != PIPERAG_OK) { free_staging(ix); return rc; }
+    ix->build_mode = mode;
+    return PIPERAG_OK;
+}
+
 // used by encode.hip
 int check_can_add(piperag_index *ix, int64_t n) {
     PR_REQUIRE(ix != nullptr, PIPERAG_ERR_ARG, "index is NULL");
@@ -299,7 +340,32 @@ int check_can_add(piperag_index *ix, int64_t n) {
     PR_REQUIRE(n >= 0, PIPERAG_ERR_ARG, "n = %lld is negative", (long long)n);
     PR_REQUIRE(ix->nadded + n <= ix->cap, PIPERAG_ERR_LIMIT, "adding %lld vectors to %lld exceeds the capacity %lld",
                (long long)n, (long long)ix->nadded, (long long)ix->cap);
+    return n > 0 ? begin_build(ix, 1) : PIPERAG_OK;
+}
+
+// Places one tile of encoded vectors (two-pass build): lists_dev[i], codes_dev[i*M..], ids_dev[i] for i < n go to
+// the next free slots of their lists, in order (a stable counting sort of the tile on top of the per-list
+// cursors).  Scratch is taken and returned in stream order.
+int place_tile(piperag_index *ix, const int32_t *lists_dev, const uint8_t *codes_dev, const int64_t *ids_dev, int64_t n,
+               hipStream_t st) {
+    const int nlist = ix->p.nlist;
+    const int64_t chunk = round_up64(std::max<int64_t>((n + 1023) / 1024, 4096), kPlaceTile);
+    const int G = (int)std::max<int64_t>(1, (n + chunk - 1) / chunk);
+    uint32_t *H = nullptr;
+    PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&H), sizeof(uint32_t) * (size_t)G * nlist, st));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)(((size_t)G * nlist + 255) / 256)), dim3(256), 0, st, H, (size_t)G * nlist, 0u);
+    hipLaunchKernelGGL(hist_kernel, dim3(G), dim3(256), 0, st, lists_dev, n, chunk, nlist, H);
+    hipLaunchKernelGGL(colscan_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, H, G, nlist, (int32_t *)nullptr, ix->bd_cursor);
+    hipLaunchKernelGGL(place_kernel, dim3(G), dim3(kPlaceTile), 0, st, lists_dev, codes_dev, ids_dev, n, chunk, nlist, ix->p.M,
+                       ix->Mp, H, ix->list_blk, ix->codes, ix->ids);
+    PR_CHECK_HIP(hipFreeAsync(H, st));
     return PIPERAG_OK;
+}
+void fill_iota(int64_t *dst, int64_t n, int64_t first, hipStream_t st) {
+    hipLaunchKernelGGL(iota_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dst, n, first);
+}
+void count_lists(const int32_t *lists, int64_t n, uint32_t *counts, hipStream_t st) {
+    hipLaunchKernelGGL(count_lists_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, lists, n, counts);
 }
 int append_ids(piperag_index *ix, int64_t n, const int64_t *ids_dev, hipStream_t st) { return append_common(ix, n, ids_dev, st); }
 }  // namespace piperag
@@ -356,11 +422,70 @@ int piperag_ivf_add_encoded(piperag_index *ix, const int32_t *lists_dev, const u
     return PIPERAG_OK;
 }
 
+// Sizes the lists (list_len is set), lays out the blocks and allocates the scan layout, cleared to "no vector".
+static int allocate_lists(piperag_index *ix, hipStream_t st) {
+    const int nlist = ix->p.nlist;
+    hipLaunchKernelGGL(blockscan_kernel, dim3(1), dim3(1024), 0, st, ix->list_len, nlist, ix->list_blk);
+    int32_t nblocks = 0;
+    hipError_t e = hipMemcpyAsync(&nblocks, ix->list_blk + nlist, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { set_error("sizing the lists failed: %s", hipGetErrorString(e)); return PIPERAG_ERR_HIP; }
+    ix->nblocks = nblocks;
+    PR_REQUIRE((int64_t)nblocks * kBlockVecs < 0xFFFFFFFFll, PIPERAG_ERR_LIMIT, "too many slots for 32-bit positions");
+    const size_t code_bytes = (size_t)std::max<int64_t>(nblocks, 1) * kBlockVecs * ix->Mp;
+    const size_t nslots = (size_t)std::max<int64_t>(nblocks, 1) * kBlockVecs;
+    if (hipMalloc(reinterpret_cast<void **>(&ix->codes), code_bytes) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&ix->ids), nslots * sizeof(int64_t)) != hipSuccess) {
+        set_error("out of device memory for %zu bytes of codes", code_bytes);
+        return PIPERAG_ERR_OOM;
+    }
+    e = hipMemsetAsync(ix->codes, 0, code_bytes, st);
+    if (e == hipSuccess) e = hipMemsetAsync(ix->ids, 0xFF, nslots * sizeof(int64_t), st);
+    if (e != hipSuccess) { set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return PIPERAG_ERR_HIP; }
+    return PIPERAG_OK;
+}
+
+static int finish_build(piperag_index *ix, int64_t n) {
+    std::vector<int32_t> hl(ix->p.nlist);
+    if (hipMemcpy(hl.data(), ix->list_len, sizeof(int32_t) * ix->p.nlist, hipMemcpyDeviceToHost) != hipSuccess) {
+        set_error("finalize (list lengths) failed");
+        return PIPERAG_ERR_HIP;
+    }
+    ix->max_list_len = 0;
+    for (int32_t v : hl) ix->max_list_len = std::max<int64_t>(ix->max_list_len, v);
+    free_staging(ix);
+    ix->ntotal = n;
+    ix->finalized = true;
+    return PIPERAG_OK;
+}
+
+int piperag_ivf_reserve(piperag_index *ix, void *stream) {
+    PR_REQUIRE(ix != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    PR_REQUIRE(!ix->finalized && ix->build_mode == 2 && !ix->reserved, PIPERAG_ERR_ARG,
+               "reserve follows the count calls of a two-pass build, once");
+    hipStream_t st = (hipStream_t)stream;
+    PR_CHECK_HIP(hipSetDevice(ix->device));
+    hipLaunchKernelGGL(counts_to_len_kernel, dim3((ix->p.nlist + 255) / 256), dim3(256), 0, st, ix->bd_counts, ix->p.nlist,
+                       ix->list_len);
+    PR_TRY(allocate_lists(ix, st));
+    PR_CHECK_HIP(hipStreamSynchronize(st));
+    ix->reserved = true;
+    return PIPERAG_OK;
+}
+
 int piperag_ivf_finalize(piperag_index *ix, void *stream) {
     PR_REQUIRE(ix != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     PR_REQUIRE(!ix->finalized, PIPERAG_ERR_ARG, "index is already finalized");
     hipStream_t st = (hipStream_t)stream;
     PR_CHECK_HIP(hipSetDevice(ix->device));
+    if (ix->build_mode == 2) {
+        PR_REQUIRE(ix->reserved && ix->nplaced == ix->nadded, PIPERAG_ERR_ARG,
+                   "two-pass build incomplete: %lld vectors counted, %lld placed", (long long)ix->nadded, (long long)ix->nplaced);
+        hipError_t e2 = hipStreamSynchronize(st);
+        if (e2 == hipSuccess) e2 = hipGetLastError();
+        if (e2 != hipSuccess) { set_error("finalize (placement) failed: %s", hipGetErrorString(e2)); return PIPERAG_ERR_HIP; }
+        return finish_build(ix, ix->nadded);
+    }
     const int64_t n = ix->nadded;
     const int nlist = ix->p.nlist, M = ix->p.M, Mp = ix->Mp;
     // chunks of the staging area, one placement workgroup each
@@ -372,43 +497,18 @@ int piperag_ivf_finalize(piperag_index *ix, void *stream) {
     hipError_t e = hipMemsetAsync(H, 0, sizeof(uint32_t) * (size_t)G * nlist, st);
     if (e != hipSuccess) { set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return cleanup(PIPERAG_ERR_HIP); }
     if (n > 0) hipLaunchKernelGGL(hist_kernel, dim3(G), dim3(256), 0, st, ix->st_list, n, chunk, nlist, H);
-    hipLaunchKernelGGL(colscan_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, H, G, nlist, ix->list_len);
-    hipLaunchKernelGGL(blockscan_kernel, dim3(1), dim3(1024), 0, st, ix->list_len, nlist, ix->list_blk);
-    int32_t nblocks = 0;
-    e = hipMemcpyAsync(&nblocks, ix->list_blk + nlist, sizeof(int32_t), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) { set_error("finalize (list sizes) failed: %s", hipGetErrorString(e)); return cleanup(PIPERAG_ERR_HIP); }
-    ix->nblocks = nblocks;
-    if ((int64_t)nblocks * kBlockVecs >= 0xFFFFFFFFll) { set_error("too many slots for 32-bit positions"); return cleanup(PIPERAG_ERR_LIMIT); }
-    const size_t code_bytes = (size_t)std::max<int64_t>(nblocks, 1) * kBlockVecs * Mp;
-    const size_t nslots = (size_t)std::max<int64_t>(nblocks, 1) * kBlockVecs;
-    if (hipMalloc(reinterpret_cast<void **>(&ix->codes), code_bytes) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&ix->ids), nslots * sizeof(int64_t)) != hipSuccess) {
-        set_error("out of device memory for %zu bytes of codes", code_bytes);
-        return cleanup(PIPERAG_ERR_OOM);
+    hipLaunchKernelGGL(colscan_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, H, G, nlist, ix->list_len, (uint32_t *)nullptr);
+    {
+        const int rca = allocate_lists(ix, st);
+        if (rca != PIPERAG_OK) return cleanup(rca);
     }
-    e = hipMemsetAsync(ix->codes, 0, code_bytes, st);
-    if (e == hipSuccess) e = hipMemsetAsync(ix->ids, 0xFF, nslots * sizeof(int64_t), st);
-    if (e != hipSuccess) { set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return cleanup(PIPERAG_ERR_HIP); }
     if (n > 0)
         hipLaunchKernelGGL(place_kernel, dim3(G), dim3(kPlaceTile), 0, st, ix->st_list, ix->st_codes, ix->st_ids, n, chunk,
                            nlist, M, Mp, H, ix->list_blk, ix->codes, ix->ids);
     e = hipStreamSynchronize(st);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) { set_error("finalize (placement) failed: %s", hipGetErrorString(e)); return cleanup(PIPERAG_ERR_HIP); }
-    {
-        std::vector<int32_t> hl(nlist);
-        if (hipMemcpy(hl.data(), ix->list_len, sizeof(int32_t) * nlist, hipMemcpyDeviceToHost) != hipSuccess) {
-            set_error("finalize (list lengths) failed");
-            return cleanup(PIPERAG_ERR_HIP);
-        }
-        ix->max_list_len = 0;
-        for (int32_t v : hl) ix->max_list_len = std::max<int64_t>(ix->max_list_len, v);
-    }
-    free_staging(ix);
-    ix->ntotal = n;
-    ix->finalized = true;
-    return cleanup(PIPERAG_OK);
+    return cleanup(finish_build(ix, n));
 }
 
 int piperag_ivf_list_lengths(const piperag_index *ix, int64_t *out_host) {

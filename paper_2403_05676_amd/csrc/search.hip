@@ -369,26 +369,24 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count;
-    __shared__ float s_qn;
+    __shared__ float s_qpart[kSelThreads / kWave];
     const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
     float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
     const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
     for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
-    if (tid == 0) { s_count = 0; s_qn = 0.f; }
-    __syncthreads();
+    if (tid == 0) s_count = 0;
+    float qn = 0.f;
     if (nparts > 0) {                                        // D holds partial inner products: the query's norm first
         float part = 0.f;
         for (int t = tid; t < d; t += kSelThreads) { const float v = q[(size_t)qi * d + t]; part += v * v; }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-        // fixed order of additions: wave w adds in turn w
-        for (int w = 0; w < kSelThreads / kWave; ++w) {
-            if (tid == w * kWave) s_qn += part;
-            __syncthreads();
-        }
+        if ((tid & 63) == 0) s_qpart[tid >> 6] = part;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kSelThreads / kWave; ++w) qn += s_qpart[w];    // the same order in every thread
     }
-    const float qn = s_qn;
     auto dist_of = [&](int i) -> float {                      // distance to centre i from the parts, summed in order
         float dot = grow[i];
         for (int p = 1; p < nparts; ++p) dot += grow[(size_t)p * nq * nlist + i];

@@ -416,3 +416,42 @@ def test_largest_nprobe_and_k():
     run_search_parity(pkg, ix, oidx, q, 1024, 1024)
     run_search_parity(pkg, ix, oidx, q[:1], 1024, 100)
     run_search_parity(pkg, ix, oidx, q, 1000, 1)
+
+
+def test_two_pass_build_gives_the_same_index_as_the_one_pass_build():
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(50000, 64, 40, 16, seed=77, nq=6)
+    xd = dev(x)
+    ids = torch.arange(50000, dtype=torch.int64, device="cuda") * 3 + 7
+    one = pkg.Index.ivf_create(coarse, pq, 50000)
+    one.ivf_add(xd, ids)
+    one.ivf_finalize()
+    two = pkg.Index.ivf_create(coarse, pq, 50000)
+    tiles = [(0, 13000), (13000, 13001), (13001, 40000), (40000, 50000)]       # ragged tiles, different in the two passes
+    for a, b in tiles:
+        two.ivf_count(xd[a:b])
+    with pytest.raises(pkg.PiperagError):
+        two.ivf_add(xd[:10])                                 # the two kinds of build do not mix
+    with pytest.raises(pkg.PiperagError):
+        two.ivf_place(xd[:10])                               # not before reserve
+    two.ivf_reserve()
+    with pytest.raises(pkg.PiperagError):
+        two.ivf_finalize()                                   # nothing placed yet
+    for a, b in [(0, 20000), (20000, 20064), (20064, 50000)]:
+        two.ivf_place(xd[a:b], ids[a:b])
+    with pytest.raises(pkg.PiperagError):
+        two.ivf_place(xd[:1])                                # more than was counted
+    two.ivf_finalize()
+    assert np.array_equal(one.ivf_list_lengths(), two.ivf_list_lengths())
+    for l in range(40):
+        c1, i1 = one.ivf_get_list(l)
+        c2, i2 = two.ivf_get_list(l)
+        assert np.array_equal(c1, c2) and np.array_equal(i1, i2), f"list {l} differs"
+    d1, r1 = one.ivfpq_search(dev(q), 8, 10)
+    d2, r2 = two.ivfpq_search(dev(q), 8, 10)
+    assert torch.equal(d1, d2) and torch.equal(r1, r2)
+    # ids by position when none are given
+    three = pkg.Index.ivf_create(coarse, pq, 1000)
+    three.ivf_count(xd[:1000]); three.ivf_reserve(); three.ivf_place(xd[:600]); three.ivf_place(xd[600:1000]); three.ivf_finalize()
+    got = np.sort(np.concatenate([three.ivf_get_list(l)[1] for l in range(40)]))
+    assert np.array_equal(got, np.arange(1000))
