@@ -111,3 +111,8 @@ def test_cfg3_full_size():
 @pytest.mark.skipif("cfg4" not in LARGE, reason="set PIPERAG_LARGE=cfg4 (builds 1.07 G vectors, tens of minutes)")
 def test_cfg4_full_size():
     run_config("cfg4", 8192, [(1, 128), (16, 128), (256, 128)], max_check=8)
+
+
+@pytest.mark.skipif("paper" not in LARGE, reason="set PIPERAG_LARGE=paper (builds 3 G vectors in two passes, 230 GB of HBM)")
+def test_paper_shaped_index():
+    run_config("paper", 8192, [(1, 64), (64, 64)], max_check=2)

@@ -78,6 +78,9 @@ CONFIGS = {
     "cfg2": WorkloadConfig("cfg2", 2, 1024, 1.1, 0.25, 16_777_216, 768, 16_384, 64, 262_144, 8, 256, 100),
     "cfg3": WorkloadConfig("cfg3", 3, 4096, 1.1, 0.25, 268_435_456, 768, 65_536, 64, 1_048_576, 64, 64, 100),
     "cfg4": WorkloadConfig("cfg4", 4, 4096, 1.1, 0.25, 1_073_741_824, 768, 65_536, 64, 1_048_576, 256, 128, 100),
+    # the shape of the paper's own database (Appendix "Detailed Evaluation Setup": three billion 384-dimensional
+    # vectors, 16,384 lists, 64-byte codes, nprobe 64, the k = 2 neighbours RETRO retrieves per chunk)
+    "paper": WorkloadConfig("paper", 5, 4096, 1.1, 0.25, 3_000_000_000, 384, 16_384, 64, 1_048_576, 64, 64, 2),
 }
 
 
