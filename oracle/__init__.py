@@ -106,6 +106,7 @@ class Index:
     list_off: np.ndarray    # [nlist + 1] i64
     codes: np.ndarray       # [ntotal, M] u8
     ids: np.ndarray         # [ntotal] i64
+    residual: bool = False  # codes quantise x - centre of x's list instead of x
 
     @property
     def nlist(self): return self.coarse.shape[0]
@@ -198,6 +199,83 @@ def scan_with_probes(index: Index, q_row: np.ndarray, probes_row: np.ndarray):
     fn.restype = C.c_int64
     got = fn(_p(q_row, C.c_float), C.c_int(q_row.shape[0]), _p(index.pq, C.c_float), C.c_int(M), C.c_int(ksub),
              _p(index.list_off, C.c_int64), _p(index.codes, C.c_uint8), _p(index.ids, C.c_int64),
+             _p(probes_row, C.c_int32), C.c_int(probes_row.shape[0]), _p(od, C.c_float), _p(oi, C.c_int64))
+    assert got == ncand
+    return od, oi
+
+
+# --------------------------------------------------------------------------
+# Residual variant: codes quantise x - centre of x's list; `Index.residual` marks such an index.
+def residuals(x: np.ndarray, coarse: np.ndarray, lists: np.ndarray) -> np.ndarray:
+    x = _f32(x); coarse = _f32(coarse)
+    lists = np.ascontiguousarray(lists, dtype=np.int32)
+    out = np.empty_like(x)
+    _load().oracle_residuals(_p(x, C.c_float), C.c_int64(x.shape[0]), C.c_int(x.shape[1]), _p(coarse, C.c_float),
+                             _p(lists, C.c_int32), _p(out, C.c_float))
+    return out
+
+
+def encode_residual(x: np.ndarray, coarse: np.ndarray, pq: np.ndarray):
+    x = _f32(x); coarse = _f32(coarse); pq = _f32(pq)
+    n, d = x.shape
+    M, ksub, dsub = pq.shape
+    lists = np.empty(n, dtype=np.int32)
+    codes = np.empty((n, M), dtype=np.uint8)
+    _load().oracle_encode_residual(_p(x, C.c_float), C.c_int64(n), C.c_int(d), _p(coarse, C.c_float),
+                                   C.c_int64(coarse.shape[0]), _p(pq, C.c_float), C.c_int(M), C.c_int(ksub),
+                                   _p(lists, C.c_int32), _p(codes, C.c_uint8))
+    return lists, codes
+
+
+def train_residual(sample: np.ndarray, nlist: int, M: int, coarse_init: np.ndarray, pq_init: list, iters: int = 10,
+                   ksub: int = 256):
+    """Coarse centres = k-means(sample, nlist); codebook m = k-means(m-th slice of the sample's residuals, ksub)."""
+    sample = _f32(sample)
+    d = sample.shape[1]
+    dsub = d // M
+    coarse = kmeans(sample, nlist, coarse_init, iters)
+    r = residuals(sample, coarse, assign(sample, coarse))
+    pq = np.empty((M, ksub, dsub), dtype=np.float32)
+    for m in range(M):
+        pq[m] = kmeans(r[:, m * dsub:(m + 1) * dsub], ksub, pq_init[m], iters)
+    return coarse, pq
+
+
+def make_index_residual(x: np.ndarray, coarse: np.ndarray, pq: np.ndarray, ids: np.ndarray | None = None) -> Index:
+    lists, codes = encode_residual(x, coarse, pq)
+    ids = np.arange(x.shape[0], dtype=np.int64) if ids is None else np.asarray(ids, dtype=np.int64)
+    off, codes, ids = build_lists(lists, codes, ids, coarse.shape[0])
+    return Index(_f32(coarse), _f32(pq), off, codes, ids, residual=True)
+
+
+def search_residual_with_probes(index: Index, q: np.ndarray, probes: np.ndarray, k: int):
+    q = _f32(q)
+    nq, d = q.shape
+    probes = np.ascontiguousarray(probes, dtype=np.int32)
+    M, ksub, dsub = index.pq.shape
+    od = np.empty((nq, k), dtype=np.float32)
+    oi = np.empty((nq, k), dtype=np.int64)
+    _load().oracle_search_residual_with_probes(
+        _p(q, C.c_float), C.c_int64(nq), C.c_int(d), _p(index.coarse, C.c_float), _p(index.pq, C.c_float), C.c_int(M),
+        C.c_int(ksub), _p(index.list_off, C.c_int64), _p(index.codes, C.c_uint8), _p(index.ids, C.c_int64),
+        _p(probes, C.c_int32), C.c_int(probes.shape[1]), C.c_int(k), _p(od, C.c_float), _p(oi, C.c_int64))
+    lens = np.diff(index.list_off)
+    scanned = np.array([int(lens[p[p >= 0]].sum()) for p in probes], dtype=np.int64)
+    return od, oi, scanned
+
+
+def scan_residual_with_probes(index: Index, q_row: np.ndarray, probes_row: np.ndarray):
+    q_row = _f32(q_row).reshape(-1)
+    probes_row = np.ascontiguousarray(probes_row, dtype=np.int32).reshape(-1)
+    M, ksub, dsub = index.pq.shape
+    lens = np.diff(index.list_off)
+    ncand = int(lens[probes_row[probes_row >= 0]].sum())
+    od = np.empty(ncand, dtype=np.float32)
+    oi = np.empty(ncand, dtype=np.int64)
+    fn = _load().oracle_scan_residual_with_probes
+    fn.restype = C.c_int64
+    got = fn(_p(q_row, C.c_float), C.c_int(q_row.shape[0]), _p(index.coarse, C.c_float), _p(index.pq, C.c_float), C.c_int(M),
+             C.c_int(ksub), _p(index.list_off, C.c_int64), _p(index.codes, C.c_uint8), _p(index.ids, C.c_int64),
              _p(probes_row, C.c_int32), C.c_int(probes_row.shape[0]), _p(od, C.c_float), _p(oi, C.c_int64))
     assert got == ncand
     return od, oi

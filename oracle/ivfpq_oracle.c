@@ -353,3 +353,103 @@ void oracle_decode(const uint8_t *codes, int64_t n, const float *pq, int M, int 
             memcpy(x_out + (i * M + m) * dsub, pq + ((int64_t)m * ksub + codes[i * M + m]) * dsub,
                    sizeof(float) * (size_t)dsub);
 }
+
+/* ================================================================== */
+/* Residual variant (the inverted-file ADC of the product-quantisation
+ * method the paper cites for its index, Section 3.2 S3): a database vector
+ * x in list l is stored as the code of its residual x - c_l to the list
+ * centre, and a query is compared with it through the residual of the
+ * query to the same centre:
+ *     dist(q, x) = sum_m | (q - c_l)_m - pq[m][code_x[m]] |^2 .
+ * Everything else (lists, probes, k-selection, ties) is as above.  The
+ * residual itself is the single fp32 subtraction x - c_l (it is an input of
+ * the quantiser, which is defined on fp32 vectors); sums are fp64. */
+
+/* residual_out[i] = x_i - coarse[lists[i]], one fp32 subtraction per coordinate. */
+void oracle_residuals(const float *x, int64_t n, int d, const float *coarse, const int32_t *lists, float *residual_out) {
+    for (int64_t i = 0; i < n; ++i) {
+        const float *c = coarse + (int64_t)lists[i] * d;
+        for (int t = 0; t < d; ++t) residual_out[i * d + t] = x[i * d + t] - c[t];
+    }
+}
+
+/* list_out[i] = nearest coarse centre; codes_out[i] = code of the residual to it. */
+void oracle_encode_residual(const float *x, int64_t n, int d, const float *coarse, int64_t nlist, const float *pq,
+                            int M, int ksub, int32_t *list_out, uint8_t *codes_out) {
+    oracle_assign(x, n, d, d, coarse, nlist, list_out, NULL);
+    float *r = (float *)malloc(sizeof(float) * (size_t)n * (size_t)d);
+    oracle_residuals(x, n, d, coarse, list_out, r);
+    oracle_encode(r, n, d, coarse, nlist, pq, M, ksub, NULL, codes_out);
+    free(r);
+}
+
+/* Scan of one query's probed lists, residual variant; same outputs as scan_probed_lists. */
+static cand_t *scan_probed_lists_residual(const float *q_row, int d, const float *coarse, const float *pq, int M, int ksub,
+                                          const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
+                                          const int32_t *probes, int nprobe, int64_t *cstart) {
+    const int dsub = d / M;
+    cstart[0] = 0;
+    for (int p = 0; p < nprobe; ++p) {
+        const int32_t l = probes[p];
+        cstart[p + 1] = cstart[p] + (l < 0 ? 0 : list_off[l + 1] - list_off[l]);
+    }
+    const int64_t ncand = cstart[nprobe];
+    cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(ncand > 0 ? ncand : 1));
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < nprobe; ++p) {
+        const int32_t l = probes[p];
+        if (l < 0) continue;
+        /* the query's residual to this list's centre (fp32, like the stored vectors' residuals), its table */
+        float *rq = (float *)malloc(sizeof(float) * (size_t)d);
+        double *lut = (double *)malloc(sizeof(double) * (size_t)M * (size_t)ksub);
+        for (int t = 0; t < d; ++t) rq[t] = q_row[t] - coarse[(int64_t)l * d + t];
+        build_lut(rq, pq, M, ksub, dsub, lut);
+        const int64_t a = list_off[l], len = list_off[l + 1] - a;
+        for (int64_t i = 0; i < len; ++i) {
+            const uint8_t *code = codes + (a + i) * M;
+            double acc = 0.0;
+            for (int m = 0; m < M; ++m) acc += lut[m * ksub + code[m]];
+            cand[cstart[p] + i].d = (float)acc;
+            cand[cstart[p] + i].id = ids[a + i];
+        }
+        free(lut); free(rq);
+    }
+    return cand;
+}
+
+void oracle_search_residual_with_probes(const float *q, int64_t nq, int d, const float *coarse, const float *pq, int M,
+                                        int ksub, const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
+                                        const int32_t *probes, int nprobe, int k, float *out_dist, int64_t *out_ids) {
+    for (int64_t qi = 0; qi < nq; ++qi) {
+        int64_t *cstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nprobe + 1));
+        cand_t *cand = scan_probed_lists_residual(q + qi * d, d, coarse, pq, M, ksub, list_off, codes, ids,
+                                                  probes + qi * nprobe, nprobe, cstart);
+        const int64_t ncand = cstart[nprobe];
+        cand_t *best = (cand_t *)malloc(sizeof(cand_t) * (size_t)k);
+        int nb = 0;
+        for (int64_t c = 0; c < ncand; ++c) {
+            if (nb == k && !cand_less(&cand[c], &best[k - 1])) continue;
+            int pos = nb < k ? nb : k - 1;
+            while (pos > 0 && cand_less(&cand[c], &best[pos - 1])) { best[pos] = best[pos - 1]; --pos; }
+            best[pos] = cand[c];
+            if (nb < k) ++nb;
+        }
+        for (int r = 0; r < k; ++r) {
+            out_dist[qi * k + r] = r < nb ? best[r].d : INFINITY;
+            out_ids[qi * k + r] = r < nb ? best[r].id : -1;
+        }
+        free(best); free(cand); free(cstart);
+    }
+}
+
+/* The same scan for one query without the selection (every candidate, in probe order). */
+int64_t oracle_scan_residual_with_probes(const float *q_row, int d, const float *coarse, const float *pq, int M, int ksub,
+                                         const int64_t *list_off, const uint8_t *codes, const int64_t *ids,
+                                         const int32_t *probes, int nprobe, float *out_dist, int64_t *out_ids) {
+    int64_t *cstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nprobe + 1));
+    cand_t *cand = scan_probed_lists_residual(q_row, d, coarse, pq, M, ksub, list_off, codes, ids, probes, nprobe, cstart);
+    const int64_t ncand = cstart[nprobe];
+    for (int64_t c = 0; c < ncand; ++c) { out_dist[c] = cand[c].d; out_ids[c] = cand[c].id; }
+    free(cand); free(cstart);
+    return ncand;
+}

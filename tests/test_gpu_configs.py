@@ -86,7 +86,8 @@ def run_config(name, slice_rows, batches, max_check=64):
         ex_k, rel = 0, 0.0
         for a in range(0, nchk, 4):
             t1 = time.time()
-            e, r = parity.check_topk(odh[a:a + 4], oih[a:a + 4], hidx, qh[a:a + 4], probes[a:a + 4], cfg.k)
+            b = min(a + 4, nchk)
+            e, r = parity.check_topk(odh[a:b], oih[a:b], hidx, qh[a:b], probes[a:b], cfg.k)
             ex_k, rel = ex_k + e, max(rel, r)
             print(f"[{name}] top-k of queries {a}..{min(a + 4, nchk) - 1} checked, {time.time() - t1:.1f}s", flush=True)
         print(f"[{name}] nq={nq} nprobe={nprobe}: top-k of {nchk} queries match the oracle ({ex_k} with tie differences), "
