@@ -20,8 +20,11 @@
  *     Calls that take a stream enqueue their work on it; unless stated otherwise
  *     they return without waiting, and results are valid once the caller has
  *     synchronised that stream.  The search calls allocate nothing.
- *   - Distance is squared L2 (no square root).  The PQ code quantises the raw
- *     vector (not its residual to the list centre), 8 bits per sub-quantiser.
+ *   - Distance is squared L2 (no square root).  8 bits per sub-quantiser.  The PQ
+ *     code quantises the raw vector, or, for an index created with residual = 1,
+ *     the vector's residual to the centre of its list (the inverted-file ADC of
+ *     the product-quantisation method the paper cites, Section 3.2, S3); the
+ *     distance to a vector x of list l is then sum_m |(q - c_l)_m - pq[m][code_x[m]]|^2.
  *   - An index must not be searched from two streams at once: the search
  *     workspace belongs to the index.
  */
@@ -52,13 +55,14 @@ typedef struct piperag_params {
     int32_t max_nq;     /* largest query batch a search call may pass (>= 1) */
     int32_t max_nprobe; /* largest nprobe (1 .. min(nlist, 1024)) */
     int32_t max_k;      /* largest k (1 .. 1024) */
+    int32_t residual;   /* 0: the code quantises the vector itself; 1: its residual to the centre of its list */
 } piperag_params;
 
 /* ---- index life cycle ------------------------------------------------------------------- */
 
 /* Reads an index file (layout below) into HBM and makes it searchable.  Only max_nq, max_nprobe and
  * max_k of `limits` are used.  File, little-endian: 64-byte header = "PRAGIVF1", u32 version (1), u32 d,
- * u32 nlist, u32 M, u32 nbits (8), u32 0, u64 ntotal, zero padding; then centres f32 [nlist*d]; codebooks
+ * u32 nlist, u32 M, u32 nbits (8), u32 flags (bit 0: residual codes), u64 ntotal, zero padding; then centres f32 [nlist*d]; codebooks
  * f32 [M*256*(d/M)]; list lengths i64 [nlist]; codes u8 [ntotal*M], list after list; ids i64 [ntotal] in
  * the same order.  On success *out owns everything; free with piperag_ivf_free. */
 int piperag_ivf_load(const char *path, const piperag_params *limits, piperag_index **out);

@@ -23,7 +23,8 @@ class PiperagError(RuntimeError):
 
 class Params(C.Structure):
     _fields_ = [("d", C.c_int32), ("nlist", C.c_int32), ("M", C.c_int32), ("nbits", C.c_int32),
-                ("ntotal", C.c_int64), ("max_nq", C.c_int32), ("max_nprobe", C.c_int32), ("max_k", C.c_int32)]
+                ("ntotal", C.c_int64), ("max_nq", C.c_int32), ("max_nprobe", C.c_int32), ("max_k", C.c_int32),
+                ("residual", C.c_int32)]
 
 
 def lib_path() -> str:
@@ -141,21 +142,21 @@ class Index:
     # ---- life cycle --------------------------------------------------------------------------
     @staticmethod
     def ivf_create(centroids: np.ndarray, pq_codebook: np.ndarray, capacity: int, max_nq: int = 256,
-                   max_nprobe: int = 256, max_k: int = 128) -> "Index":
+                   max_nprobe: int = 256, max_k: int = 128, residual: bool = False) -> "Index":
         cent = np.ascontiguousarray(centroids, dtype=np.float32)
         pq = np.ascontiguousarray(pq_codebook, dtype=np.float32)
         nlist, d = cent.shape
         M, ksub, dsub = pq.shape
         if ksub != 256 or M * dsub != d:
             raise ValueError("codebook must be [M, 256, d/M]")
-        p = Params(d, nlist, M, 8, capacity, max_nq, min(max_nprobe, nlist), max_k)
+        p = Params(d, nlist, M, 8, capacity, max_nq, min(max_nprobe, nlist), max_k, int(residual))
         h = C.c_void_p()
         _check(load_library().piperag_ivf_create(C.byref(p), cent.ctypes.data, pq.ctypes.data, C.byref(h)))
         return Index(h.value, d, nlist, M)
 
     @staticmethod
     def ivf_load(path: str, max_nq: int = 256, max_nprobe: int = 256, max_k: int = 128) -> "Index":
-        p = Params(0, 0, 0, 8, 0, max_nq, max_nprobe, max_k)
+        p = Params(0, 0, 0, 8, 0, max_nq, max_nprobe, max_k, 0)
         h = C.c_void_p()
         _check(load_library().piperag_ivf_load(path.encode(), C.byref(p), C.byref(h)))
         # read the shape back from the file header

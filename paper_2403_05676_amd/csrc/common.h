@@ -104,6 +104,9 @@ struct piperag_index {
     int64_t nplaced;       // vectors placed in pass 2
     bool reserved;         // lists are sized, codes / ids allocated (two-pass)
     bool finalized;
+    // residual indexes only: tx[slot] = 2 <c_l, decode(code)> of the vector in the slot (l its list), so that the
+    // distance to it is the raw-table sum + tx[slot] + (|c_l|^2 - 2 <q, c_l>); computed at finalize
+    float *tx;
     // scan layout (after finalize)
     int64_t ntotal, nblocks;
     uint8_t *codes;     // [nblocks*64*Mp]
@@ -125,6 +128,7 @@ struct piperag_index {
     uint32_t *ws_done;    // [kMaxScanWGs+2*max_nq] counters of that merge
     uint32_t *ws_tb;      // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
     uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
+    float *ws_pcst;       // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
     int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
     float *ws_qn;         // [max_nq] squared norms of the queries

@@ -122,6 +122,7 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ x
 // out as one contiguous run.
 __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict__ x, int64_t n, int d,
                                                         const float *__restrict__ pq, int M, int dsub,
+                                                        const int32_t *__restrict__ lists, const float *__restrict__ cent,
                                                         uint8_t *__restrict__ out_codes) {
     extern __shared__ __align__(16) unsigned char smem[];
     float *cs = reinterpret_cast<float *>(smem);              // [256][dsub]
@@ -135,7 +136,9 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
         for (int i = tid; i < kKsub * dsub; i += 256) cs[i] = pq[(size_t)m * kKsub * dsub + i];
         for (int e = tid; e < 256 * dsub; e += 256) {
             const int r = e / dsub, t = e - r * dsub;
-            xs[t * 256 + r] = r < rows ? x[(row0 + r) * d + m * dsub + t] : 0.f;
+            float v = r < rows ? x[(row0 + r) * d + m * dsub + t] : 0.f;
+            if (lists && r < rows) v -= cent[(size_t)lists[row0 + r] * d + m * dsub + t];   // residual to the list's centre
+            xs[t * 256 + r] = v;
         }
         __syncthreads();
         float best = __builtin_inff();
@@ -165,6 +168,7 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
 // collected in LDS and written out as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
 __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__restrict__ x, int64_t n, int d,
                                                              const float *__restrict__ pqE, int M, int dsub, int T,
+                                                             const int32_t *__restrict__ lists, const float *__restrict__ cent,
                                                              uint8_t *__restrict__ out_codes) {
     extern __shared__ __align__(16) unsigned char smem[];
     float *sA = reinterpret_cast<float *>(smem);                  // [T][256]
@@ -175,6 +179,8 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
     const int64_t myrow = row0 + wave * 32 + l32;
     const float *xr = x + myrow * d;
     const bool live = myrow < n;
+    // residual indexes quantise x - c_l (one fp32 subtraction), l the vector's list
+    const float *cr = lists && live ? cent + (size_t)lists[myrow] * d : nullptr;
     for (int m = 0; m < M; ++m) {
         __syncthreads();                                          // the previous sub-quantiser's centres are no longer read
         const float4 *src = reinterpret_cast<const float4 *>(pqE + (size_t)m * T * kKsub);
@@ -188,7 +194,11 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
         for (int p = 0; p < T / 2; ++p) {
             const int t = 2 * p + half;                           // lanes 0-31: depth 2p, lanes 32-63: depth 2p + 1
             float bv = t == dsub ? 1.f : 0.f;                     // the row of norms; padding rows are zero on both sides
-            if (t < dsub) bv = live ? -2.f * xr[m * dsub + t] : 0.f;
+            if (t < dsub) {
+                float v = live ? xr[m * dsub + t] : 0.f;
+                if (cr) v -= cr[m * dsub + t];
+                bv = -2.f * v;
+            }
             const float *a = sA + t * kKsub + l32;
 #pragma unroll
             for (int bi = 0; bi < 8; ++bi) acc[bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi * 32], bv, acc[bi], 0, 0, 0);
@@ -499,13 +509,23 @@ size_t split_bf16_elems(int64_t n, int d) { return Bf16x3Tile::part_elems(n, d);
 
 namespace {
 
-int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out_lists, uint8_t *out_codes, hipStream_t st) {
+// lists: buffer of n list numbers; assign = true: they are computed here (lists may be NULL for a raw index
+// when only codes are wanted), assign = false: they are given (the codes of a residual index need them).
+int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *lists, bool assign, uint8_t *out_codes,
+                hipStream_t st) {
     const piperag_params &p = ix->p;
     PR_REQUIRE(ix->dsub <= 32, PIPERAG_ERR_ARG, "d/M = %d: the encoder supports at most 32 coordinates per sub-quantiser", ix->dsub);
-    if (out_lists) {
-        const int rc = launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, p.nlist, out_lists, nullptr, st);
-        if (rc != PIPERAG_OK) return rc;
+    int32_t *tmp_lists = nullptr;
+    if (p.residual && out_codes && !lists) {                 // codes of residuals need the lists even if the caller does not
+        PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&tmp_lists), sizeof(int32_t) * (size_t)n, st));
+        lists = tmp_lists;
+        assign = true;
     }
+    if (assign && lists) {
+        const int rc = launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, p.nlist, lists, nullptr, st);
+        if (rc != PIPERAG_OK) { if (tmp_lists) (void)hipFreeAsync(tmp_lists, st); return rc; }
+    }
+    const int32_t *res_lists = p.residual ? lists : nullptr;
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
     for (int64_t a = 0; a < n; a += kSlice) {
         const int64_t cnt = n - a < kSlice ? n - a : kSlice;
@@ -520,7 +540,8 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out
                     configured = lds;
                 }
                 hipLaunchKernelGGL(pq_encode_mfma_kernel, dim3((unsigned)((cnt + 127) / 128)), dim3(256), lds, st, x + a * p.d, cnt,
-                                   p.d, ix->pqE, p.M, ix->dsub, T, out_codes + (size_t)a * p.M);
+                                   p.d, ix->pqE, p.M, ix->dsub, T, res_lists ? res_lists + a : nullptr, ix->centroids,
+                                   out_codes + (size_t)a * p.M);
             } else {
                 const size_t lds = sizeof(float) * 2 * kKsub * ix->dsub + (size_t)256 * p.M;
                 static size_t configured = 0;
@@ -530,10 +551,12 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *out
                     configured = lds;
                 }
                 hipLaunchKernelGGL(pq_encode_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), lds, st, x + a * p.d, cnt, p.d,
-                                   ix->pq, p.M, ix->dsub, out_codes + (size_t)a * p.M);
+                                   ix->pq, p.M, ix->dsub, res_lists ? res_lists + a : nullptr, ix->centroids,
+                                   out_codes + (size_t)a * p.M);
             }
         }
     }
+    if (tmp_lists) PR_CHECK_HIP(hipFreeAsync(tmp_lists, st));
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
 }
@@ -549,7 +572,7 @@ int piperag_ivf_encode(const piperag_index *index, const float *x_dev, int64_t n
     if (n == 0) return PIPERAG_OK;
     PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
     PR_CHECK_HIP(hipSetDevice(index->device));
-    return encode_impl(index, x_dev, n, out_lists_dev, out_codes_dev, (hipStream_t)stream);
+    return encode_impl(index, x_dev, n, out_lists_dev, true, out_codes_dev, (hipStream_t)stream);
 }
 
 int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_t K, int32_t iters,
@@ -623,7 +646,7 @@ int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const i
     PR_REQUIRE(x_dev != nullptr, PIPERAG_ERR_ARG, "x_dev is NULL");
     hipStream_t st = (hipStream_t)stream;
     PR_CHECK_HIP(hipSetDevice(index->device));
-    rc = encode_impl(index, x_dev, n, index->st_list + index->nadded, index->st_codes + (size_t)index->nadded * index->p.M, st);
+    rc = encode_impl(index, x_dev, n, index->st_list + index->nadded, true, index->st_codes + (size_t)index->nadded * index->p.M, st);
     if (rc != PIPERAG_OK) return rc;
     rc = append_ids(index, n, ids_dev, st);
     if (rc != PIPERAG_OK) return rc;
@@ -673,7 +696,7 @@ int piperag_ivf_place(piperag_index *index, const float *x_dev, int64_t n, const
         if (e != hipSuccess) { (void)hipFreeAsync(codes, st); set_error("scratch allocation failed: %s", hipGetErrorString(e)); return PIPERAG_ERR_OOM; }
         fill_iota(ids, n, index->nplaced, st);
     }
-    int rc = encode_impl(index, x_dev, n, nullptr, codes, st);
+    int rc = encode_impl(index, x_dev, n, index->st_list + index->nplaced, false, codes, st);
     if (rc == PIPERAG_OK) rc = place_tile(index, index->st_list + index->nplaced, codes, ids_dev ? ids_dev : ids, n, st);
     (void)hipFreeAsync(codes, st);
     if (ids) (void)hipFreeAsync(ids, st);

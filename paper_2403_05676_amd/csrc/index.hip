@@ -155,6 +155,35 @@ __global__ void gather_list_kernel(const uint8_t *__restrict__ codes, const int6
     }
 }
 
+// Residual indexes: tx[slot] = 2 <c_l, decode(code in slot)> for every slot of the scan layout (0 for padding).
+// One wavefront per block of 64 slots; the block's list is found by bisection of list_blk.
+__global__ __launch_bounds__(64) void residual_term_kernel(const uint8_t *__restrict__ codes, const int32_t *__restrict__ list_blk,
+                                                           const int32_t *__restrict__ list_len, int nlist,
+                                                           const float *__restrict__ cent, const float *__restrict__ pq, int d,
+                                                           int M, int Mp, int dsub, float *__restrict__ tx) {
+    const uint32_t block = blockIdx.x, lane = threadIdx.x;
+    int lo = 0, hi = nlist;                                 // last list whose first block is <= block and that is not empty there
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((uint32_t)list_blk[mid] <= block) lo = mid; else hi = mid;
+    }
+    const int l = lo;
+    const uint32_t slot = block * kBlockVecs + lane;
+    const int in_list = (int)(slot - (uint32_t)list_blk[l] * kBlockVecs);
+    float acc = 0.f;
+    if (in_list < list_len[l]) {
+        const float *c = cent + (size_t)l * d;
+        for (int t = 0; t < Mp; ++t) {
+            const int m = (int)((lane + t) % Mp);
+            if (m >= M) continue;
+            const int code = codes[(size_t)block * kBlockVecs * Mp + (size_t)(t >> 4) * 1024 + lane * 16 + (t & 15)];
+            const float *pc = pq + ((size_t)m * kKsub + code) * dsub;
+            for (int u = 0; u < dsub; ++u) acc += c[m * dsub + u] * pc[u];
+        }
+    }
+    tx[slot] = 2.f * acc;
+}
+
 __global__ void fill_u32_kernel(uint32_t *__restrict__ dst, size_t n, uint32_t v) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = v;
@@ -187,6 +216,7 @@ int dev_alloc(T **p, size_t count) {
 int check_params(const piperag_params *p) {
     PR_REQUIRE(p != nullptr, PIPERAG_ERR_ARG, "params is NULL");
     PR_REQUIRE(p->nbits == 8, PIPERAG_ERR_ARG, "nbits = %d: only 8-bit sub-quantisers are supported", p->nbits);
+    PR_REQUIRE(p->residual == 0 || p->residual == 1, PIPERAG_ERR_ARG, "residual = %d must be 0 or 1", p->residual);
     PR_REQUIRE(p->M >= 1 && p->M <= 128, PIPERAG_ERR_ARG, "M = %d out of range 1..128", p->M);
     PR_REQUIRE(p->d >= 1 && p->d % p->M == 0, PIPERAG_ERR_ARG, "d = %d must be a positive multiple of M = %d", p->d, p->M);
     PR_REQUIRE(p->d <= 8192, PIPERAG_ERR_ARG, "d = %d exceeds 8192", p->d);
@@ -233,7 +263,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_pfx, (size_t)p.max_nq * (p.max_nprobe + 1))) ||
         (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) || (rc = dev_alloc(&ix->ws_thr, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_desc, (size_t)kMaxScanWGs + p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_tb, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
+        (rc = dev_alloc(&ix->ws_tb, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_pcst, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
         (rc = dev_alloc(&ix->ws_part, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
@@ -383,7 +413,7 @@ void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
     void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
-                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
+                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pcst, ix->tx, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);
@@ -446,6 +476,16 @@ static int allocate_lists(piperag_index *ix, hipStream_t st) {
 }
 
 static int finish_build(piperag_index *ix, int64_t n) {
+    if (ix->p.residual) {
+        const size_t nslots = (size_t)std::max<int64_t>(ix->nblocks, 1) * kBlockVecs;
+        PR_TRY(dev_alloc(&ix->tx, nslots));
+        if (ix->nblocks > 0)
+            hipLaunchKernelGGL(residual_term_kernel, dim3((unsigned)ix->nblocks), dim3(64), 0, nullptr, ix->codes, ix->list_blk,
+                               ix->list_len, ix->p.nlist, ix->centroids, ix->pq, ix->p.d, ix->p.M, ix->Mp, ix->dsub, ix->tx);
+        else
+            PR_CHECK_HIP(hipMemset(ix->tx, 0, nslots * sizeof(float)));
+        PR_CHECK_HIP(hipStreamSynchronize(nullptr));
+    }
     std::vector<int32_t> hl(ix->p.nlist);
     if (hipMemcpy(hl.data(), ix->list_len, sizeof(int32_t) * ix->p.nlist, hipMemcpyDeviceToHost) != hipSuccess) {
         set_error("finalize (list lengths) failed");
@@ -554,7 +594,7 @@ int piperag_ivf_get_list(const piperag_index *ix, int32_t list, int64_t *len_out
 namespace {
 struct FileHeader {
     char magic[8];
-    uint32_t version, d, nlist, M, nbits, zero;
+    uint32_t version, d, nlist, M, nbits, zero;      // zero: flags (bit 0: residual codes)
     uint64_t ntotal;
     char pad[64 - 8 - 24 - 8];
 };
@@ -572,7 +612,7 @@ int piperag_ivf_save(const piperag_index *ix, const char *path) {
     FileHeader h;
     memset(&h, 0, sizeof(h));
     memcpy(h.magic, "PRAGIVF1", 8);
-    h.version = 1; h.d = p.d; h.nlist = p.nlist; h.M = p.M; h.nbits = 8; h.ntotal = (uint64_t)ix->ntotal;
+    h.version = 1; h.d = p.d; h.nlist = p.nlist; h.M = p.M; h.nbits = 8; h.zero = p.residual ? 1u : 0u; h.ntotal = (uint64_t)ix->ntotal;
     int rc = PIPERAG_OK;
     uint8_t *dc = nullptr;
     int64_t *di = nullptr;
@@ -646,7 +686,8 @@ int piperag_ivf_load(const char *path, const piperag_params *limits, piperag_ind
     piperag_params p = *limits;
     p.d = (int32_t)h.d; p.nlist = (int32_t)h.nlist; p.M = (int32_t)h.M; p.nbits = (int32_t)h.nbits;
     p.ntotal = (int64_t)h.ntotal;
-    if (h.d > 8192 || h.nlist > (1u << 20) || h.M > 128 || h.M == 0 || h.d % h.M != 0 || h.ntotal > 0xFFF00000ull) {
+    p.residual = (int32_t)(h.zero & 1u);
+    if (h.zero > 1u || h.d > 8192 || h.nlist > (1u << 20) || h.M > 128 || h.M == 0 || h.d % h.M != 0 || h.ntotal > 0xFFF00000ull) {
         set_error("%s: header fields out of range", path);
         return done(PIPERAG_ERR_FILE);
     }

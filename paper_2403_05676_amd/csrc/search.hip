@@ -221,10 +221,12 @@ struct PlanOut {
     int32_t *pfx, *pblk, *plen;
     int64_t *scanned;
     uint32_t *thr;
+    float *pcst;                 // residual indexes: |c_l|^2 - 2 <q, c_l> per probe (NULL otherwise)
 };
 __device__ __forceinline__ PlanOut plan_of_query(const PlanOut &all, int qi, int probe_stride) {
     return PlanOut{all.pfx + (size_t)qi * (probe_stride + 1), all.pblk + (size_t)qi * probe_stride,
-                   all.plen + (size_t)qi * probe_stride, all.scanned + qi, all.thr + qi};
+                   all.plen + (size_t)qi * probe_stride, all.scanned + qi, all.thr + qi,
+                   all.pcst ? all.pcst + (size_t)qi * probe_stride : nullptr};
 }
 template <class ProbeFn>
 __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restrict__ list_blk,
@@ -256,6 +258,22 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
         vecs += len;
     }
     if (lane == 0) { pfx[nprobe] = running; *o.scanned = vecs; *o.thr = 0xFFFFFFFFu; }
+}
+
+// Residual indexes, probe lists given by the caller: pcst[q][i] = |c_l|^2 - 2 <q, c_l> for l = the i-th probe
+// (0 for a skipped entry).  One wavefront per (probe, query).
+__global__ __launch_bounds__(64) void probe_const_kernel(const float *__restrict__ q, const float *__restrict__ cent,
+                                                         const float *__restrict__ cn, int d,
+                                                         const int32_t *__restrict__ probe, int probe_stride,
+                                                         float *__restrict__ pcst) {
+    const int qi = blockIdx.y, i = blockIdx.x, lane = threadIdx.x;
+    const int32_t l = probe[(size_t)qi * probe_stride + i];
+    float acc = 0.f;
+    if (l >= 0)
+        for (int t = lane; t < d; t += 64) acc += q[(size_t)qi * d + t] * cent[(size_t)l * d + t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) pcst[(size_t)qi * probe_stride + i] = l >= 0 ? cn[l] - 2.f * acc : 0.f;
 }
 
 // Shares the scan workgroups out over the queries (one workgroup): query q gets
@@ -377,7 +395,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
     if (tid == 0) s_count = 0;
     float qn = 0.f;
-    if (nparts > 0) {                                        // D holds partial inner products: the query's norm first
+    if (nparts > 0 || plan.pcst) {                           // D holds partial inner products, or a residual index: the query's norm first
         float part = 0.f;
         for (int t = tid; t < d; t += kSelThreads) { const float v = q[(size_t)qi * d + t]; part += v * v; }
 #pragma unroll
@@ -417,6 +435,8 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     }
     auto probe_at = [&](int i) { return (int32_t)(s_keys[i] & 0xFFFFFFFFu); };
     const PlanOut mine = plan_of_query(plan, qi, probe_stride);
+    if (mine.pcst)                                           // |q - c|^2 - |q|^2 = |c|^2 - 2 <q, c>
+        for (int i = tid; i < nprobe; i += kSelThreads) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
     plan_query(probe_at, nprobe, list_blk, list_len, mine);
     // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
     // workgroup publishes its query's number of blocks with a device-scope store, waits for it to complete and
@@ -464,6 +484,8 @@ struct ScanArgs {
     const int32_t *pfx;        // [nq][probe_stride+1] block prefix sums of the probed lists
     const int32_t *pblk;       // [nq][probe_stride] first block of each probed list
     const int32_t *plen;       // [nq][probe_stride] length of each probed list
+    const float *pcst;         // residual indexes: [nq][probe_stride] constant of each probed list
+    const float *tx;           // residual indexes: [slots] term of each stored vector
     uint64_t *part;            // [workgroups][KW] partial results
     uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
     const int4 *desc;          // [workgroups] (query, number among the query's workgroups, their count, counters in use); query -1: spare
@@ -501,6 +523,7 @@ struct ScanLds {
     unsigned *hist;              // [256]
     unsigned *misc;              // [8]: 0 count, 1 min distance bits, 2 max distance bits, 3 waves done
     int32_t *pfx, *blk, *len;    // probe tables [nprobe+1], [nprobe], [nprobe]
+    float *cst;                  // [nprobe] residual indexes: constant of each probed list
 };
 __device__ __forceinline__ ScanLds carve_lds(unsigned char *smem, int Mp, int cap, int nprobe) {
     ScanLds s;
@@ -512,11 +535,12 @@ __device__ __forceinline__ ScanLds carve_lds(unsigned char *smem, int Mp, int ca
     s.pfx = reinterpret_cast<int32_t *>(s.misc + 8);
     s.blk = s.pfx + (nprobe + 1);
     s.len = s.blk + nprobe;
+    s.cst = reinterpret_cast<float *>(s.len + nprobe);
     return s;
 }
 size_t scan_lds_bytes(int Mp, int cap, int nprobe) {
     return (size_t)1024 * Mp + sizeof(uint64_t) * ((size_t)cap + 8) + sizeof(unsigned) * (256 + 8) +
-           sizeof(int32_t) * (3 * (size_t)nprobe + 1);
+           sizeof(int32_t) * (4 * (size_t)nprobe + 1);
 }
 
 // Distance of this lane's vector of one block, any Mp: table index = byte * Mp + (lane + t) mod Mp.
@@ -713,6 +737,7 @@ template <int NTHREADS>
 struct ProbeTableRegs {
     static constexpr int kIter = kMaxNprobe / NTHREADS;
     int32_t pf[kIter], pb[kIter], pl[kIter], pf_last;
+    float pc[kIter];
 };
 template <int NTHREADS>
 __device__ __forceinline__ void load_probe_tables(const ScanArgs &a, int qi, ProbeTableRegs<NTHREADS> &r) {
@@ -724,6 +749,7 @@ __device__ __forceinline__ void load_probe_tables(const ScanArgs &a, int qi, Pro
         const int i = tid + j * NTHREADS;
         const bool ok = i < a.nprobe;
         r.pf[j] = ok ? pf[i] : 0; r.pb[j] = ok ? pb[i] : 0; r.pl[j] = ok ? pl[i] : 0;
+        r.pc[j] = ok && a.pcst ? a.pcst[(size_t)qi * a.probe_stride + i] : 0.f;
     }
     r.pf_last = pf[a.nprobe];
 }
@@ -733,7 +759,7 @@ __device__ __forceinline__ void store_probe_tables(const ScanArgs &a, const Scan
 #pragma unroll
     for (int j = 0; j < ProbeTableRegs<NTHREADS>::kIter; ++j) {
         const int i = tid + j * NTHREADS;
-        if (i < a.nprobe) { s.pfx[i] = r.pf[j]; s.blk[i] = r.pb[j]; s.len[i] = r.pl[j]; }
+        if (i < a.nprobe) { s.pfx[i] = r.pf[j]; s.blk[i] = r.pb[j]; s.len[i] = r.pl[j]; s.cst[i] = r.pc[j]; }
     }
     if (tid == 0) { s.pfx[a.nprobe] = r.pf_last; s.misc[0] = 0; s.misc[3] = 0; }
 }
@@ -813,7 +839,7 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
 // Priming of the bound: one workgroup (512 threads) per query stages the query's table in LDS, scans the first
 // kPrimeBlocks blocks of the query's probed lists (the closest lists come first) and sets thr[q] to a distance
 // that at least k of those vectors reach.
-template <int C>
+template <int C, bool RES>
 __global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
     constexpr int MP = 16 * C;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -839,12 +865,14 @@ __global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
     uint4 w[kPerWave][C];
     uint32_t gblock[kPerWave];
     int nvalid[kPerWave];
+    float extra[kPerWave];            // residual indexes: the vector's own term + the list's constant
     int pi = 0;
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
         const int b = wave + i * kLutWaves;
         nvalid[i] = 0;
         gblock[i] = 0;
+        extra[i] = 0.f;
         if (b < nb) {
             while (b >= s.pfx[pi + 1]) ++pi;                  // b < TB = pfx[nprobe]
             const int bl = b - s.pfx[pi];
@@ -853,6 +881,7 @@ __global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
             const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock[i] * kBlockVecs * MP);
 #pragma unroll
             for (int c = 0; c < C; ++c) w[i][c] = blk[c * kWave + lane];
+            if (RES) extra[i] = a.tx[(size_t)gblock[i] * kBlockVecs + lane] + s.cst[pi];
         }
     }
     lut_copy_end<kLutThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
@@ -863,6 +892,7 @@ __global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
             float dist;
             if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w[i]), off4);
             else dist = block_dist_generic<C>(w[i], s.lut, lane_m);
+            if (RES) dist = fmaxf(0.f, dist + extra[i]);
             append_candidates(lane < nvalid[i], __float_as_uint(dist), gblock[i] * kBlockVecs + lane, s.cand, &s.misc[0], cap,
                               lane);
         }
@@ -997,7 +1027,7 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // (thr[q] in global memory, polled with every block load).  At the end the workgroup's (at most KW)
 // surviving keys go to the partial-result buffer, unsorted; stage 4 selects among them.
 // ------------------------------------------------------------------------------------------------
-template <int C, int NSETS>
+template <int C, int NSETS, bool RES>
 __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     constexpr int MP = 16 * C;
     extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
@@ -1052,12 +1082,15 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // Every call issues the same number of loads, whether or not block b exists (beyond the end a wave re-reads
     // a few bytes of block 0, which always exists): the compiler can then count the loads in flight exactly
     // and lets NSETS - 1 later requests stay in flight while one block is worked on.
-    struct Meta { uint32_t gblock; int nvalid; uint32_t tg; bool valid; };
+    // nvalid = 0 marks a request beyond the end.  tx, cl: residual indexes only (the vector's own term, loaded with
+    // the block, and the constant of its list).
+    struct Meta { uint32_t gblock; int nvalid; float tx, cl; };
     const uint4 *idle = reinterpret_cast<const uint4 *>(a.codes);
     auto issue = [&](uint4 (&w)[C], Meta &m, int b) {
-        m.valid = b < TB;
+        m.nvalid = 0;
         const uint4 *src = idle;
-        if (m.valid) {
+        size_t tx_at = 0;
+        if (b < TB) {
             for (;;) {              // lanes look at the next 64 prefix sums at once; b < TB = pfx[nprobe] bounds pi
                 const int32_t e = s.pfx[min(pi + 1 + lane, a.nprobe)];
                 const int adv = __popcll(__ballot(b >= e));
@@ -1068,10 +1101,14 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
             m.gblock = (uint32_t)(s.blk[pi] + bl);
             m.nvalid = s.len[pi] - bl * kBlockVecs;           // >= 1; lanes >= nvalid hold padding
             src = reinterpret_cast<const uint4 *>(a.codes + (size_t)m.gblock * kBlockVecs * MP) + lane;
+            if (RES) {              // the list's constant is the same in all lanes: kept in a scalar register
+                m.cl = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s.cst[pi])));
+                tx_at = (size_t)m.gblock * kBlockVecs;
+            }
         }
 #pragma unroll
         for (int c = 0; c < C; ++c) w[c] = src[c * kWave];
-        m.tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (RES) m.tx = a.tx[tx_at + lane];                  // one more load per request, block or not
     };
     auto process = [&](const uint4 (&w)[C], const Meta &m) {
         float dist;
@@ -1085,8 +1122,10 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 #endif
         if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
         else dist = block_dist_generic<C>(w, s.lut, lane_m);
+        // residual index: the table sum is |q - p|^2 for the decoded residual p; adding 2 <c, p> (stored per vector)
+        // and |c|^2 - 2 <q, c> (per probed list) makes it |q - c - p|^2; clamped, since key order needs dist >= 0
+        if (RES) dist = fmaxf(0.f, dist + m.tx + m.cl);
         const uint32_t dbits = __float_as_uint(dist);
-        thr = min(thr, ((uint64_t)m.tg << 32) | 0xFFFFFFFFull);
         const uint32_t slot = m.gblock * kBlockVecs + lane;
         bool pass = (lane < m.nvalid) && ((((uint64_t)dbits << 32) | slot) <= thr);
 #ifdef PIPERAG_TRACE
@@ -1099,6 +1138,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     Meta meta[NSETS];
     int cb = wave_of_query * kChunkBlocks;                   // first block of the chunk being requested
     uint32_t pending = ask_chunk();
+    // the query's bound is polled once per chunk, with the chunk request, and used one turn later
+    uint32_t tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i], cb + i);
     lut_copy_end<kScanThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
@@ -1136,7 +1177,7 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     for (;;) {
         bool any = false;           // this wave still holds a requested block
 #pragma unroll
-        for (int i = 0; i < NSETS; ++i) any |= meta[i].valid;
+        for (int i = 0; i < NSETS; ++i) any |= meta[i].nvalid > 0;
         if (!any) break;            // chunks only move forward: nothing valid in flight means nothing is left
 #pragma unroll
         for (int j = 0; j < kChunkBlocks; ++j) {
@@ -1145,8 +1186,10 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
                 const uint32_t v = min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / (kChunkBlocks * kCtrPerQuery) - 1u);
                 cb = (int)(v * nctr + my_ctr) * kChunkBlocks;
                 pending = ask_chunk();
+                thr = min(thr, ((uint64_t)tg << 32) | 0xFFFFFFFFull);
+                tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (meta[i].valid) {
+            if (meta[i].nvalid > 0) {
                 // the count is looked at before every block; a wave appends at most 64 keys per block
                 while ((int)lds_peek(&s.misc[0]) > trigger) episode();
                 process(w[i], meta[i]);
@@ -1329,31 +1372,41 @@ void launch_lut_build(const piperag_index *ix, const float *q, int nq, hipStream
     }
 }
 
-template <int C>
-int launch_prime(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
+template <int C, bool RES>
+int launch_prime_r(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
     const size_t lds = scan_lds_bytes(ix->Mp, kPrimeBlocks * kBlockVecs, a.nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "priming kernel needs %zu bytes of LDS", lds);
     static size_t configured = 0;
     if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&prime_kernel<C>),
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&prime_kernel<C, RES>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    hipLaunchKernelGGL((prime_kernel<C>), dim3(nq), dim3(kLutThreads), lds, st, a);
+    hipLaunchKernelGGL((prime_kernel<C, RES>), dim3(nq), dim3(kLutThreads), lds, st, a);
     return PIPERAG_OK;
 }
-
 template <int C>
-int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
-    constexpr int NSETS = C <= 4 ? 4 : (C <= 6 ? 2 : 1);   // code blocks in flight per wave: as many as fit without register spills
+int launch_prime(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
+    return ix->p.residual ? launch_prime_r<C, true>(ix, nq, a, st) : launch_prime_r<C, false>(ix, nq, a, st);
+}
+
+template <int C, bool RES>
+int launch_scan_r(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
+    // code blocks in flight per wave: as many as fit without register spills (the residual variant holds one more
+    // value per lane and block)
+    constexpr int NSETS = C <= (RES ? 3 : 4) ? 4 : (C <= 6 ? 2 : 1);
     static size_t configured = 0;
     if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS>),
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS, RES>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS>), dim3(G), dim3(kScanThreads), lds, st, a);
+    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS, RES>), dim3(G), dim3(kScanThreads), lds, st, a);
     return PIPERAG_OK;
+}
+template <int C>
+int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
+    return a.tx ? launch_scan_r<C, true>(a, G, lds, st) : launch_scan_r<C, false>(a, G, lds, st);
 }
 
 #define PR_DISPATCH_C(expr_prefix, ...)                                         \
@@ -1369,7 +1422,9 @@ int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
         default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");           \
     }
 
-PlanOut plan_bufs(const piperag_index *ix) { return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr}; }
+PlanOut plan_bufs(const piperag_index *ix) {
+    return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr, ix->p.residual ? ix->ws_pcst : nullptr};
+}
 
 ShareOut share_bufs(const piperag_index *ix) { return ShareOut{ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_done}; }
 
@@ -1477,11 +1532,14 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
                            ix->list_blk, ix->list_len, plan_bufs(ix));
         hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ix));
+        if (ix->p.residual)
+            hipLaunchKernelGGL(probe_const_kernel, dim3(nprobe, nq), dim3(64), 0, st, q, ix->centroids, ix->cnorm, ix->p.d,
+                               ix->ws_probe, pstride, ix->ws_pcst);
     }
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
-    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_part, ix->ws_thr, ix->ws_desc,
-               ix->ws_ctr, nprobe, pstride, k, KW};
+    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->p.residual ? ix->ws_pcst : nullptr,
+               ix->p.residual ? ix->tx : nullptr, ix->ws_part, ix->ws_thr, ix->ws_desc, ix->ws_ctr, nprobe, pstride, k, KW};
 #ifdef PIPERAG_TRACE
     static unsigned long long *trace_buf = nullptr;
     if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));

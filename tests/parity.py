@@ -64,11 +64,13 @@ def check_topk(gpu_dist, gpu_ids, index: oracle.Index, q, probes, k):
     for qi in range(nq):
         pr = probes[qi:qi + 1]
         ncand = int(lens[pr[pr >= 0]].sum())
-        od, oi, scanned = oracle.search_with_probes(index, q[qi:qi + 1], pr, k)
+        search_fn = oracle.search_residual_with_probes if index.residual else oracle.search_with_probes
+        scan_fn = oracle.scan_residual_with_probes if index.residual else oracle.scan_with_probes
+        od, oi, scanned = search_fn(index, q[qi:qi + 1], pr, k)
         od, oi = od[0], oi[0]
         tau = od[min(k, ncand) - 1] if ncand > 0 else np.inf
         # every candidate the oracle places within tolerance of its k-th distance (any number of them may tie)
-        ad, ai = oracle.scan_with_probes(index, q[qi], pr[0])
+        ad, ai = scan_fn(index, q[qi], pr[0])
         near = ad <= tau * (1 + RTOL) + ATOL
         near_d, near_i = ad[near], ai[near]
         nvalid = min(k, ncand)
@@ -93,19 +95,25 @@ def check_topk(gpu_dist, gpu_ids, index: oracle.Index, q, probes, k):
     return excused, max_rel
 
 
-def check_encoding(gpu_lists, gpu_codes, x, coarse, pq):
+def check_encoding(gpu_lists, gpu_codes, x, coarse, pq, residual=False):
     """List numbers and code bytes equal the oracle's, except where the oracle's own two distances are
-    within tolerance.  Returns (list differences excused, code-byte differences excused)."""
+    within tolerance.  Returns (list differences excused, code-byte differences excused).  residual: the codes
+    quantise x minus the centre of its list; rows whose list differs (an excused tie) are then compared with the
+    oracle's codes for the list the library chose."""
     o_lists, o_codes = oracle.encode(x, coarse, pq)
     M, ksub, dsub = pq.shape
     bad_l = np.nonzero(gpu_lists != o_lists)[0]
     for i in bad_l:
         d = oracle.coarse_search(x[i:i + 1], coarse[[o_lists[i], gpu_lists[i]]], 2)[1][0]
         assert close(d[0], d[1]), f"row {i}: list {gpu_lists[i]} vs oracle {o_lists[i]}, distances {d}"
+    xq = x
+    if residual:
+        xq = oracle.residuals(x, coarse, gpu_lists)
+        o_codes = oracle.encode(xq, coarse, pq)[1]
     bad_c = np.argwhere(gpu_codes != o_codes)
     if len(bad_c):
         for i, m in bad_c:
-            table = oracle.lut(x[i:i + 1], pq)[0, m]
+            table = oracle.lut(xq[i:i + 1], pq)[0, m]
             a, b = table[o_codes[i, m]], table[gpu_codes[i, m]]
             assert close(a, b), f"row {i} sub-quantiser {m}: code {gpu_codes[i, m]} vs oracle {o_codes[i, m]} ({b} vs {a})"
     return len(bad_l), len(bad_c)

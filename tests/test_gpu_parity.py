@@ -37,7 +37,7 @@ def make_problem(N, d, nlist, M, seed, ncomp=16, sigma=0.3, iters=4, nq=16, zipf
 
 def gpu_index_from_oracle(pkg, oidx: oracle.Index, **limits):
     """Library index holding exactly the oracle's lists (so that search parity does not depend on encoding ties)."""
-    ix = pkg.Index.ivf_create(oidx.coarse, oidx.pq, oidx.ntotal, **limits)
+    ix = pkg.Index.ivf_create(oidx.coarse, oidx.pq, oidx.ntotal, residual=oidx.residual, **limits)
     lists = np.repeat(np.arange(oidx.nlist, dtype=np.int32), np.diff(oidx.list_off))
     ix.ivf_add_encoded(dev(lists), dev(oidx.codes), dev(oidx.ids))
     ix.ivf_finalize()
@@ -455,3 +455,63 @@ def test_two_pass_build_gives_the_same_index_as_the_one_pass_build():
     three.ivf_count(xd[:1000]); three.ivf_reserve(); three.ivf_place(xd[:600]); three.ivf_place(xd[600:1000]); three.ivf_finalize()
     got = np.sort(np.concatenate([three.ivf_get_list(l)[1] for l in range(40)]))
     assert np.array_equal(got, np.arange(1000))
+
+
+# ---- residual variant -----------------------------------------------------------------------------
+def make_residual_problem(N, d, nlist, M, seed, nq=9, sigma=0.3, ncomp=16, iters=4):
+    cfg = gen.WorkloadConfig(f"r{seed}", seed, ncomp, 0.0, sigma, N, d, nlist, M, min(N, 20000), nq, 1, 1)
+    x = gen.database(cfg)
+    q = gen.queries(cfg, nq)
+    S = min(N, 20000)
+    ci = gen.draw_distinct_rows(S, nlist, seed)
+    pi = [gen.draw_distinct_rows(S, 256, seed + 1 + m) for m in range(M)]
+    coarse, pq = oracle.train_residual(x[:S], nlist, M, ci, pi, iters=iters)
+    return cfg, x, q, coarse, pq
+
+
+@pytest.mark.parametrize("N,d,nlist,M,nprobe,k", [
+    (20000, 64, 33, 16, 6, 50),       # Mp = 16
+    (30000, 256, 64, 64, 12, 100),    # the M = 64 scan kernel (two blocks in flight)
+    (9000, 96, 25, 48, 25, 20),       # Mp = 48, nprobe = nlist
+    (4000, 200, 16, 100, 4, 10),      # M = 100 (padded to 112)
+    (3000, 18, 12, 6, 3, 300),        # d/M = 3: the VALU encoder; k beyond most candidate sets
+])
+def test_residual_index_search_and_encode(N, d, nlist, M, nprobe, k):
+    pkg = P()
+    cfg, x, q, coarse, pq = make_residual_problem(N, d, nlist, M, seed=N + d + M)
+    oidx = oracle.make_index_residual(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=64, max_k=512)
+    run_search_parity(pkg, ix, oidx, q, nprobe, k)
+    run_search_parity(pkg, ix, oidx, q[:1], nprobe, k)
+    # given probes (the constants of the lists are then computed by their own kernel), with a repeat and a gap
+    probes = np.tile(np.arange(nprobe, dtype=np.int32), (q.shape[0], 1))
+    probes[:, -1] = probes[:, 0]
+    od, oi = ix.ivfpq_search_probes(dev(q), dev(probes), k)
+    torch.cuda.synchronize()
+    probes[:, -1] = -1
+    parity.check_topk(od.cpu().numpy(), oi.cpu().numpy(), oidx, q, probes, k)
+    # encoder, built both ways
+    ix2 = pkg.Index.ivf_create(coarse, pq, N, residual=True)
+    gl, gc = ix2.ivf_encode(dev(x))
+    torch.cuda.synchronize()
+    parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), x, coarse, pq, residual=True)
+    ix2.ivf_add(dev(x)); ix2.ivf_finalize()
+    ix3 = pkg.Index.ivf_create(coarse, pq, N, residual=True)
+    ix3.ivf_count(dev(x)); ix3.ivf_reserve(); ix3.ivf_place(dev(x)); ix3.ivf_finalize()
+    d2, i2 = ix2.ivfpq_search(dev(q), nprobe, min(k, 100))
+    d3, i3 = ix3.ivfpq_search(dev(q), nprobe, min(k, 100))
+    assert torch.equal(d2, d3) and torch.equal(i2, i3)
+
+
+def test_residual_index_file_roundtrip(tmp_path):
+    pkg = P()
+    cfg, x, q, coarse, pq = make_residual_problem(6000, 32, 10, 8, seed=44)
+    oidx = oracle.make_index_residual(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=16, max_k=64)
+    path = str(tmp_path / "res.idx")
+    ix.ivf_save(path)
+    ix2 = pkg.Index.ivf_load(path, max_nq=16, max_nprobe=16, max_k=64)
+    d1, i1 = ix.ivfpq_search(dev(q), 5, 20)
+    d2, i2 = ix2.ivfpq_search(dev(q), 5, 20)
+    assert torch.equal(d1, d2) and torch.equal(i1, i2)
+    run_search_parity(pkg, ix2, oidx, q, 5, 20)
