@@ -28,8 +28,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None, max_k=None):
-    """Generates the database on the device, trains and encodes on the GPU.  Returns (index, generator, info)."""
+def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None, max_k=None, residual=False):
+    """Generates the database on the device, trains and encodes on the GPU.  Returns (index, generator, info).
+    residual: the codebooks are trained on, and the codes quantise, the vectors' residuals to their list centres."""
     from workload import gen, gen_gpu
     g = gen_gpu.DeviceGenerator(cfg)
     t0 = time.time()
@@ -39,6 +40,12 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
     torch.cuda.synchronize()
     log(f"[build] coarse centres trained, {time.time() - t0:.0f}s")
     pq = torch.empty((cfg.M, 256, cfg.dsub), dtype=torch.float32, device="cuda")
+    if residual:                                        # the sample's residuals: lists from the library, subtraction by torch
+        tmp = pkg.Index.ivf_create(coarse.cpu().numpy(), np.zeros((cfg.M, 256, cfg.dsub), dtype=np.float32), 1)
+        for a in range(0, cfg.train_sample, tile_rows):
+            lists, _ = tmp.ivf_encode(sample[a:a + tile_rows])
+            sample[a:a + tile_rows] -= coarse[lists.long()]
+        tmp.ivf_free()
     for m in range(cfg.M):
         init_m = gen.draw_distinct_rows(cfg.train_sample, 256, cfg.seed + 1 + m)
         pq[m] = pkg.kmeans(sample[:, m * cfg.dsub:(m + 1) * cfg.dsub], 256, init_m, cfg.kmeans_iters)
@@ -46,7 +53,7 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
     t_train = time.time() - t0
     del sample
     ix = pkg.Index.ivf_create(coarse.cpu().numpy(), pq.cpu().numpy(), cfg.N, max_nq=max_nq or cfg.nq,
-                              max_nprobe=max_nprobe or cfg.nprobe, max_k=max_k or cfg.k)
+                              max_nprobe=max_nprobe or cfg.nprobe, max_k=max_k or cfg.k, residual=residual)
     t0 = time.time()
     buf = torch.empty((min(tile_rows, cfg.N), cfg.d), dtype=torch.float32, device="cuda")
     # a staging area of more than 32 GiB is not worth its memory: the database is generated twice instead
@@ -79,7 +86,7 @@ def build_index(pkg, cfg, torch, tile_rows=262144, max_nq=None, max_nprobe=None,
                    "coarse": coarse, "pq": pq}
 
 
-def host_copy(ix, coarse, pq, lists=None):
+def host_copy(ix, coarse, pq, lists=None, residual=False):
     """The GPU-built index in the oracle's canonical form, read back list by list through the C ABI.  With
     `lists` given, only those lists are fetched and every other list is left empty (enough for an oracle
     search that probes only them)."""
@@ -97,7 +104,7 @@ def host_copy(ix, coarse, pq, lists=None):
         c, i = ix.ivf_get_list(int(l))
         codes[off[l]:off[l + 1]] = c
         ids[off[l]:off[l + 1]] = i
-    return oracle.Index(coarse, pq, off, codes, ids)
+    return oracle.Index(coarse, pq, off, codes, ids, residual=residual)
 
 
 def shorten(kernel_name):
@@ -186,7 +193,7 @@ def nprobe_sweep(args, pkg, cfg, torch):
     fit latency = a + b * nprobe of Section 3.3's performance model) and recall@k of 1,000 queries against the
     exact neighbours, for nprobe = 1, 2, 4, ... up to the configuration's nprobe."""
     nprobes = [p for p in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if p <= cfg.nprobe]
-    ix, g, info = build_index(pkg, cfg, torch, max_nq=64, max_nprobe=max(nprobes))
+    ix, g, info = build_index(pkg, cfg, torch, max_nq=64, max_nprobe=max(nprobes), residual=args.residual)
     nrec = 1000
     q = g.queries(nrec)
     p50_1, fit_1 = ix.latency_profile(q[:1].contiguous(), nprobes, cfg.k, reps=50)
@@ -284,6 +291,8 @@ def main():
     ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB copy kernel three times (reference for the HBM traffic counters)")
+    ap.add_argument("--residual", action="store_true",
+                    help="build a residual index (codes of the vectors' residuals to their list centres) instead of the raw-vector one")
     ap.add_argument("--nprobe-sweep", action="store_true",
                     help="instead of the bench line: latency and recall against nprobe on the chosen workload (meant for cfg2)")
     ap.add_argument("--overlap", action="store_true",
@@ -312,7 +321,7 @@ def main():
         overlap_demo(args, pkg, cfg, torch)
         return
     log(f"[bench] building {cfg.name}: N={cfg.N} d={cfg.d} nlist={cfg.nlist} M={cfg.M}")
-    ix, g, info = build_index(pkg, cfg, torch, max_nq=max(cfg.nq, 1))
+    ix, g, info = build_index(pkg, cfg, torch, max_nq=max(cfg.nq, 1), residual=args.residual)
     log(f"[bench] train {info['train_s']:.1f}s encode {info['encode_s']:.1f}s finalize {info['finalize_s']:.1f}s")
     q = g.queries(cfg.nq)
     out_d = torch.empty((cfg.nq, cfg.k), dtype=torch.float32, device="cuda")
@@ -363,7 +372,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} nlist={cfg.nlist} M={cfg.M}x8bit nq={cfg.nq} "
                                f"nprobe={cfg.nprobe} k={cfg.k} (Zipf Gaussian mixture, seed {cfg.seed})",
-                   "nq": cfg.nq, "nprobe": cfg.nprobe, "k": cfg.k},
+                   "nq": cfg.nq, "nprobe": cfg.nprobe, "k": cfg.k, "codes": "residual" if args.residual else "raw vector"},
         "p50_1query_ms": p50_1q,
         "scanned_code_GBps": achieved,
         "scanned_vectors_per_batch": scanned_vecs,
@@ -393,7 +402,7 @@ def main():
         gl0, _ = ix.ivf_coarse(q, cfg.nprobe)
         torch.cuda.synchronize()
         needed = np.union1d(gl0.cpu().numpy().ravel(), oracle.coarse_search(qh, coarse_h, cfg.nprobe)[0].ravel())
-        hidx = host_copy(ix, coarse_h, pq_h, lists=needed)   # only the lists either side probes
+        hidx = host_copy(ix, coarse_h, pq_h, lists=needed, residual=args.residual)   # only the lists either side probes
         oracle.search(hidx, qh, cfg.nprobe, cfg.k)            # warm-up
         times = []
         t_budget = time.time()

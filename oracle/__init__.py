@@ -284,6 +284,10 @@ def scan_residual_with_probes(index: Index, q_row: np.ndarray, probes_row: np.nd
 def search(index: Index, q: np.ndarray, nprobe: int, k: int):
     """(dist [nq,k] f32, ids [nq,k] i64, probes [nq,nprobe] i32, scanned [nq] i64)."""
     q = _f32(q)
+    if index.residual:
+        probes, _ = coarse_search(q, index.coarse, nprobe)
+        od, oi, scanned = search_residual_with_probes(index, q, probes, k)
+        return od, oi, probes, scanned
     nq, d = q.shape
     M, ksub, dsub = index.pq.shape
     od = np.empty((nq, k), dtype=np.float32)
