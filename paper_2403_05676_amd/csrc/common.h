@@ -123,7 +123,7 @@ struct piperag_index {
     int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
-    int4 *ws_desc;        // [kMaxScanWGs+max_nq] (query, first block, end block, 0) of each scan workgroup
+    int4 *ws_desc;        // [kMaxScanWGs+max_nq] (query, number among the query's workgroups, their count, chunk counters in use) of each scan workgroup
     uint64_t *ws_part2;   // same shape as ws_part: keys kept by groups of scan workgroups (merge inside the scan kernel)
     uint32_t *ws_done;    // [kMaxScanWGs+2*max_nq] counters of that merge
     uint32_t *ws_tb;      // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
@@ -131,7 +131,6 @@ struct piperag_index {
     float *ws_pcst;       // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
     int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
-    float *ws_qn;         // [max_nq] squared norms of the queries
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
     uint64_t *ws_part;    // [(kMaxScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results

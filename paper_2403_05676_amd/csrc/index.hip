@@ -269,7 +269,6 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->ws_done, (size_t)kMaxScanWGs + 2 * (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->pqE, (size_t)p.M * pqe_rows(ix->dsub) * kKsub)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
-        (rc = dev_alloc(&ix->ws_qn, (size_t)p.max_nq)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
         return fail(rc);
@@ -412,7 +411,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
-    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->ws_qn, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
+    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
                     ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pcst, ix->tx, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)

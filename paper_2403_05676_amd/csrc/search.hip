@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <class ForEach>
 __device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigned *s_hist, unsigned long long *s_state) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
-    // round 0: minimum, maximum and number of valid keys
+    // first pass: minimum, maximum and number of valid keys
     uint64_t lo = kSentinel, hi = 0;
     unsigned cnt = 0;
     for_each_key([&](uint64_t key) {
@@ -280,9 +280,9 @@ __global__ __launch_bounds__(64) void probe_const_kernel(const float *__restrict
 // S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
 // per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
 // the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
-// use, at most max(target, nq)); desc[w] = (query, first block, end block, 0) of workgroup w, blocks counted
-// along the query's concatenated probed lists; desc of spare workgroups has query -1.  A workgroup gets at
-// least kMinBlocksPerWG blocks (unless its query has fewer), so that small searches are not spread over
+// use, at most max(target, nq)); desc[w] = (query, number of the workgroup among the query's, their count,
+// chunk counters in use) of workgroup w; desc of spare workgroups has query -1.  A workgroup gets at least
+// kMinBlocksPerWG blocks on average (unless its query has fewer), so that small searches are not spread over
 // needlessly many workgroups.
 struct ShareOut {
     int32_t *seg0;
@@ -1015,8 +1015,8 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // ------------------------------------------------------------------------------------------------
 // Stage 3: scan of the probed lists with candidate selection.
 // The probed lists of a query, concatenated in probe order, form a sequence of 64-vector blocks; the plan
-// gives workgroup w a query and an equal share [b_begin, b_end) of that sequence, and the 4 waves of the
-// workgroup take its blocks round-robin.  A lane owns one vector of the block: it reads its Mp code bytes
+// gives every workgroup a query, and the waves of a query's workgroups take that sequence in chunks of
+// kChunkBlocks blocks from shared counters.  A lane owns one vector of the block: it reads its Mp code bytes
 // with Mp/16 16-byte loads (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.
 // Because of the rotated code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp,
 // so with the table stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
@@ -1024,8 +1024,9 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // to one buffer per workgroup.  The waves run independently; a wave that sees the buffer nearly full (or has
 // no blocks left) waits at a barrier, and once all four are there the buffer is pruned to about k keys and
 // the bound tightened.  The bound is the smallest such value any workgroup of the query has reached
-// (thr[q] in global memory, polled with every block load).  At the end the workgroup's (at most KW)
-// surviving keys go to the partial-result buffer, unsorted; stage 4 selects among them.
+// (thr[q] in global memory, polled once per chunk).  At the end the workgroup's (at most KW) surviving keys
+// go to the partial-result buffer, unsorted; stage 4 (the merge kernel, or the last workgroups to finish
+// inside this kernel) selects among them.  RES: residual index (see the comment in process below).
 // ------------------------------------------------------------------------------------------------
 template <int C, int NSETS, bool RES>
 __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
