@@ -65,6 +65,7 @@ def load_library() -> C.CDLL:
         "piperag_search_stats": [vp, C.POINTER(i64), C.POINTER(i64)],
         "piperag_set_stage_timing": [vp, C.c_int],
         "piperag_set_graph_replay": [vp, C.c_int],
+        "piperag_set_scan_streaming": [vp, C.c_int],
         "piperag_stage_times": [vp, vp],
     }
     for name, args in sig.items():
@@ -281,6 +282,9 @@ class Index:
 
     def set_graph_replay(self, enable: bool) -> None:
         _check(load_library().piperag_set_graph_replay(self._h, int(enable)))
+
+    def set_scan_streaming(self, mode: int) -> None:
+        _check(load_library().piperag_set_scan_streaming(self._h, int(mode)))
 
     def stage_times(self) -> np.ndarray:
         out = np.empty(NSTAGES, dtype=np.float32)

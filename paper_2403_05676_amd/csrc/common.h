@@ -28,6 +28,7 @@ constexpr int kCtrStride = 32;         // chunk counters sit 128 bytes apart
 constexpr int kCtrPerQuery = 16;       // at most this many chunk counters share out one query's blocks
 constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
 constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
+constexpr size_t kStreamingCodeBytes = (size_t)4 << 30;   // indexes with at least this many code bytes are scanned with non-temporal loads
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
@@ -147,6 +148,7 @@ struct piperag_index {
     hipEvent_t ev_fork, ev_join;
     hipStream_t cap_stream;       // capture stream for the search graphs
     bool replay;                  // graph replay of repeated calls is enabled
+    int streaming;                // scan loads: < 0 by index size, 0 ordinary, > 0 non-temporal
     SearchGraph graphs[8];
     uint64_t graph_clock;
     bool ev_valid;

@@ -246,6 +246,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     PR_REQUIRE(ix != nullptr, PIPERAG_ERR_OOM, "host allocation failed");
     memset(ix, 0, sizeof(*ix));
     ix->p = *params;
+    ix->streaming = -1;
     ix->p.max_nprobe = std::min(ix->p.max_nprobe, ix->p.nlist);
     ix->dsub = params->d / params->M;
     ix->Mp = round_up(params->M, 16);

@@ -137,11 +137,12 @@ __device__ void block_bitonic_sort_u64(uint64_t *keys, int n) {
 
 // ------------------------------------------------------------------------------------------------
 // Stage 0: coarse distances  D[q][j] = || query_q - centre_j ||^2  (direct form, fp32)
-// One wavefront per centre at a time; the lanes split the coordinates (VEC floats per lane per 64*VEC
-// chunk, so a centre row is read with contiguous wavefront loads); QT queries of the batch are kept in
-// LDS and share each centre read.  grid = (centre groups, ceil(nq / QT)).
+// One wavefront per JT centres at a time; the lanes split the coordinates (VEC floats per lane per 64*VEC
+// chunk, so a centre row is read with contiguous wavefront loads, JT of them in flight per lane); QT queries
+// of the batch are kept in LDS and share each centre read.  HBM-bound on the centre matrix.
+// grid = (centre groups, ceil(nq / QT)).
 // ------------------------------------------------------------------------------------------------
-template <int QT, int VEC>
+template <int QT, int VEC, int JT>
 __global__ __launch_bounds__(256) void coarse_rowwise_kernel(const float *__restrict__ q, const float *__restrict__ cent,
                                                              float *__restrict__ D, int nq, int nlist, int d) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -155,33 +156,47 @@ __global__ __launch_bounds__(256) void coarse_rowwise_kernel(const float *__rest
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nwaves = gridDim.x * (blockDim.x >> 6);
-    for (int j = blockIdx.x * (blockDim.x >> 6) + wave; j < nlist; j += nwaves) {
-        const float *row = cent + (size_t)j * d;
-        float acc[QT];
+    for (int j = blockIdx.x * (blockDim.x >> 6) + wave; j < nlist; j += JT * nwaves) {
+        const float *row[JT];
 #pragma unroll
-        for (int qi = 0; qi < QT; ++qi) acc[qi] = 0.f;
+        for (int jt = 0; jt < JT; ++jt)            // centres past the end re-read centre j (loads stay unconditional)
+            row[jt] = cent + (size_t)(j + jt * nwaves < nlist ? j + jt * nwaves : j) * d;
+        float acc[JT][QT];
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int qi = 0; qi < QT; ++qi) acc[jt][qi] = 0.f;
         for (int t0 = lane * VEC; t0 < d; t0 += 64 * VEC) {
-            float c[VEC];
-            if (VEC == 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(row + t0);
-                c[0] = v.x; c[1 % VEC] = v.y; c[2 % VEC] = v.z; c[3 % VEC] = v.w;
-            } else {
-                c[0] = row[t0];
+            float c[JT][VEC];
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) {
+                if (VEC == 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(row[jt] + t0);
+                    c[jt][0] = v.x; c[jt][1 % VEC] = v.y; c[jt][2 % VEC] = v.z; c[jt][3 % VEC] = v.w;
+                } else {
+                    c[jt][0] = row[jt][t0];
+                }
             }
 #pragma unroll
             for (int qi = 0; qi < QT; ++qi) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    const float diff = s_q[qi * d + t0 + v] - c[v];
-                    acc[qi] += diff * diff;
+                    const float qv = s_q[qi * d + t0 + v];
+#pragma unroll
+                    for (int jt = 0; jt < JT; ++jt) {
+                        const float diff = qv - c[jt][v];
+                        acc[jt][qi] += diff * diff;
+                    }
                 }
             }
         }
 #pragma unroll
-        for (int qi = 0; qi < QT; ++qi) {
-            const float s = wave_sum(acc[qi]);
-            if (lane == 0 && qi < nqt) D[(size_t)(q0 + qi) * nlist + j] = s;
-        }
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int qi = 0; qi < QT; ++qi) {
+                const float s = wave_sum(acc[jt][qi]);
+                if (lane == 0 && qi < nqt && j + jt * nwaves < nlist) D[(size_t)(q0 + qi) * nlist + j + jt * nwaves] = s;
+            }
     }
 }
 
@@ -371,6 +386,9 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 // LDS (dynamic, nlist * 4 bytes) for the rounds of the selection when it fits (stage_row != 0).
 constexpr int kSelThreads = 512;
 constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
+constexpr int kSelGroups = 4 * kSelThreads; // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
+constexpr int kSelCand = 4096;              // ... and room for the keys collected under it
+static_assert(kSelGroups >= kMaxNprobe, "the bound is the nprobe-th smallest group minimum");
 
 __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__restrict__ D, int nparts,
                                                                     const float *__restrict__ q, int d,
@@ -386,7 +404,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     __shared__ unsigned s_hist[256];
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
-    __shared__ unsigned s_count;
+    __shared__ unsigned s_count, s_ncand;
     __shared__ float s_qpart[kSelThreads / kWave];
     const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
     float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
@@ -414,17 +432,85 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
         for (int i = tid; i < nlist; i += kSelThreads) s_row[i] = nparts > 0 ? __float_as_uint(dist_of(i)) : row[i];
         row = s_row;
-    } else if (nparts > 0) {                                 // too long for LDS: the distances replace part 0 in place
-        for (int i = tid; i < nlist; i += kSelThreads) grow[i] = dist_of(i);
     }
     __syncthreads();
     auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
-    const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
-    for (int i = tid; i < nlist; i += kSelThreads) {
-        const uint64_t key = key_at(i);
-        if (key <= T) {                                    // exactly nprobe keys qualify (keys are distinct)
-            const unsigned slot = atomicAdd(&s_count, 1u);
-            if (slot < (unsigned)np2) s_keys[slot] = key;
+    // Rows too long for LDS are cut down first, in two sweeps over global memory with sixteen loads in flight per
+    // thread: the centres are dealt to kSelGroups groups (centre i to group i mod kSelGroups) and every group
+    // keeps its smallest key; the nprobe-th smallest of those minima is an upper bound of the nprobe-th smallest
+    // key of the row (the minima are nprobe different keys of the row at or below it), so the second sweep
+    // collects every key up to that bound - about kSelGroups * -ln(1 - nprobe / kSelGroups) of them for
+    // exchangeable distances - and the selection runs on the collected keys in LDS.  (Selecting on the row itself
+    // takes five or more sweeps of dependent loads.)  More than kSelCand collected keys: the row is used after all.
+    bool from_cand = false;
+    uint64_t *s_cand = reinterpret_cast<uint64_t *>(sel_smem) + kSelGroups;
+    if (!stage_row) {
+        uint64_t *s_gmin = reinterpret_cast<uint64_t *>(sel_smem);
+        constexpr int U = 16;
+        static_assert(kSelGroups == 4 * kSelThreads && U % 4 == 0, "a thread owns four groups: tid + kSelThreads * (0..3)");
+        uint64_t gm[4] = {kSentinel, kSentinel, kSentinel, kSentinel};
+        for (int i0 = tid; i0 < nlist; i0 += U * kSelThreads) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kSelThreads;
+                v[u] = i < nlist ? (nparts > 0 ? dist_of(i) : grow[i]) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kSelThreads;
+                if (i < nlist) {
+                    if (nparts > 0) grow[i] = v[u];         // the distances replace part 0 in place (re-read by this thread only)
+                    const uint64_t key = ((uint64_t)__float_as_uint(v[u]) << 32) | (uint32_t)i;
+                    gm[u & 3] = key < gm[u & 3] ? key : gm[u & 3];
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) s_gmin[g * kSelThreads + tid] = gm[g];
+        if (tid == 0) s_ncand = 0;
+        __syncthreads();
+        auto gmin_at = [&](int i) { return s_gmin[i]; };
+        const uint64_t T0 = block_select_kth(gmin_at, kSelGroups, nprobe, s_hist, s_state);
+        for (int i0 = tid; i0 < nlist; i0 += U * kSelThreads) {
+            uint32_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kSelThreads;
+                v[u] = i < nlist ? row[i] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kSelThreads;
+                const uint64_t key = ((uint64_t)v[u] << 32) | (uint32_t)i;
+                if (i < nlist && key <= T0) {
+                    const unsigned slot = atomicAdd(&s_ncand, 1u);
+                    if (slot < (unsigned)kSelCand) s_cand[slot] = key;
+                }
+            }
+        }
+        __syncthreads();
+        from_cand = s_ncand <= (unsigned)kSelCand;         // uniform
+    }
+    if (from_cand) {
+        const int ncand = (int)s_ncand;
+        auto cand_at = [&](int i) { return s_cand[i]; };
+        const uint64_t T = block_select_kth(cand_at, ncand, nprobe, s_hist, s_state);
+        for (int i = tid; i < ncand; i += kSelThreads) {
+            const uint64_t key = s_cand[i];
+            if (key <= T) {                                // exactly nprobe keys qualify (keys are distinct)
+                const unsigned slot = atomicAdd(&s_count, 1u);
+                if (slot < (unsigned)np2) s_keys[slot] = key;
+            }
+        }
+    } else {
+        const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
+        for (int i = tid; i < nlist; i += kSelThreads) {
+            const uint64_t key = key_at(i);
+            if (key <= T) {
+                const unsigned slot = atomicAdd(&s_count, 1u);
+                if (slot < (unsigned)np2) s_keys[slot] = key;
+            }
         }
     }
     __syncthreads();
@@ -1027,8 +1113,12 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // (thr[q] in global memory, polled once per chunk).  At the end the workgroup's (at most KW) surviving keys
 // go to the partial-result buffer, unsorted; stage 4 (the merge kernel, or the last workgroups to finish
 // inside this kernel) selects among them.  RES: residual index (see the comment in process below).
+// STREAM: the code blocks are read with non-temporal loads.  That is faster when the codes come from HBM anyway
+// (measured on 16 GiB of codes: 5.7 instead of 5.5 TB/s) and slower when the batch's lists would otherwise be
+// found again in the caches by the next query or the next call (1 GiB of codes, 64 queries: 5.5 instead of
+// 6.3 TB/s), so the host chooses it by the size of the index.
 // ------------------------------------------------------------------------------------------------
-template <int C, int NSETS, bool RES>
+template <int C, int NSETS, bool RES, bool STREAM>
 __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     constexpr int MP = 16 * C;
     extern __shared__ __align__(16) unsigned char smem[];   // the kernel has no other LDS: smem starts at LDS address 0
@@ -1108,7 +1198,15 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
             }
         }
 #pragma unroll
-        for (int c = 0; c < C; ++c) w[c] = src[c * kWave];
+        for (int c = 0; c < C; ++c) {
+            if constexpr (STREAM) {
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + c * kWave));
+                w[c] = make_uint4(v.x, v.y, v.z, v.w);
+            } else {
+                w[c] = src[c * kWave];
+            }
+        }
         if (RES) m.tx = a.tx[tx_at + lane];                  // one more load per request, block or not
     };
     auto process = [&](const uint4 (&w)[C], const Meta &m) {
@@ -1391,23 +1489,24 @@ int launch_prime(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t
     return ix->p.residual ? launch_prime_r<C, true>(ix, nq, a, st) : launch_prime_r<C, false>(ix, nq, a, st);
 }
 
-template <int C, bool RES>
-int launch_scan_r(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
+template <int C, bool RES, bool STREAM>
+int launch_scan_rs(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
     // code blocks in flight per wave: as many as fit without register spills (the residual variant holds one more
     // value per lane and block)
     constexpr int NSETS = C <= (RES ? 3 : 4) ? 4 : (C <= 6 ? 2 : 1);
     static size_t configured = 0;
     if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS, RES>),
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS, RES, STREAM>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS, RES>), dim3(G), dim3(kScanThreads), lds, st, a);
+    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS, RES, STREAM>), dim3(G), dim3(kScanThreads), lds, st, a);
     return PIPERAG_OK;
 }
 template <int C>
-int launch_scan(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
-    return a.tx ? launch_scan_r<C, true>(a, G, lds, st) : launch_scan_r<C, false>(a, G, lds, st);
+int launch_scan(const ScanArgs &a, bool stream, int G, size_t lds, hipStream_t st) {
+    if (a.tx) return stream ? launch_scan_rs<C, true, true>(a, G, lds, st) : launch_scan_rs<C, true, false>(a, G, lds, st);
+    return stream ? launch_scan_rs<C, false, true>(a, G, lds, st) : launch_scan_rs<C, false, false>(a, G, lds, st);
 }
 
 #define PR_DISPATCH_C(expr_prefix, ...)                                         \
@@ -1444,7 +1543,7 @@ int coarse_parts(const piperag_index *ix, const float *q, int nq) {
 int launch_select(const piperag_index *ix, const float *q, int nq, int nprobe, int target, int max_wg, hipStream_t st) {
     const int nlist = ix->p.nlist;
     const int stage = nlist <= kSelMaxLdsRow;
-    const size_t lds = stage ? sizeof(float) * (size_t)nlist : 0;
+    const size_t lds = stage ? sizeof(float) * (size_t)nlist : sizeof(uint64_t) * (kSelGroups + kSelCand);
     static size_t configured = 0;
     if (lds > configured) {
         PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel),
@@ -1468,21 +1567,32 @@ int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t s
                            dim3(256), 0, st, q, nq, ix->centroids, nlist, d, dper, ix->ws_D);
         return PIPERAG_OK;
     }
-    const int groups = std::min((nlist + 3) / 4, 2048);
-    const dim3 grid(groups, (nq + QT - 1) / QT);
-    const size_t lds = sizeof(float) * QT * d;
+    // one query (the serving case) gets a kernel of its own: a quarter of the lookups and lane reductions
+    const int QTr = nq == 1 ? 1 : QT;
+    const int groups = std::min((nlist + 15) / 16, 2048);   // a workgroup's 4 waves take 4 centres each per turn
+    const dim3 grid(groups, (nq + QTr - 1) / QTr);
+    const size_t lds = sizeof(float) * QTr * d;
     static size_t configured = 48 * 1024;
-    if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 1>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
+    if (sizeof(float) * QT * d > configured) {
+        const int want = (int)(sizeof(float) * QT * d);
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 4, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 1, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<1, 4, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<1, 1, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
+        configured = want;
     }
-    if (d % 4 == 0)
-        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+    if (d % 4 == 0 && QTr == 1)
+        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+    else if (d % 4 == 0)
+        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+    else if (QTr == 1)
+        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
     else
-        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 1>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
     return PIPERAG_OK;
 }
 
@@ -1572,7 +1682,9 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     a.part2 = ix->ws_part2; a.done = ix->ws_done; a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
     const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
-    PR_DISPATCH_C(launch_scan, a, G, lds, st)
+    // indexes far larger than the last-level cache are streamed: nothing read now is still cached when it is needed again
+    const bool streaming = ix->streaming < 0 ? (size_t)ix->nblocks * kBlockVecs * ix->Mp >= kStreamingCodeBytes : ix->streaming > 0;
+    PR_DISPATCH_C(launch_scan, a, streaming, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[4], st));
     if (!fused)
@@ -1708,14 +1820,24 @@ int piperag_set_stage_timing(piperag_index *index, int enable) {
     return PIPERAG_OK;
 }
 
+static void drop_graphs(piperag_index *index) {
+    for (SearchGraph &g : index->graphs) {
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+        g = SearchGraph{};
+    }
+}
+
 int piperag_set_graph_replay(piperag_index *index, int enable) {
     PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     index->replay = enable != 0;
-    if (!index->replay)
-        for (SearchGraph &g : index->graphs) {
-            if (g.exec) (void)hipGraphExecDestroy(g.exec);
-            g = SearchGraph{};
-        }
+    if (!index->replay) drop_graphs(index);
+    return PIPERAG_OK;
+}
+
+int piperag_set_scan_streaming(piperag_index *index, int mode) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    index->streaming = mode < 0 ? -1 : (mode > 0 ? 1 : 0);
+    drop_graphs(index);              // a captured search holds the kernel that was chosen when it was captured
     return PIPERAG_OK;
 }
 

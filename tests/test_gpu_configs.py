@@ -3,7 +3,9 @@ and encoded on the GPU, a slice of the encoder output is checked against the ora
 whole index is checked by invariants, and the oracle searches a host copy of the probed lists.
 
 cfg1 and cfg2 run by default (seconds).  cfg3 and cfg4 take minutes to build and are enabled with
-PIPERAG_LARGE=cfg3,cfg4."""
+PIPERAG_LARGE=cfg3,cfg4.  The oracle encodes about 430 rows per second against 65,536 centres on 16 host cores
+(40 minutes for 2^20 rows), so the slice checked by default is 32,768 rows there; PIPERAG_SLICE_ROWS sets another
+size."""
 import os
 import time
 
@@ -36,17 +38,24 @@ def run_config(name, slice_rows, batches, max_check=64):
     lens = ix.ivf_list_lengths()
     assert ix.ivf_ntotal() == cfg.N and lens.sum() == cfg.N and lens.min() >= 0
     # ---- encoder against the oracle on a slice in the middle of the database
+    slice_rows = int(os.environ.get("PIPERAG_SLICE_ROWS", slice_rows))
     row0 = (cfg.N // 2) // 64 * 64 + 17
     xs = g.database(row0, slice_rows)
     gl, gc = ix.ivf_encode(xs)
     torch.cuda.synchronize()
     xh = xs.cpu().numpy()
-    assert np.array_equal(xh, gen.database(cfg, row0, slice_rows))        # device generator == numpy generator
-    nl, nc = parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), xh, coarse, pq)
+    gl_h, gc_h = gl.cpu().numpy(), gc.cpu().numpy()
+    nl = nc = 0
+    t1 = time.time()
+    for a in range(0, slice_rows, 4096):                                   # in pieces, so that progress is reported
+        b = min(a + 4096, slice_rows)
+        assert np.array_equal(xh[a:b], gen.database(cfg, row0 + a, b - a))  # device generator == numpy generator
+        dl, dc = parity.check_encoding(gl_h[a:b], gc_h[a:b], xh[a:b], coarse, pq)
+        nl, nc = nl + dl, nc + dc
+        print(f"[{name}] encode slice rows {a}..{b - 1} checked, {time.time() - t1:.0f}s", flush=True)
     print(f"[{name}] encode slice of {slice_rows}: {nl} list / {nc} code-byte differences, all at ties", flush=True)
     assert nl <= max(2, slice_rows // 200) and nc <= slice_rows * cfg.M // 200
     # the slice's vectors sit in the lists the encoder chose, with those codes
-    gl_h, gc_h = gl.cpu().numpy(), gc.cpu().numpy()
     for l in np.unique(gl_h)[:8]:
         codes, ids = ix.ivf_get_list(int(l))
         assert np.all(np.diff(ids) > 0)
@@ -106,12 +115,12 @@ def test_cfg2_full_size():
 
 @pytest.mark.skipif("cfg3" not in LARGE, reason="set PIPERAG_LARGE=cfg3 (builds 268 M vectors, minutes)")
 def test_cfg3_full_size():
-    run_config("cfg3", 8192, [(64, 64)], max_check=16)
+    run_config("cfg3", 32768, [(64, 64)], max_check=16)
 
 
 @pytest.mark.skipif("cfg4" not in LARGE, reason="set PIPERAG_LARGE=cfg4 (builds 1.07 G vectors, tens of minutes)")
 def test_cfg4_full_size():
-    run_config("cfg4", 8192, [(1, 128), (16, 128), (256, 128)], max_check=8)
+    run_config("cfg4", 32768, [(1, 128), (16, 128), (256, 128)], max_check=8)
 
 
 @pytest.mark.skipif("paper" not in LARGE, reason="set PIPERAG_LARGE=paper (builds 3 G vectors in two passes, 230 GB of HBM)")

@@ -418,6 +418,51 @@ def test_largest_nprobe_and_k():
     run_search_parity(pkg, ix, oidx, q, 1000, 1)
 
 
+def test_scan_with_streaming_loads_gives_the_same_results(cfg0):
+    # large indexes are scanned with non-temporal loads; forced here on a small one, against the oracle and
+    # bit for bit against the ordinary loads
+    pkg = P()
+    cfg, x, q, oidx = cfg0
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=cfg.nq, max_nprobe=cfg.nlist, max_k=128)
+    qd = dev(q)
+    for nprobe, k in [(cfg.nprobe, cfg.k), (cfg.nlist, 100)]:
+        ix.set_scan_streaming(0)
+        d0, i0 = ix.ivfpq_search(qd, nprobe, k)
+        ix.set_scan_streaming(1)
+        run_search_parity(pkg, ix, oidx, q, nprobe, k)
+        d1, i1 = ix.ivfpq_search(qd, nprobe, k)
+        torch.cuda.synchronize()
+        assert torch.equal(d0, d1) and torch.equal(i0, i1)
+    ix.set_scan_streaming(-1)
+
+
+def long_row_problem(adversarial):
+    """40,000 centres (a row of coarse distances too long for the selection's LDS staging) and few vectors.
+    adversarial: the centres close to the queries all sit at list numbers i with i mod 2048 < 512, so that
+    bounding the row by minima over interleaved groups of lists keeps far too many of them."""
+    rng = np.random.default_rng(77 + adversarial)
+    nlist, d, M, N = 40000, 16, 4, 3000
+    coarse = rng.normal(0.0, 1.0, (nlist, d)).astype(np.float32)
+    if adversarial:
+        far = (np.arange(nlist) % 2048) >= 512
+        coarse[far] += np.float32(20.0)
+    x = (coarse[rng.integers(0, nlist, N)] + rng.normal(0.0, 0.1, (N, d))).astype(np.float32)
+    q = rng.normal(0.0, 1.0 if not adversarial else 0.3, (6, d)).astype(np.float32)
+    pq = np.stack([oracle.kmeans(x[:, m * 4:(m + 1) * 4], 256, gen.draw_distinct_rows(N, 256, 5 + m), 2) for m in range(M)])
+    return x, q, coarse, pq
+
+
+@pytest.mark.parametrize("adversarial", [0, 1])
+def test_probe_selection_over_rows_too_long_for_lds(adversarial):
+    pkg = P()
+    x, q, coarse, pq = long_row_problem(adversarial)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=8, max_nprobe=1024, max_k=16)
+    for nq in (6, 1, 3):                   # matrix-core products finished by the selection; row-wise distances
+        for nprobe in (1, 50, 1024):
+            run_search_parity(pkg, ix, oidx, q[:nq], nprobe, 10)
+
+
 def test_two_pass_build_gives_the_same_index_as_the_one_pass_build():
     pkg = P()
     cfg, x, q, coarse, pq = make_problem(50000, 64, 40, 16, seed=77, nq=6)
@@ -483,6 +528,9 @@ def test_residual_index_search_and_encode(N, d, nlist, M, nprobe, k):
     ix = gpu_index_from_oracle(pkg, oidx, max_nq=16, max_nprobe=64, max_k=512)
     run_search_parity(pkg, ix, oidx, q, nprobe, k)
     run_search_parity(pkg, ix, oidx, q[:1], nprobe, k)
+    ix.set_scan_streaming(1)                    # the large-index variant of the scan
+    run_search_parity(pkg, ix, oidx, q, nprobe, k)
+    ix.set_scan_streaming(-1)
     # given probes (the constants of the lists are then computed by their own kernel), with a repeat and a gap
     probes = np.tile(np.arange(nprobe, dtype=np.int32), (q.shape[0], 1))
     probes[:, -1] = probes[:, 0]
