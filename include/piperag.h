@@ -207,10 +207,10 @@ int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, i
  * When enabled, every search call records HIP events around its stages on its stream;
  * piperag_stage_times synchronises on them and writes the most recent call's milliseconds:
  * [0] coarse quantiser, [1] top-nprobe selection, scan plan and work sharing, [2] wait for the lookup
- * tables (built on a side stream from the start of the call) and priming of the bound, [3] list scan with
- * k-selection (includes the merge for batches of up to 32 queries), [4] merge and id gather.  Stages
- * [0]+[1] are the index-scan term, [2]..[4] the vector-scan term. */
-#define PIPERAG_NSTAGES 5
+ * tables (built on a side stream from the start of the call), [3] list scan with k-selection, merge of
+ * the query's partial results and id gather (one kernel).  Stages [0]+[1] are the index-scan term,
+ * [2]+[3] the vector-scan term. */
+#define PIPERAG_NSTAGES 4
 int piperag_set_stage_timing(piperag_index *index, int enable);
 int piperag_stage_times(const piperag_index *index, float *out_ms_host /* [PIPERAG_NSTAGES] */);
 

@@ -11,8 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpiperag.so")
 _lib = None
 
-NSTAGES = 5
-STAGE_NAMES = ("coarse", "select+plan", "lut", "scan", "merge")
+NSTAGES = 4
+STAGE_NAMES = ("coarse", "select+plan", "lut", "scan+merge")
 
 
 class PiperagError(RuntimeError):

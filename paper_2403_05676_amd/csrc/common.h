@@ -27,7 +27,6 @@ constexpr int kCoarseSplitMaxLists = 8192;   // ... for indexes of up to this ma
 constexpr int kCtrStride = 32;         // chunk counters sit 128 bytes apart
 constexpr int kCtrPerQuery = 16;       // at most this many chunk counters share out one query's blocks
 constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
-constexpr int kMergeCap = 6144;        // keys the merge stage can hold in LDS
 constexpr size_t kStreamingCodeBytes = (size_t)4 << 30;   // indexes with at least this many code bytes are scanned with non-temporal loads
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
@@ -125,8 +124,8 @@ struct piperag_index {
     int64_t *ws_scanned;  // [max_nq]
     int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
     int4 *ws_desc;        // [kMaxScanWGs+max_nq] (query, number among the query's workgroups, their count, chunk counters in use) of each scan workgroup
-    uint64_t *ws_part2;   // same shape as ws_part: keys kept by groups of scan workgroups (merge inside the scan kernel)
-    uint32_t *ws_done;    // [kMaxScanWGs+2*max_nq] counters of that merge
+    uint32_t *ws_done;    // [max_nq + kMaxScanWGs + max_nq] finished scan workgroups (or groups of them) per query, then finished workgroups per group
+    uint64_t *ws_part2;   // same shape as ws_part: the queries' lists when a query's workgroups are grouped
     uint32_t *ws_tb;      // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
     uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
     float *ws_pcst;       // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
@@ -134,7 +133,7 @@ struct piperag_index {
     int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
     uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
     float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
-    uint64_t *ws_part;    // [(kMaxScanWGs+2*max_nq)*(max_k+64)] per-workgroup partial results
+    uint64_t *ws_part;    // [(kMaxScanWGs+2*max_nq)*(max_k+64)] key lists of the queries (or of their groups of workgroups): room for max_k+64 keys per scan workgroup
     float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
     int64_t *ws_out_i;    // [max_nq*max_k]
     int *flag;            // [1] device flag for argument checks

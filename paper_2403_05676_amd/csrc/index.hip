@@ -267,8 +267,8 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         (rc = dev_alloc(&ix->ws_tb, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_pcst, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
         (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
         (rc = dev_alloc(&ix->ws_part, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
-        (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->ws_done, (size_t)kMaxScanWGs + 2 * (size_t)p.max_nq)) ||
+        (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->pqE, (size_t)p.M * pqe_rows(ix->dsub) * kKsub)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))

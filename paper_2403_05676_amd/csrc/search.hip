@@ -1,10 +1,11 @@
 // Search path of libpiperag: coarse quantiser, top-nprobe selection, scan plan, lookup-table build,
-// list scan with k-selection, merge + id gather.  All kernels are written for gfx950 (wave64).
+// list scan with k-selection, merge of a query's partial results and id gather.  All kernels are written for
+// gfx950 (wave64).
 //
 // Method: Section 3.2 (S3) of the paper - nprobe of the nlist inverted lists are selected per query and
 // the product-quantised vectors inside them are compared with the query; Section 2 - the k closest are
 // returned.  The retrieval latency model of S3 splits the time into an index-scan term (stages 0-1 here)
-// and a vector-scan term proportional to nprobe (stages 2-4).
+// and a vector-scan term proportional to nprobe (stages 2-3).
 #include <stdlib.h>
 
 #include <algorithm>
@@ -112,6 +113,24 @@ __device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_h
         for (int i = threadIdx.x; i < n; i += blockDim.x) f(key_at(i));
     };
     return block_select_kth_each(each, kth, s_hist, s_state);
+}
+
+// In-place ascending sort of n <= 64 keys in LDS by one wavefront (all 64 lanes call it): one key per lane, bitonic
+// network over lane exchanges, unused lanes hold the sentinel.
+__device__ void wave_sort_u64(uint64_t *keys, int n) {
+    const int lane = threadIdx.x & 63;
+    uint64_t key = lane < n ? keys[lane] : kSentinel;
+#pragma unroll
+    for (int size = 2; size <= kWave; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const uint64_t other = (uint64_t)__shfl_xor((unsigned long long)key, stride, 64);
+            const bool up = (lane & size) == 0 || size == kWave, lower = (lane & stride) == 0;
+            const uint64_t lo = key < other ? key : other, hi = key < other ? other : key;
+            key = lower == up ? lo : hi;
+        }
+    }
+    if (lane < n) keys[lane] = key;
 }
 
 // In-place ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
@@ -231,17 +250,18 @@ __global__ __launch_bounds__(256) void coarse_mfma_kernel(const float *__restric
 // Per-query part of the plan, run by the first wavefront of a workgroup: pfx[i] = number of 64-vector blocks
 // in the first i probed lists (i = 0..nprobe), pblk[i] / plen[i] = first block and length of the i-th probed
 // list (0 for a skipped entry), *scanned = vectors in the probed lists, *thr = "no bound yet" for the scan's
-// shared threshold.  probe_at(i) gives the i-th probed list or -1.
+// shared threshold, *qdone = 0 for the scan's count of finished workgroups.  probe_at(i) gives the i-th probed list or -1.
 struct PlanOut {
     int32_t *pfx, *pblk, *plen;
     int64_t *scanned;
     uint32_t *thr;
     float *pcst;                 // residual indexes: |c_l|^2 - 2 <q, c_l> per probe (NULL otherwise)
+    uint32_t *qdone;             // scan workgroups (or groups of them) of the query that have finished
 };
 __device__ __forceinline__ PlanOut plan_of_query(const PlanOut &all, int qi, int probe_stride) {
     return PlanOut{all.pfx + (size_t)qi * (probe_stride + 1), all.pblk + (size_t)qi * probe_stride,
                    all.plen + (size_t)qi * probe_stride, all.scanned + qi, all.thr + qi,
-                   all.pcst ? all.pcst + (size_t)qi * probe_stride : nullptr};
+                   all.pcst ? all.pcst + (size_t)qi * probe_stride : nullptr, all.qdone + qi};
 }
 template <class ProbeFn>
 __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restrict__ list_blk,
@@ -272,7 +292,7 @@ __device__ void plan_query(ProbeFn probe_at, int nprobe, const int32_t *__restri
         for (int off = 32; off > 0; off >>= 1) len += __shfl_xor(len, off, 64);
         vecs += len;
     }
-    if (lane == 0) { pfx[nprobe] = running; *o.scanned = vecs; *o.thr = 0xFFFFFFFFu; }
+    if (lane == 0) { pfx[nprobe] = running; *o.scanned = vecs; *o.thr = 0xFFFFFFFFu; *o.qdone = 0; }
 }
 
 // Residual indexes, probe lists given by the caller: pcst[q][i] = |c_l|^2 - 2 <q, c_l> for l = the i-th probe
@@ -299,10 +319,12 @@ __global__ __launch_bounds__(64) void probe_const_kernel(const float *__restrict
 // chunk counters in use) of workgroup w; desc of spare workgroups has query -1.  A workgroup gets at least
 // kMinBlocksPerWG blocks on average (unless its query has fewer), so that small searches are not spread over
 // needlessly many workgroups.
+constexpr int kShareLdsQueries = 1024;
 struct ShareOut {
     int32_t *seg0;
     int4 *desc;
-    uint32_t *ctr, *done;
+    uint32_t *ctr;
+    uint32_t *gdone;            // [workgroups] finished workgroups per group of workgroups (zeroed here)
 };
 
 // The sharing itself, by the first 256 threads of the calling workgroup (all of its threads must call it: it
@@ -312,6 +334,8 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
     __shared__ long long s_total;
     __shared__ int32_t s_scan[256];
     __shared__ int32_t s_carry;
+    __shared__ int32_t s_seg0[kShareLdsQueries + 1];      // copy of seg0 for the search below (batches up to this size)
+    const bool seg_in_lds = nq <= kShareLdsQueries;
     const int tid = threadIdx.x;
     const bool act = tid < 256;
     if (tid == 0) { s_total = 0; s_carry = 0; }
@@ -344,24 +368,28 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
         const int32_t base = s_carry;
         int32_t before = 0;
         for (int w = 0; w < (tid >> 6) && w < 4; ++w) before += s_scan[w];
-        if (act && q < nq) o.seg0[q] = base + before + incl - sq;
+        if (act && q < nq) {
+            o.seg0[q] = base + before + incl - sq;
+            if (seg_in_lds) s_seg0[q] = base + before + incl - sq;
+        }
         __syncthreads();
         if (tid == 255) s_carry = base + before + incl;
         __syncthreads();
     }
-    if (tid == 0) o.seg0[nq] = s_carry;
+    if (tid == 0) { o.seg0[nq] = s_carry; if (seg_in_lds) s_seg0[nq] = s_carry; }
     __syncthreads();
+    auto seg_at = [&](int i) { return seg_in_lds ? s_seg0[i] : o.seg0[i]; };
     const int total_wg = s_carry;
     if (!act) return;
-    for (int w = tid; w < max_wg + nq; w += 256) o.done[w] = 0;   // merge counters: per group of workgroups, then per query
+    for (int w = tid; w < max_wg; w += 256) o.gdone[w] = 0;
     for (int w = tid; w < max_wg; w += 256) {
         if (w >= total_wg) { o.desc[w] = int4{-1, 0, 0, 0}; continue; }
         int lo = 0, hi = nq;                               // query of workgroup w: last q with seg0[q] <= w
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (o.seg0[mid] <= w) lo = mid; else hi = mid;
+            if (seg_at(mid) <= w) lo = mid; else hi = mid;
         }
-        const int seg = w - o.seg0[lo], S = o.seg0[lo + 1] - o.seg0[lo];
+        const int seg = w - seg_at(lo), S = seg_at(lo + 1) - seg_at(lo);
         // The query's chunks are dealt to P counters (chunk c belongs to counter c mod P) and its waves likewise
         // (wave g of the query draws from counter g mod P), so that the additions of a query with many
         // workgroups do not all queue up at one address.  Every wave starts on the chunk of its own number;
@@ -385,6 +413,12 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 // are >= 0 so their bit patterns order like the values), compaction, bitonic sort.  The row of D is staged in
 // LDS (dynamic, nlist * 4 bytes) for the rounds of the selection when it fits (stage_row != 0).
 constexpr int kSelThreads = 512;
+#ifdef PIPERAG_TRACE
+__device__ unsigned long long d_sel_trace[4096 * 8];
+#define SEL_MARK(j) do { if (threadIdx.x == 0) d_sel_trace[blockIdx.x * 8 + (j)] = wall_clock64(); } while (0)
+#else
+#define SEL_MARK(j) do {} while (0)
+#endif
 constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
 constexpr int kSelGroups = 4 * kSelThreads; // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
 constexpr int kSelCand = 4096;              // ... and room for the keys collected under it
@@ -407,13 +441,41 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     __shared__ unsigned s_count, s_ncand;
     __shared__ float s_qpart[kSelThreads / kWave];
     const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
+    SEL_MARK(0);
     float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
     const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
     for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
     if (tid == 0) s_count = 0;
+    // Inner product with centre i from the parts, summed in order.  With several parts all kCoarseMaxParts loads
+    // are made whatever their number (a missing part re-reads the last one and counts as +0), so that the loads
+    // of several centres can be in flight together.
+    const size_t part_stride = (size_t)nq * nlist;
+    auto dot_of = [&](int i) -> float {
+        float dot = grow[i];
+        if (nparts > 1) {                                    // uniform
+#pragma unroll
+            for (int p = 1; p < kCoarseMaxParts; ++p) {
+                const float v = grow[(size_t)min(p, nparts - 1) * part_stride + i];
+                dot += p < nparts ? v : 0.f;
+            }
+        }
+        return dot;
+    };
+    // the first sweep's products and centre norms are requested before the query's norm is reduced (one memory
+    // round trip instead of two)
+    constexpr int US = 8;
+    float pd[US], pc[US];
+    if (stage_row && nparts > 0) {
+#pragma unroll
+        for (int u = 0; u < US; ++u) {
+            const int i = tid + u * kSelThreads;
+            pd[u] = i < nlist ? dot_of(i) : 0.f;
+            pc[u] = i < nlist ? cn[i] : 0.f;
+        }
+    }
     float qn = 0.f;
-    if (nparts > 0 || plan.pcst) {                           // D holds partial inner products, or a residual index: the query's norm first
+    if (nparts > 0 || plan.pcst) {                           // D holds partial inner products, or a residual index: the query's norm
         float part = 0.f;
         for (int t = tid; t < d; t += kSelThreads) { const float v = q[(size_t)qi * d + t]; part += v * v; }
 #pragma unroll
@@ -423,17 +485,35 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
 #pragma unroll
         for (int w = 0; w < kSelThreads / kWave; ++w) qn += s_qpart[w];    // the same order in every thread
     }
-    auto dist_of = [&](int i) -> float {                      // distance to centre i from the parts, summed in order
-        float dot = grow[i];
-        for (int p = 1; p < nparts; ++p) dot += grow[(size_t)p * nq * nlist + i];
-        return fmaxf(0.f, qn + cn[i] - 2.f * dot);
-    };
+    auto finish = [&](float dot, float cnorm) -> float { return fmaxf(0.f, qn + cnorm - 2.f * dot); };
+    auto dist_of = [&](int i) -> float { return finish(dot_of(i), cn[i]); };
     if (stage_row) {
         uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
-        for (int i = tid; i < nlist; i += kSelThreads) s_row[i] = nparts > 0 ? __float_as_uint(dist_of(i)) : row[i];
+        for (int i0 = tid; i0 < nlist; i0 += US * kSelThreads) {
+            uint32_t v[US];
+            if (nparts > 0 && i0 != tid) {                   // later sweeps (uniform)
+#pragma unroll
+                for (int u = 0; u < US; ++u) {
+                    const int i = i0 + u * kSelThreads;
+                    pd[u] = i < nlist ? dot_of(i) : 0.f;
+                    pc[u] = i < nlist ? cn[i] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < US; ++u) {
+                const int i = i0 + u * kSelThreads;
+                v[u] = nparts > 0 ? __float_as_uint(finish(pd[u], pc[u])) : (i < nlist ? row[i] : 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < US; ++u) {
+                const int i = i0 + u * kSelThreads;
+                if (i < nlist) s_row[i] = v[u];
+            }
+        }
         row = s_row;
     }
     __syncthreads();
+    SEL_MARK(1);
     auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
     // Rows too long for LDS are cut down first, in two sweeps over global memory with sixteen loads in flight per
     // thread: the centres are dealt to kSelGroups groups (centre i to group i mod kSelGroups) and every group
@@ -514,7 +594,14 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         }
     }
     __syncthreads();
-    block_bitonic_sort_u64(s_keys, np2);
+    SEL_MARK(2);
+    if (np2 <= kWave) {                                      // uniform: up to 64 probes are sorted in the registers of one wave
+        if (tid < kWave) wave_sort_u64(s_keys, np2);
+        __syncthreads();
+    } else {
+        block_bitonic_sort_u64(s_keys, np2);
+    }
+    SEL_MARK(3);
     for (int i = tid; i < nprobe; i += kSelThreads) {
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
@@ -524,6 +611,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     if (mine.pcst)                                           // |q - c|^2 - |q|^2 = |c|^2 - 2 <q, c>
         for (int i = tid; i < nprobe; i += kSelThreads) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
     plan_query(probe_at, nprobe, list_blk, list_len, mine);
+    SEL_MARK(4);
     // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
     // workgroup publishes its query's number of blocks with a device-scope store, waits for it to complete and
     // adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
@@ -534,10 +622,12 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         s_ticket = atomicAdd(arrived, 1u);
     }
     __syncthreads();
+    SEL_MARK(5);
     if (s_ticket != gridDim.x - 1) return;                  // uniform
     auto blocks_of = [&](int q) { return (long long)__hip_atomic_load(&tb[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
     share_plan(blocks_of, (int)gridDim.x, target, max_wg, share);
     if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    SEL_MARK(6);
 }
 
 // Probe lists given by the caller: entries outside 0..nlist-1 and repeats of an earlier entry become -1
@@ -572,17 +662,20 @@ struct ScanArgs {
     const int32_t *plen;       // [nq][probe_stride] length of each probed list
     const float *pcst;         // residual indexes: [nq][probe_stride] constant of each probed list
     const float *tx;           // residual indexes: [slots] term of each stored vector
-    uint64_t *part;            // [workgroups][KW] partial results
+    uint64_t *part;            // [workgroups][KW] result lists of the queries
     uint32_t *thr;             // [nq] bound on the k-th best distance (bits)
     const int4 *desc;          // [workgroups] (query, number among the query's workgroups, their count, counters in use); query -1: spare
     uint32_t *ctr;             // [nq * kCtrPerQuery * kCtrStride] chunk counters of each query
     int nprobe, probe_stride, k, KW;
-    int cap;                   // scan only: slots of the workgroup's candidate buffer
-    // scan only, merge inside the scan kernel (fan > 0): the last workgroup to finish of every `fan` consecutive
-    // workgroups of a query reduces their keys to k, and the last such group of the query produces the result
+    int cap;                   // slots of the workgroup's candidate buffer
+    // Result of a query: its workgroups write the keys they still hold at the end to one list (KW slots per
+    // workgroup, in `part` from the query's first workgroup on), and the last of them to finish selects the k best
+    uint32_t *qdone;           // [nq] workgroups, or groups, of the query that have finished (zeroed by the plan)
+    int room;                  // keys that fit the LDS of a selection
+    // a query with more than `fan` workgroups collects its keys per group of fan consecutive workgroups first
     int fan;
-    uint64_t *part2;           // [workgroups][KW] keys kept by the groups
-    uint32_t *done;            // [workgroups + nq] finished workgroups per group, finished groups per query (zeroed by the plan)
+    uint32_t *gdone;           // [workgroups] finished workgroups of a group, at the group's first workgroup (zeroed by the plan)
+    uint64_t *part2;           // [workgroups][KW] the queries' lists when there are groups (the groups' lists are in part)
     const int64_t *ids;
     float *out_d;
     int64_t *out_i;
@@ -598,10 +691,9 @@ constexpr int kKeepSlack = 64;                        // pruning keeps between k
 constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack, at most
 constexpr int kCandRoomMin = 512;                     // and at least (the scan needs more than kScanThreads)
 constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
-constexpr int kPrimeBlocks = 32;                      // blocks of the closest lists scanned to prime the bound
 constexpr int kChunkBlocks = 4;                       // consecutive blocks a scan wave takes at a time
 
-// LDS carve-up shared by the priming and the scan kernel (all dynamic, so that the table starts at address 0)
+// LDS carve-up of the scan kernel (all dynamic, so that the table starts at address 0)
 struct ScanLds {
     float *lut;                  // [256*Mp]
     uint64_t *cand;              // [cap]
@@ -703,22 +795,32 @@ __device__ __forceinline__ void append_candidates(bool pass, uint32_t dbits, uin
 __device__ uint64_t wg_prune(const ScanLds s, int n, int k) {
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     uint64_t mine[kCandPerThread];
-    uint64_t kmin = ~0ull, kmax = 0;
+    // range of the keys: from the smallest and the largest distance (32-bit lane exchanges instead of 64-bit ones)
+    uint32_t dmin = 0xFFFFFFFFu, dmax = 0;
 #pragma unroll
     for (int e = 0; e < kCandPerThread; ++e) {
         const int i = tid + e * nt;
-        mine[e] = i < n ? s.cand[i] : kSentinel;
-        if (i < n) { kmin = min(kmin, mine[e]); kmax = max(kmax, mine[e]); }
+        mine[e] = kSentinel;
+        if (e * nt < n) {                   // uniform: rounds of the buffer beyond its fill are skipped
+            if (i < n) {
+                mine[e] = s.cand[i];
+                const uint32_t dd = (uint32_t)(mine[e] >> 32);
+                dmin = min(dmin, dd); dmax = max(dmax, dd);
+            }
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        kmin = min(kmin, (uint64_t)__shfl_xor((unsigned long long)kmin, off, 64));
-        kmax = max(kmax, (uint64_t)__shfl_xor((unsigned long long)kmax, off, 64));
+        dmin = min(dmin, (uint32_t)__shfl_xor(dmin, off, 64));
+        dmax = max(dmax, (uint32_t)__shfl_xor(dmax, off, 64));
     }
     if (tid == 0) { s.state[3] = ~0ull; s.state[4] = 0; }
     for (int i = tid; i < 256; i += nt) s.hist[i] = 0;
     __syncthreads();
-    if (lane == 0) { atomicMin(&s.state[3], (unsigned long long)kmin); atomicMax(&s.state[4], (unsigned long long)kmax); }
+    if (lane == 0) {
+        atomicMin(&s.state[3], (unsigned long long)dmin << 32);
+        atomicMax(&s.state[4], ((unsigned long long)dmax << 32) | 0xFFFFFFFFull);
+    }
     __syncthreads();
     uint64_t lo = s.state[3], hi = s.state[4];
     unsigned need = (unsigned)k, kept_below = 0;
@@ -728,7 +830,8 @@ __device__ uint64_t wg_prune(const ScanLds s, int n, int k) {
         const int sh = width < 256 ? 0 : (56 - __clzll((long long)width));   // (width >> sh) <= 255
 #pragma unroll
         for (int e = 0; e < kCandPerThread; ++e)
-            if (mine[e] != kSentinel && mine[e] >= lo && mine[e] <= hi) atomicAdd(&s.hist[(unsigned)((mine[e] - lo) >> sh)], 1u);
+            if (e * nt < n && mine[e] != kSentinel && mine[e] >= lo && mine[e] <= hi)
+                atomicAdd(&s.hist[(unsigned)((mine[e] - lo) >> sh)], 1u);
         __syncthreads();
         if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
             unsigned h[4], sum = 0;
@@ -763,9 +866,18 @@ __device__ uint64_t wg_prune(const ScanLds s, int n, int k) {
     }
     if (tid == 0) s.misc[0] = 0;
     __syncthreads();
+    // the kept keys go back to the front of the buffer: one counter update per wave and round
 #pragma unroll
-    for (int e = 0; e < kCandPerThread; ++e)
-        if (mine[e] <= T && mine[e] != kSentinel) s.cand[atomicAdd(&s.misc[0], 1u)] = mine[e];
+    for (int e = 0; e < kCandPerThread; ++e) {
+        if (e * nt < n) {                   // uniform
+            const bool keep = mine[e] <= T && mine[e] != kSentinel;
+            const uint64_t mask = __ballot(keep);
+            unsigned base = 0;
+            if (lane == 0 && mask != 0) base = atomicAdd(&s.misc[0], (unsigned)__popcll(mask));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (keep) s.cand[base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull))] = mine[e];
+        }
+    }
     __syncthreads();
     return T;
 }
@@ -851,16 +963,11 @@ __device__ __forceinline__ void store_probe_tables(const ScanArgs &a, const Scan
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage 2: lookup tables + priming of the bound.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2,
+// Stage 2: lookup tables.  entry(q, m, j) = sum_t (query_q[m*dsub+t] - pq[m][j][t])^2,
 // stored in the scan layout lut[q][j][Mp] (rows of padding sub-quantisers m >= M are zero), built from the
 // centre-major copy of the codebook pqT[j][m][t] by four workgroups per query (the codebook read, 768 KiB at
-// d = 768, is what the build costs, so it is spread over several compute units).  A second kernel scans the
-// first kPrimeBlocks blocks of each query's probed lists with its table and sets thr[q] to a distance that at
-// least k of those vectors reach: the scan proper starts with a useful bound instead of accepting everything.
+// d = 768, is what the build costs, so it is spread over several compute units).
 // ------------------------------------------------------------------------------------------------
-constexpr int kLutThreads = 512;
-constexpr int kLutWaves = kLutThreads / kWave;
-static_assert(kPrimeBlocks % kLutWaves == 0, "priming blocks are shared out evenly over the waves");
 
 // One table entry: squared distance between dsub query coordinates and dsub centre coordinates.  DSUB > 0
 // fixes dsub at compile time (all loads of several entries can then be in flight together).
@@ -922,75 +1029,6 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
     }
 }
 
-// Priming of the bound: one workgroup (512 threads) per query stages the query's table in LDS, scans the first
-// kPrimeBlocks blocks of the query's probed lists (the closest lists come first) and sets thr[q] to a distance
-// that at least k of those vectors reach.
-template <int C, bool RES>
-__global__ __launch_bounds__(kLutThreads) void prime_kernel(ScanArgs a) {
-    constexpr int MP = 16 * C;
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int cap = kPrimeBlocks * kBlockVecs;
-    const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qi = blockIdx.x;
-    const bool lut_at_zero =
-        reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
-    // the table starts on its way to LDS first (it depends on nothing else), then the probe tables; every wave
-    // then requests all its blocks, waits for the table, and works through the blocks
-    ProbeTableRegs<kLutThreads> tables;
-    load_probe_tables(a, qi, tables);
-    lut_copy_begin<kLutThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
-    store_probe_tables(a, s, tables);
-    __syncthreads();
-    const int TB = s.pfx[a.nprobe];
-    const int nb = min(TB, kPrimeBlocks);
-    const int lane_m = lane % MP;
-    uint32_t off4[16];
-    make_off4(off4, lane);
-    constexpr int kPerWave = kPrimeBlocks / kLutWaves;
-    uint4 w[kPerWave][C];
-    uint32_t gblock[kPerWave];
-    int nvalid[kPerWave];
-    float extra[kPerWave];            // residual indexes: the vector's own term + the list's constant
-    int pi = 0;
-#pragma unroll
-    for (int i = 0; i < kPerWave; ++i) {
-        const int b = wave + i * kLutWaves;
-        nvalid[i] = 0;
-        gblock[i] = 0;
-        extra[i] = 0.f;
-        if (b < nb) {
-            while (b >= s.pfx[pi + 1]) ++pi;                  // b < TB = pfx[nprobe]
-            const int bl = b - s.pfx[pi];
-            gblock[i] = (uint32_t)(s.blk[pi] + bl);
-            nvalid[i] = s.len[pi] - bl * kBlockVecs;
-            const uint4 *blk = reinterpret_cast<const uint4 *>(a.codes + (size_t)gblock[i] * kBlockVecs * MP);
-#pragma unroll
-            for (int c = 0; c < C; ++c) w[i][c] = blk[c * kWave + lane];
-            if (RES) extra[i] = a.tx[(size_t)gblock[i] * kBlockVecs + lane] + s.cst[pi];
-        }
-    }
-    lut_copy_end<kLutThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kPerWave; ++i) {
-        if (nvalid[i] > 0) {                                  // uniform per wave
-            float dist;
-            if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w[i]), off4);
-            else dist = block_dist_generic<C>(w[i], s.lut, lane_m);
-            if (RES) dist = fmaxf(0.f, dist + extra[i]);
-            append_candidates(lane < nvalid[i], __float_as_uint(dist), gblock[i] * kBlockVecs + lane, s.cand, &s.misc[0], cap,
-                              lane);
-        }
-    }
-    __syncthreads();
-    const int n = min((int)lds_peek(&s.misc[0]), cap);
-    if (n > a.k) {                          // uniform
-        const uint32_t T = (uint32_t)(wg_prune(s, n, a.k) >> 32);
-        if (tid == 0) a.thr[qi] = T;        // plan_query set "no bound"; the scan only lowers it from here
-    }
-}
-
 // Tap: the tables in canonical layout out[(q*M + m)*256 + j].
 __global__ __launch_bounds__(256) void lut_tap_kernel(const float *__restrict__ q, const float *__restrict__ pq, int d, int M,
                                                       int dsub, float *__restrict__ out) {
@@ -1018,44 +1056,48 @@ __device__ __forceinline__ void publish_keys() {
     __syncthreads();
 }
 
-// Reduction of `count` partial key arrays (KW slots each, consecutive in src; unused slots hold kSentinel) by
-// one workgroup: the keys within the bound are gathered into s_keys (the caller guarantees count * KW <=
-// room there) and the k smallest selected.  FINAL = false: they are written to dst[0..KW) (unsorted, padded
-// with kSentinel).  FINAL = true: ids are looked up and the results written to out_d / out_i, sorted by
-// (distance, id) and padded with (+inf, -1); s_d / s_id: power-of-two >= k slots.
+// Selection from a key list by one workgroup: the k smallest of the keys in list[0..n) (global memory, written by
+// this and other workgroups, all different).  Up to `room` keys are gathered into s_keys first (those within
+// `bound`, which at least k keys are if k exist) and selected there; a longer list is selected in place, one
+// sweep over global memory per round.
+// FINAL = true: ids are looked up and the results written to out_d / out_i, sorted by (distance, id) and padded
+// with (+inf, -1); s_d / s_id: power-of-two >= k slots.
+// FINAL = false: the selected keys are written to dst[0..KW), unsorted and padded with kSentinel.
+// Slots of `list` that hold kSentinel are skipped.
 template <bool FINAL>
-__device__ void reduce_partials(const uint64_t *__restrict__ src, int count, int KW, int k, uint32_t bound, uint64_t *s_keys,
-                                unsigned *s_hist, unsigned long long *s_state, unsigned *s_count, uint64_t *__restrict__ dst,
-                                const int64_t *__restrict__ ids, uint32_t *s_d, int64_t *s_id, float *__restrict__ out_d,
-                                int64_t *__restrict__ out_i) {
+__device__ void select_from_list(const uint64_t *__restrict__ list, int n, int room, int k, uint32_t bound, uint64_t *s_keys,
+                                 unsigned *s_hist, unsigned long long *s_state, unsigned *s_count,
+                                 const int64_t *__restrict__ ids, uint32_t *s_d, int64_t *s_id, float *__restrict__ out_d,
+                                 int64_t *__restrict__ out_i, uint64_t *__restrict__ dst, int KW) {
     const int tid = threadIdx.x, nt = blockDim.x;
-    const int n = count * KW;
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
     if (FINAL)
         for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
     if (tid == 0) *s_count = 0;
     __syncthreads();
-    for (int i0 = tid; i0 < n; i0 += 8 * nt) {                   // 8 loads in flight per thread, then the appends
-        uint64_t key[8];
+    const bool in_lds = n <= room;                               // uniform
+    int found = n;
+    if (in_lds) {
+        for (int i0 = tid; i0 < n; i0 += 8 * nt) {               // 8 loads in flight per thread, then the appends
+            uint64_t key[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) key[j] = i0 + j * nt < n ? load_key(src + i0 + j * nt) : kSentinel;
+            for (int j = 0; j < 8; ++j) key[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound) s_keys[atomicAdd(s_count, 1u)] = key[j];
+            for (int j = 0; j < 8; ++j)
+                if (key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound) s_keys[atomicAdd(s_count, 1u)] = key[j];
+        }
+        __syncthreads();
+        found = (int)*s_count;
+        __syncthreads();
     }
-    __syncthreads();
-    const int found = (int)*s_count;
-    __syncthreads();
+    auto key_at = [&](int i) { return in_lds ? s_keys[i] : load_key(list + i); };
     uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
-    if (found > k) {
-        auto key_at = [&](int i) { return s_keys[i]; };
-        T = block_select_kth(key_at, found, k, s_hist, s_state);
-    }
+    if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state);
     if (tid == 0) *s_count = 0;
     __syncthreads();
     for (int i = tid; i < found; i += nt) {
-        const uint64_t key = s_keys[i];
-        if (key <= T) {                                          // min(found, k) keys qualify (keys are distinct)
+        const uint64_t key = key_at(i);
+        if (key <= T) {                                          // at most k keys qualify (keys are distinct; kSentinel > T)
             const unsigned slot = atomicAdd(s_count, 1u);
             if (FINAL) { s_d[slot] = (uint32_t)(key >> 32); s_id[slot] = ids[(uint32_t)key]; }
             else store_key(dst + slot, key);
@@ -1091,8 +1133,8 @@ __device__ void reduce_partials(const uint64_t *__restrict__ src, int count, int
     }
 }
 
-// Room for keys when the table and candidate areas of the scan kernel's LDS are reused for the reduction above
-// (after s_id and s_d for the final step).
+// Room for keys when the table and candidate areas of the scan kernel's LDS are reused for the final selection
+// (after its s_id and s_d).
 __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
     const int k2 = k <= 2 ? 2 : 1 << (32 - __builtin_clz((unsigned)(k - 1)));
     return (1024 * Mp + 8 * cap - 12 * k2) / 8;
@@ -1111,8 +1153,9 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // no blocks left) waits at a barrier, and once all four are there the buffer is pruned to about k keys and
 // the bound tightened.  The bound is the smallest such value any workgroup of the query has reached
 // (thr[q] in global memory, polled once per chunk).  At the end the workgroup's (at most KW) surviving keys
-// go to the partial-result buffer, unsorted; stage 4 (the merge kernel, or the last workgroups to finish
-// inside this kernel) selects among them.  RES: residual index (see the comment in process below).
+// go to the query's key list, unsorted, and the query's last workgroup to finish selects the k best among
+// them, looks up the ids and writes the results (see the end of the kernel).  RES: residual index (see the
+// comment in process below).
 // STREAM: the code blocks are read with non-temporal loads.  That is faster when the codes come from HBM anyway
 // (measured on 16 GiB of codes: 5.7 instead of 5.5 TB/s) and slower when the batch's lists would otherwise be
 // found again in the caches by the next query or the next call (1 GiB of codes, 64 queries: 5.5 instead of
@@ -1311,144 +1354,62 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[3] = wall_clock64();
 #endif
-    uint64_t *out = a.part + (size_t)wg * KW;
-    for (int i = tid; i < KW; i += kScanThreads) store_key(out + i, i < n ? s.cand[i] : kSentinel);
+    // What the workgroup still holds goes to its KW slots (padded with kSentinel) of a key list: the query's, or,
+    // when the query has more workgroups than one selection can take in LDS (fan), the list of its group of fan
+    // consecutive workgroups.  The keys are written before the workgroup adds itself to the count of finished
+    // workgroups; whoever sees that count complete may read the whole list.  The last workgroup of a group passes
+    // the group's k best on to the query's list in the same way, and the last group of the query (or its last
+    // workgroup, without groups) selects the results.  (With local bounds only, a query spread over S workgroups
+    // ends with about k keys per workgroup that none of them can rule out; that is what the two levels are for.)
+    const int seg = desc.y, S = desc.z, wg0 = wg - seg;          // the query's workgroups: wg0 .. wg0 + S - 1
+    const int fan = a.fan, R = (S + fan - 1) / fan;              // R groups (R = 1: no groups)
+    const int r = R == 1 ? 0 : seg / fan, gsize = R == 1 ? S : min(fan, S - r * fan);
+    uint64_t *list = a.part + (size_t)(wg0 + r * fan) * KW;      // of the group (of the query, without groups)
+    uint32_t *ldone = R == 1 ? &a.qdone[qi] : &a.gdone[wg0 + r];
+    uint64_t *mine = list + (size_t)(seg - r * fan) * KW;
+    for (int i = tid; i < KW; i += kScanThreads) store_key(mine + i, i < n ? s.cand[i] : kSentinel);
 #ifdef PIPERAG_TRACE
     if (tid == 0) tr[4] = wall_clock64();
 #endif
-    if (a.fan <= 0) return;         // the merge kernel takes over
-    // Merge inside this kernel.  A workgroup's keys are published before it adds itself to its group's counter;
-    // whoever sees the count complete may read them all.
-    const int seg = desc.y, S = desc.z, wg0 = wg - seg;          // wg0: the query's first workgroup
-    const int r = seg / a.fan, gsize = min(a.fan, S - r * a.fan), R = (S + a.fan - 1) / a.fan;
+    publish_keys();
+    if (tid == 0) s.misc[4] = atomicAdd(ldone, 1u);
+    __syncthreads();
+#ifdef PIPERAG_TRACE
+    if (tid == 0 && (a.flags & 4)) tr[5] = wall_clock64();
+#endif
+    if (s.misc[4] != (unsigned)(gsize - 1)) return;              // uniform
+    // the last workgroup of the list: selection in the LDS that held table and candidates
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
     int64_t *s_id = reinterpret_cast<int64_t *>(smem);
     uint32_t *s_d = reinterpret_cast<uint32_t *>(s_id + k2);
     uint64_t *s_keys = reinterpret_cast<uint64_t *>(smem + 12 * (size_t)k2);
     float *res_d = a.out_d + (size_t)qi * k;
     int64_t *res_i = a.out_i + (size_t)qi * k;
-    publish_keys();
-    if (tid == 0) s.misc[4] = atomicAdd(&a.done[wg0 + r], 1u);
-    __syncthreads();
-#ifdef PIPERAG_TRACE
-    if (tid == 0 && (a.flags & 4)) tr[5] = wall_clock64();
-#endif
-    if (s.misc[4] != (unsigned)(gsize - 1)) return;              // uniform
     uint32_t bound = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (R == 1) {
-        reduce_partials<true>(a.part + (size_t)wg0 * KW, S, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, a.ids,
-                              s_d, s_id, res_d, res_i);
+        select_from_list<true>(list, S * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], a.ids, s_d, s_id, res_d, res_i,
+                               nullptr, KW);
 #ifdef PIPERAG_TRACE
         if (tid == 0 && (a.flags & 4)) tr[6] = wall_clock64();
 #endif
         return;
     }
-    reduce_partials<false>(a.part + (size_t)(wg0 + r * a.fan) * KW, gsize, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0],
-                           a.part2 + (size_t)(wg0 + r) * KW, nullptr, nullptr, nullptr, nullptr, nullptr);
+    uint64_t *list2 = a.part2 + (size_t)wg0 * KW;                // the query's list: KW slots per group
+    select_from_list<false>(list, gsize * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, nullptr, nullptr,
+                            nullptr, nullptr, list2 + (size_t)r * KW, KW);
+#ifdef PIPERAG_TRACE
+    if (tid == 0 && (a.flags & 4)) tr[6] = wall_clock64();
+#endif
     publish_keys();
-    if (tid == 0) s.misc[4] = atomicAdd(&a.done[gridDim.x + qi], 1u);
+    if (tid == 0) s.misc[4] = atomicAdd(&a.qdone[qi], 1u);
     __syncthreads();
     if (s.misc[4] != (unsigned)(R - 1)) return;                  // uniform
     bound = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    reduce_partials<true>(a.part2 + (size_t)wg0 * KW, R, KW, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, a.ids, s_d,
-                          s_id, res_d, res_i);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Stage 4: merge of the partial results of one query + id gather.  One workgroup of 1024 threads per
-// query.  Only keys within the query's final bound thr[q] can be among the k best; they are compacted into
-// LDS, the k smallest are selected there by radix selection.  If more than kMergeCap keys survive the
-// bound (e.g. no workgroup ever collected k candidates, so there is no bound), the selection runs over the
-// partial keys in global memory instead.  Then ids are looked up and the k results are sorted by
-// (distance, id).
-// ------------------------------------------------------------------------------------------------
-constexpr int kMergeThreads = 1024;
-
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const uint64_t *__restrict__ part,
-                                                              const int32_t *__restrict__ seg0, int KW, int k,
-                                                              const int64_t *__restrict__ ids,
-                                                              const uint32_t *__restrict__ thr, float *__restrict__ out_d,
-                                                              int64_t *__restrict__ out_i) {
-    __shared__ uint64_t s_keys[kMergeCap];
-    __shared__ unsigned s_hist[256];
-    __shared__ unsigned long long s_state[8];
-    __shared__ uint32_t s_d[kMaxK];
-    __shared__ int64_t s_id[kMaxK];
-    __shared__ unsigned s_count;
-    const int qi = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    const int n = (seg0[qi + 1] - seg0[qi]) * KW;            // KW slots per workgroup, unused ones hold kSentinel
-    const uint64_t *keys = part + (size_t)seg0[qi] * KW;
-    const uint32_t bound = thr[qi];
-    const int k2 = max(2, 1 << (32 - __clz(k - 1)));
-    for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
-    if (tid == 0) s_count = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += nt) {
-        const uint64_t key = keys[i];
-        if (key != kSentinel && (uint32_t)(key >> 32) <= bound) {
-            const unsigned slot = atomicAdd(&s_count, 1u);
-            if (slot < (unsigned)kMergeCap) s_keys[slot] = key;
-        }
-    }
-    __syncthreads();
-    const int found = (int)s_count;
-    __syncthreads();
-    if (found <= kMergeCap) {
-        uint64_t T = kSentinel - 1;                              // fewer than k candidates: keep them all
-        if (found > k) {
-            auto key_at = [&](int i) { return s_keys[i]; };
-            T = block_select_kth(key_at, found, k, s_hist, s_state);
-        }
-        if (tid == 0) s_count = 0;
-        __syncthreads();
-        for (int i = tid; i < found; i += nt) {
-            const uint64_t key = s_keys[i];
-            if (key <= T) {
-                const unsigned slot = atomicAdd(&s_count, 1u);   // min(found, k) keys qualify (keys are distinct)
-                if (slot < (unsigned)k) {
-                    s_d[slot] = (uint32_t)(key >> 32);
-                    s_id[slot] = ids[(uint32_t)key];
-                }
-            }
-        }
-    } else {
-        auto key_at = [&](int i) { return keys[i]; };
-        const uint64_t T = block_select_kth(key_at, n, k, s_hist, s_state);
-        if (tid == 0) s_count = 0;
-        __syncthreads();
-        for (int i = tid; i < n; i += nt) {
-            const uint64_t key = keys[i];
-            if (key <= T && key != kSentinel) {
-                const unsigned slot = atomicAdd(&s_count, 1u);   // exactly k keys are <= T (keys are distinct)
-                if (slot < (unsigned)k) {
-                    s_d[slot] = (uint32_t)(key >> 32);
-                    s_id[slot] = ids[(uint32_t)key];
-                }
-            }
-        }
-    }
-    __syncthreads();
-    const int cnt = min((int)s_count, k);
-    // bitonic sort of (distance bits, id) pairs
-    for (int size = 2; size <= k2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int i = tid; i < (k2 >> 1); i += nt) {
-                const int lo = 2 * i - (i & (stride - 1));
-                const int hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint32_t da = s_d[lo], db = s_d[hi];
-                const int64_t ia = s_id[lo], ib = s_id[hi];
-                const bool gt = da > db || (da == db && ia > ib);
-                if (gt == up) { s_d[lo] = db; s_d[hi] = da; s_id[lo] = ib; s_id[hi] = ia; }
-            }
-        }
-    }
-    __syncthreads();
-    for (int i = tid; i < k; i += nt) {
-        out_d[(size_t)qi * k + i] = i < cnt ? __uint_as_float(s_d[i]) : __builtin_inff();
-        out_i[(size_t)qi * k + i] = i < cnt ? s_id[i] : -1;
-    }
+    select_from_list<true>(list2, R * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], a.ids, s_d, s_id, res_d, res_i,
+                           nullptr, KW);
+#ifdef PIPERAG_TRACE
+    if (tid == 0 && (a.flags & 4)) tr[7] = wall_clock64();
+#endif
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1469,24 +1430,6 @@ void launch_lut_build(const piperag_index *ix, const float *q, int nq, hipStream
         case 16: launch_lut_build_d<16>(ix, q, nq, st); break;
         default: launch_lut_build_d<0>(ix, q, nq, st); break;
     }
-}
-
-template <int C, bool RES>
-int launch_prime_r(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
-    const size_t lds = scan_lds_bytes(ix->Mp, kPrimeBlocks * kBlockVecs, a.nprobe);
-    PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "priming kernel needs %zu bytes of LDS", lds);
-    static size_t configured = 0;
-    if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&prime_kernel<C, RES>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
-    }
-    hipLaunchKernelGGL((prime_kernel<C, RES>), dim3(nq), dim3(kLutThreads), lds, st, a);
-    return PIPERAG_OK;
-}
-template <int C>
-int launch_prime(const piperag_index *ix, int nq, const ScanArgs &a, hipStream_t st) {
-    return ix->p.residual ? launch_prime_r<C, true>(ix, nq, a, st) : launch_prime_r<C, false>(ix, nq, a, st);
 }
 
 template <int C, bool RES, bool STREAM>
@@ -1523,10 +1466,11 @@ int launch_scan(const ScanArgs &a, bool stream, int G, size_t lds, hipStream_t s
     }
 
 PlanOut plan_bufs(const piperag_index *ix) {
-    return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr, ix->p.residual ? ix->ws_pcst : nullptr};
+    return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr, ix->p.residual ? ix->ws_pcst : nullptr,
+                   ix->ws_done};
 }
 
-ShareOut share_bufs(const piperag_index *ix) { return ShareOut{ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_done}; }
+ShareOut share_bufs(const piperag_index *ix) { return ShareOut{ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_done + ix->p.max_nq}; }
 
 // Parts of the depth the matrix-core coarse quantiser is split into for this shape (0: the row-wise kernel
 // runs instead and writes finished distances).
@@ -1660,8 +1604,6 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     g_trace_buf = trace_buf; g_trace_n = G;
 #endif
     PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
-    PR_DISPATCH_C(launch_prime, ix, nq, a, st)
-    if (rc != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
     // Candidate slots: as many as kCandRoom beyond the keys kept, but fewer if that lets two workgroups share a
     // compute unit's 160 KiB of LDS (long probe tables would otherwise push the second one out).
@@ -1671,32 +1613,29 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
         if (fixed + 8 * (size_t)kCandRoom > half && fixed + 8 * (size_t)kCandRoomMin <= half) room = (int)((half - fixed) / 8);
     }
     a.cap = KW + room;
-    // The merge runs inside the scan kernel when two levels of reduction in its LDS cover any number of
-    // workgroups a query can get; otherwise (very large k with short codes) the merge kernel does it.
-    const int fan = reduce_room_keys(ix->Mp, a.cap, k) / KW;
-    // It pays when a query is spread over many workgroups (one merge workgroup per query would then have to
-    // read thousands of keys alone); with few workgroups per query the separate kernel's 1024 threads are as
-    // fast and keep the scan kernel's tail short.
-    const bool fused = fan >= 2 && (long long)fan * fan >= G && nq * 16 <= target_wgs;
-    a.fan = fused ? fan : 0;
-    a.part2 = ix->ws_part2; a.done = ix->ws_done; a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
+    // the query's last workgroup selects the results in the LDS that held its table and candidates
+    a.qdone = ix->ws_done;
+    a.room = reduce_room_keys(ix->Mp, a.cap, k);
+    // groups of workgroups whose keys fit one selection; if two levels do not cover a query's workgroups (very large
+    // k with short codes), there are no groups and a long list is selected in global memory
+    a.fan = std::max(1, a.room / KW);
+    if ((long long)a.fan * a.fan < G) a.fan = G;
+    a.gdone = ix->ws_done + ix->p.max_nq;
+    a.part2 = ix->ws_part2;
+    a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
     const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
     // indexes far larger than the last-level cache are streamed: nothing read now is still cached when it is needed again
     const bool streaming = ix->streaming < 0 ? (size_t)ix->nblocks * kBlockVecs * ix->Mp >= kStreamingCodeBytes : ix->streaming > 0;
     PR_DISPATCH_C(launch_scan, a, streaming, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
-    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[4], st));
-    if (!fused)
-        hipLaunchKernelGGL(merge_kernel, dim3(nq), dim3(kMergeThreads), 0, st, ix->ws_part, ix->ws_seg0, KW, k, ix->ids, ix->ws_thr,
-                           out_d, out_i);
-    if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[5], st)); ix->ev_valid = true; }
+    if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[4], st)); ix->ev_valid = true; }
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
 }
 
-// A search is about six launches and four event operations; enqueueing them one by one costs the host about
-// 45 us, a large part of a single query's latency.  With replay enabled (piperag_set_graph_replay), a call
+// A search is four launches and four event operations; enqueueing them one by one costs the host tens of
+// microseconds, a large part of a single query's latency.  With replay enabled (piperag_set_graph_replay), a call
 // that repeats an earlier one (same buffers, same sizes: a serving loop that refills its query buffer) is
 // captured into a graph the second time it is seen and replayed with one launch from then on (measured: 8 us
 // less per waited-for call, but 10 us more per call in a back-to-back loop, hence opt-in).  The graph holds
@@ -1793,6 +1732,9 @@ int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_
 }
 
 #ifdef PIPERAG_TRACE
+__attribute__((visibility("default"))) int piperag_debug_sel_trace(unsigned long long *out_host, int nwg) {
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(d_sel_trace), sizeof(unsigned long long) * 8 * nwg) == hipSuccess ? 0 : -1;
+}
 __attribute__((visibility("default"))) int piperag_debug_trace(unsigned long long *out_host, int max_wg) {
     const int n = g_trace_n < max_wg ? g_trace_n : max_wg;
     if (hipMemcpy(out_host, g_trace_buf, sizeof(unsigned long long) * 8 * n, hipMemcpyDeviceToHost) != hipSuccess) return -1;
