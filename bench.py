@@ -394,7 +394,9 @@ def main():
         "build_s": {k: round(info[k], 2) for k in ("train_s", "encode_s", "finalize_s")},
         "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(cfg.name),
-                     "bytes_per_launch": scanned_bytes, "avg_launch_ms": scan_ms},
+                     "bytes_per_launch": scanned_bytes, "avg_launch_ms": scan_ms,
+                     "note": "the kernel's whole launch: table staging, scan, k-selection, merge of the query's partial "
+                             "results, id gather and sort (there is no separate priming or merge kernel)"},
     }
 
     if args.calibrate_copy:
