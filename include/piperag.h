@@ -225,10 +225,11 @@ int piperag_stage_times(const piperag_index *index, float *out_ms_host /* [PIPER
 int piperag_set_graph_replay(piperag_index *index, int enable);
 
 /* How the scan reads the code blocks (Section 3.2, S3: the vector-scan term of the latency).  mode < 0
- * (default): by the size of the index - indexes with 4 GiB of codes or more are read with non-temporal
- * loads, because nothing a search reads is still cached when it is needed again and streaming the codes
- * past the caches is then faster; smaller indexes are read with ordinary loads so that lists probed by
- * several queries of a batch, or again by the next call, are found in the caches.  mode = 0: always
+ * (default): by the shape of the index - indexes with 4 GiB of codes or more whose lists average less than
+ * 4 MiB of codes are read with non-temporal loads, because nothing a search reads is still cached when it
+ * is needed again and streaming the codes past the caches is then faster (measured); other indexes are
+ * read with ordinary loads so that lists probed by several queries of a batch, or again by the next call,
+ * are found in the caches.  mode = 0: always
  * ordinary loads; mode > 0: always non-temporal loads.  Results do not depend on the mode.  Cached graphs
  * of repeated calls are dropped. */
 int piperag_set_scan_streaming(piperag_index *index, int mode);

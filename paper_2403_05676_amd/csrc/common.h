@@ -27,7 +27,8 @@ constexpr int kCoarseSplitMaxLists = 8192;   // ... for indexes of up to this ma
 constexpr int kCtrStride = 32;         // chunk counters sit 128 bytes apart
 constexpr int kCtrPerQuery = 16;       // at most this many chunk counters share out one query's blocks
 constexpr int kMinBlocksPerWG = 16;    // one round of the scan loop: 4 waves x 4 blocks
-constexpr size_t kStreamingCodeBytes = (size_t)4 << 30;   // indexes with at least this many code bytes are scanned with non-temporal loads
+constexpr size_t kStreamingCodeBytes = (size_t)4 << 30;   // indexes with at least this many code bytes are scanned with non-temporal loads ...
+constexpr size_t kStreamingListBytes = (size_t)4 << 20;   // ... unless their lists average this many code bytes or more
 constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);

@@ -1157,9 +1157,9 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // them, looks up the ids and writes the results (see the end of the kernel).  RES: residual index (see the
 // comment in process below).
 // STREAM: the code blocks are read with non-temporal loads.  That is faster when the codes come from HBM anyway
-// (measured on 16 GiB of codes: 5.7 instead of 5.5 TB/s) and slower when the batch's lists would otherwise be
-// found again in the caches by the next query or the next call (1 GiB of codes, 64 queries: 5.5 instead of
-// 6.3 TB/s), so the host chooses it by the size of the index.
+// (measured on 16 GiB of codes: 5.7 instead of 5.5 TB/s; on 64 GiB: 6.2 instead of 5.8) and slower when the
+// batch's lists would otherwise be found again in the caches by the next query or the next call (1 GiB of codes,
+// 64 queries: 5.5 instead of 6.3 TB/s), so the host chooses it by the shape of the index.
 // ------------------------------------------------------------------------------------------------
 template <int C, int NSETS, bool RES, bool STREAM>
 __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
@@ -1625,8 +1625,13 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
     const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
     PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
-    // indexes far larger than the last-level cache are streamed: nothing read now is still cached when it is needed again
-    const bool streaming = ix->streaming < 0 ? (size_t)ix->nblocks * kBlockVecs * ix->Mp >= kStreamingCodeBytes : ix->streaming > 0;
+    // Indexes far larger than the last-level cache are streamed: nothing read now is still cached when it is needed
+    // again.  Measured with 64-byte codes: +4 % to +6 % at 16 GiB and 64 GiB of codes in 65,536 lists (0.25 and 1 MiB
+    // per list on average) for 1 to 256 queries; but -4 % for batches of 8 and 64 queries on 192 GB of codes in 16,384
+    // lists (11.7 MiB per list), hence the second condition.
+    const size_t code_bytes = (size_t)ix->nblocks * kBlockVecs * ix->Mp;
+    const bool streaming = ix->streaming < 0 ? code_bytes >= kStreamingCodeBytes && code_bytes / ix->p.nlist < kStreamingListBytes
+                                             : ix->streaming > 0;
     PR_DISPATCH_C(launch_scan, a, streaming, G, lds, st)
     if (rc != PIPERAG_OK) return rc;
     if (tm) { PR_CHECK_HIP(hipEventRecord(ix->ev[4], st)); ix->ev_valid = true; }

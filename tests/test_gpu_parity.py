@@ -436,6 +436,16 @@ def test_scan_with_streaming_loads_gives_the_same_results(cfg0):
     ix.set_scan_streaming(-1)
 
 
+def test_batches_larger_than_the_number_of_scan_workgroups():
+    # 700 queries share 2048 scan workgroups; 2500 queries get one workgroup each
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(20000, 32, 64, 8, seed=99, nq=2500, iters=2)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=2500, max_nprobe=8, max_k=16)
+    run_search_parity(pkg, ix, oidx, q[:700], 4, 10)
+    run_search_parity(pkg, ix, oidx, q, 3, 5)
+
+
 def long_row_problem(adversarial):
     """40,000 centres (a row of coarse distances too long for the selection's LDS staging) and few vectors.
     adversarial: the centres close to the queries all sit at list numbers i with i mod 2048 < 512, so that
