@@ -1056,6 +1056,12 @@ __device__ __forceinline__ void publish_keys() {
     __syncthreads();
 }
 
+#ifdef PIPERAG_TRACE
+__device__ unsigned long long d_fin_trace[4096 * 8];
+#define FIN_MARK(j) do { if (threadIdx.x == 0) d_fin_trace[blockIdx.x * 8 + (j)] = wall_clock64(); } while (0)
+#else
+#define FIN_MARK(j) do {} while (0)
+#endif
 // Selection from a key list by one workgroup: the k smallest of the keys in list[0..n) (global memory, written by
 // this and other workgroups, all different).  Up to `room` keys are gathered into s_keys first (those within
 // `bound`, which at least k keys are if k exist) and selected there; a longer list is selected in place, one
@@ -1071,6 +1077,7 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
                                  int64_t *__restrict__ out_i, uint64_t *__restrict__ dst, int KW) {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
+    FIN_MARK(0);
     if (FINAL)
         for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
     if (tid == 0) *s_count = 0;
@@ -1083,16 +1090,24 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
 #pragma unroll
             for (int j = 0; j < 8; ++j) key[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound) s_keys[atomicAdd(s_count, 1u)] = key[j];
+            for (int j = 0; j < 8; ++j) {                        // one counter update per wave and round
+                const bool pass = key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound;
+                const uint64_t mask = __ballot(pass);
+                unsigned at = 0;
+                if ((tid & 63) == 0 && mask != 0) at = atomicAdd(s_count, (unsigned)__popcll(mask));
+                at = __builtin_amdgcn_readfirstlane(at);
+                if (pass) s_keys[at + (unsigned)__popcll(mask & ((1ull << (tid & 63)) - 1ull))] = key[j];
+            }
         }
         __syncthreads();
         found = (int)*s_count;
         __syncthreads();
     }
     auto key_at = [&](int i) { return in_lds ? s_keys[i] : load_key(list + i); };
+    FIN_MARK(1);
     uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
     if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state);
+    FIN_MARK(2);
     if (tid == 0) *s_count = 0;
     __syncthreads();
     for (int i = tid; i < found; i += nt) {
@@ -1104,18 +1119,54 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         }
     }
     __syncthreads();
+    FIN_MARK(3);
     const int cnt = (int)*s_count;
     if (!FINAL) {
         for (int i = cnt + tid; i < KW; i += nt) store_key(dst + i, kSentinel);
         return;
     }
-    // bitonic sort of (distance bits, id) pairs; up to 128 of them are sorted by one wavefront, whose lanes run
-    // in lockstep and need no workgroup barriers between the steps
-    const bool one_wave = k2 <= 2 * kWave;
+    // Order by (distance, id).  Up to one result per thread: every thread counts the results that sort before its
+    // own (the pairs are all different, so the counts are the places) and writes it there - a short loop over
+    // LDS reads that all lanes make at the same address (measured 4 us for 100 results; a bitonic network, over
+    // lane exchanges or in LDS, took 7 us).  More results than threads: bitonic network in LDS.
+    if (k2 <= nt) {                                              // uniform
+        if (tid < cnt) {
+            const uint32_t d_mine = s_d[tid];
+            const int64_t id_mine = s_id[tid];
+            int place = 0;
+            bool tie = false;
+            // over all k2 slots (unused ones hold the largest distance bits and count for nobody), 16 reads at a
+            // time so that they overlap, and without branches: ids are looked at afterwards, and only by a thread
+            // whose distance occurs a second time
+            for (int j = 0; j < k2; j += 16) {                   // k2 is a power of two; below 16 the tail loop runs
+                if (j + 16 > k2) break;
+                uint32_t dj[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) dj[u] = s_d[j + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    place += dj[u] < d_mine ? 1 : 0;
+                    tie |= dj[u] == d_mine && j + u != tid;
+                }
+            }
+            for (int j = k2 < 16 ? 0 : k2; j < k2; ++j) {
+                place += s_d[j] < d_mine ? 1 : 0;
+                tie |= s_d[j] == d_mine && j != tid;
+            }
+            if (tie)
+                for (int j = 0; j < cnt; ++j) place += (s_d[j] == d_mine && s_id[j] < id_mine) ? 1 : 0;
+            out_d[place] = __uint_as_float(d_mine);
+            out_i[place] = id_mine;
+        }
+        for (int i = cnt + tid; i < k; i += nt) { out_d[i] = __builtin_inff(); out_i[i] = -1; }
+        FIN_MARK(4);
+        FIN_MARK(5);
+        return;
+    }
     for (int size = 2; size <= k2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (one_wave) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); else __syncthreads();
-            for (int i = tid; i < (k2 >> 1) && (!one_wave || tid < kWave); i += nt) {
+            __syncthreads();
+            for (int i = tid; i < (k2 >> 1); i += nt) {
                 const int lo = 2 * i - (i & (stride - 1));
                 const int hi = lo + stride;
                 const bool up = (lo & size) == 0;
@@ -1127,10 +1178,12 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         }
     }
     __syncthreads();
+    FIN_MARK(4);
     for (int i = tid; i < k; i += nt) {
         out_d[i] = i < cnt ? __uint_as_float(s_d[i]) : __builtin_inff();
         out_i[i] = i < cnt ? s_id[i] : -1;
     }
+    FIN_MARK(5);
 }
 
 // Room for keys when the table and candidate areas of the scan kernel's LDS are reused for the final selection
@@ -1737,6 +1790,9 @@ int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_
 }
 
 #ifdef PIPERAG_TRACE
+__attribute__((visibility("default"))) int piperag_debug_fin_trace(unsigned long long *out_host, int nwg) {
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(d_fin_trace), sizeof(unsigned long long) * 8 * nwg) == hipSuccess ? 0 : -1;
+}
 __attribute__((visibility("default"))) int piperag_debug_sel_trace(unsigned long long *out_host, int nwg) {
     return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(d_sel_trace), sizeof(unsigned long long) * 8 * nwg) == hipSuccess ? 0 : -1;
 }
