@@ -207,7 +207,7 @@ int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, i
  * When enabled, every search call records HIP events around its stages on its stream;
  * piperag_stage_times synchronises on them and writes the most recent call's milliseconds:
  * [0] coarse quantiser, [1] top-nprobe selection, scan plan and work sharing, [2] wait for the lookup
- * tables (built on a side stream from the start of the call), [3] list scan with k-selection, merge of
+ * tables (built on a side stream beside the selection), [3] list scan with k-selection, merge of
  * the query's partial results and id gather (one kernel).  Stages [0]+[1] are the index-scan term,
  * [2]+[3] the vector-scan term. */
 #define PIPERAG_NSTAGES 4

@@ -1620,13 +1620,14 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     const int pstride = ix->p.max_nprobe;
     const bool tm = ix->timing;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
-    // fork: the tables need only the queries and are built beside the coarse quantiser and the selection
+    // The coarse quantiser is enqueued first (the whole call waits for it); then the fork: the tables need only the
+    // queries and are built on the side stream beside the selection.
+    if (!probes && (rc = launch_coarse(ix, q, nq, st)) != PIPERAG_OK) return rc;
+    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
     PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));
     PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
     launch_lut_build(ix, q, nq, ix->side);
     PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
-    if (!probes && (rc = launch_coarse(ix, q, nq, st)) != PIPERAG_OK) return rc;
-    if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
     static const int wgs_override = [] {                    // tuning override, read once
         const char *e = getenv("PIPERAG_SCAN_WGS");
         const int v = e ? atoi(e) : 0;
