@@ -409,10 +409,12 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 }
 
 // Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
-// of 512 threads per query: selection of the nprobe-th smallest key (distance bits << 32 | list; distances
+// of NT threads per query (512 for rows of up to 8,192 distances, 1024 for longer ones): selection of the nprobe-th smallest key (distance bits << 32 | list; distances
 // are >= 0 so their bit patterns order like the values), compaction, bitonic sort.  The row of D is staged in
 // LDS (dynamic, nlist * 4 bytes) for the rounds of the selection when it fits (stage_row != 0).
-constexpr int kSelThreads = 512;
+constexpr int kSelThreads = 512;            // rows of up to kSelSmallRow distances
+constexpr int kSelThreadsLong = 1024;       // longer rows: the sweeps over the row are what the selection costs there
+constexpr int kSelSmallRow = 8192;          // (measured: 1024 threads are 8 us faster at 16,384 lists and 4 us slower at 4,096)
 #ifdef PIPERAG_TRACE
 __device__ unsigned long long d_sel_trace[4096 * 8];
 #define SEL_MARK(j) do { if (threadIdx.x == 0) d_sel_trace[blockIdx.x * 8 + (j)] = wall_clock64(); } while (0)
@@ -420,11 +422,12 @@ __device__ unsigned long long d_sel_trace[4096 * 8];
 #define SEL_MARK(j) do {} while (0)
 #endif
 constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
-constexpr int kSelGroups = 4 * kSelThreads; // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
+constexpr int kSelGroups = 4 * kSelThreadsLong;   // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
 constexpr int kSelCand = 4096;              // ... and room for the keys collected under it
 static_assert(kSelGroups >= kMaxNprobe, "the bound is the nprobe-th smallest group minimum");
 
-__global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__restrict__ D, int nparts,
+template <int NT>
+__global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D, int nparts,
                                                                     const float *__restrict__ q, int d,
                                                                     const float *__restrict__ cn, int nlist, int nprobe,
                                                                     int stage_row, int32_t *__restrict__ probe,
@@ -439,13 +442,13 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
     __shared__ unsigned s_count, s_ncand;
-    __shared__ float s_qpart[kSelThreads / kWave];
+    __shared__ float s_qpart[NT / kWave];
     const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
     SEL_MARK(0);
     float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
     const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
-    for (int i = tid; i < np2; i += kSelThreads) s_keys[i] = kSentinel;
+    for (int i = tid; i < np2; i += NT) s_keys[i] = kSentinel;
     if (tid == 0) s_count = 0;
     // Inner product with centre i from the parts, summed in order.  With several parts all kCoarseMaxParts loads
     // are made whatever their number (a missing part re-reads the last one and counts as +0), so that the loads
@@ -469,7 +472,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     if (stage_row && nparts > 0) {
 #pragma unroll
         for (int u = 0; u < US; ++u) {
-            const int i = tid + u * kSelThreads;
+            const int i = tid + u * NT;
             pd[u] = i < nlist ? dot_of(i) : 0.f;
             pc[u] = i < nlist ? cn[i] : 0.f;
         }
@@ -477,36 +480,36 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     float qn = 0.f;
     if (nparts > 0 || plan.pcst) {                           // D holds partial inner products, or a residual index: the query's norm
         float part = 0.f;
-        for (int t = tid; t < d; t += kSelThreads) { const float v = q[(size_t)qi * d + t]; part += v * v; }
+        for (int t = tid; t < d; t += NT) { const float v = q[(size_t)qi * d + t]; part += v * v; }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
         if ((tid & 63) == 0) s_qpart[tid >> 6] = part;
         __syncthreads();
 #pragma unroll
-        for (int w = 0; w < kSelThreads / kWave; ++w) qn += s_qpart[w];    // the same order in every thread
+        for (int w = 0; w < NT / kWave; ++w) qn += s_qpart[w];    // the same order in every thread
     }
     auto finish = [&](float dot, float cnorm) -> float { return fmaxf(0.f, qn + cnorm - 2.f * dot); };
     auto dist_of = [&](int i) -> float { return finish(dot_of(i), cn[i]); };
     if (stage_row) {
         uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
-        for (int i0 = tid; i0 < nlist; i0 += US * kSelThreads) {
+        for (int i0 = tid; i0 < nlist; i0 += US * NT) {
             uint32_t v[US];
             if (nparts > 0 && i0 != tid) {                   // later sweeps (uniform)
 #pragma unroll
                 for (int u = 0; u < US; ++u) {
-                    const int i = i0 + u * kSelThreads;
+                    const int i = i0 + u * NT;
                     pd[u] = i < nlist ? dot_of(i) : 0.f;
                     pc[u] = i < nlist ? cn[i] : 0.f;
                 }
             }
 #pragma unroll
             for (int u = 0; u < US; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 v[u] = nparts > 0 ? __float_as_uint(finish(pd[u], pc[u])) : (i < nlist ? row[i] : 0u);
             }
 #pragma unroll
             for (int u = 0; u < US; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 if (i < nlist) s_row[i] = v[u];
             }
         }
@@ -527,18 +530,19 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
     if (!stage_row) {
         uint64_t *s_gmin = reinterpret_cast<uint64_t *>(sel_smem);
         constexpr int U = 16;
-        static_assert(kSelGroups == 4 * kSelThreads && U % 4 == 0, "a thread owns four groups: tid + kSelThreads * (0..3)");
+        static_assert(U % 4 == 0, "a thread owns four groups: tid + NT * (0..3)");
+        constexpr int kGroups = 4 * NT;
         uint64_t gm[4] = {kSentinel, kSentinel, kSentinel, kSentinel};
-        for (int i0 = tid; i0 < nlist; i0 += U * kSelThreads) {
+        for (int i0 = tid; i0 < nlist; i0 += U * NT) {
             float v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 v[u] = i < nlist ? (nparts > 0 ? dist_of(i) : grow[i]) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 if (i < nlist) {
                     if (nparts > 0) grow[i] = v[u];         // the distances replace part 0 in place (re-read by this thread only)
                     const uint64_t key = ((uint64_t)__float_as_uint(v[u]) << 32) | (uint32_t)i;
@@ -547,21 +551,21 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
             }
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) s_gmin[g * kSelThreads + tid] = gm[g];
+        for (int g = 0; g < 4; ++g) s_gmin[g * NT + tid] = gm[g];
         if (tid == 0) s_ncand = 0;
         __syncthreads();
         auto gmin_at = [&](int i) { return s_gmin[i]; };
-        const uint64_t T0 = block_select_kth(gmin_at, kSelGroups, nprobe, s_hist, s_state);
-        for (int i0 = tid; i0 < nlist; i0 += U * kSelThreads) {
+        const uint64_t T0 = block_select_kth(gmin_at, kGroups, nprobe, s_hist, s_state);
+        for (int i0 = tid; i0 < nlist; i0 += U * NT) {
             uint32_t v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 v[u] = i < nlist ? row[i] : 0xFFFFFFFFu;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * kSelThreads;
+                const int i = i0 + u * NT;
                 const uint64_t key = ((uint64_t)v[u] << 32) | (uint32_t)i;
                 if (i < nlist && key <= T0) {
                     const unsigned slot = atomicAdd(&s_ncand, 1u);
@@ -576,7 +580,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         const int ncand = (int)s_ncand;
         auto cand_at = [&](int i) { return s_cand[i]; };
         const uint64_t T = block_select_kth(cand_at, ncand, nprobe, s_hist, s_state);
-        for (int i = tid; i < ncand; i += kSelThreads) {
+        for (int i = tid; i < ncand; i += NT) {
             const uint64_t key = s_cand[i];
             if (key <= T) {                                // exactly nprobe keys qualify (keys are distinct)
                 const unsigned slot = atomicAdd(&s_count, 1u);
@@ -585,7 +589,7 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         }
     } else {
         const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
-        for (int i = tid; i < nlist; i += kSelThreads) {
+        for (int i = tid; i < nlist; i += NT) {
             const uint64_t key = key_at(i);
             if (key <= T) {
                 const unsigned slot = atomicAdd(&s_count, 1u);
@@ -602,14 +606,14 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(float *__res
         block_bitonic_sort_u64(s_keys, np2);
     }
     SEL_MARK(3);
-    for (int i = tid; i < nprobe; i += kSelThreads) {
+    for (int i = tid; i < nprobe; i += NT) {
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
     }
     auto probe_at = [&](int i) { return (int32_t)(s_keys[i] & 0xFFFFFFFFu); };
     const PlanOut mine = plan_of_query(plan, qi, probe_stride);
     if (mine.pcst)                                           // |q - c|^2 - |q|^2 = |c|^2 - 2 <q, c>
-        for (int i = tid; i < nprobe; i += kSelThreads) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
+        for (int i = tid; i < nprobe; i += NT) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
     plan_query(probe_at, nprobe, list_blk, list_len, mine);
     SEL_MARK(4);
     // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
@@ -1541,15 +1545,23 @@ int launch_select(const piperag_index *ix, const float *q, int nq, int nprobe, i
     const int nlist = ix->p.nlist;
     const int stage = nlist <= kSelMaxLdsRow;
     const size_t lds = stage ? sizeof(float) * (size_t)nlist : sizeof(uint64_t) * (kSelGroups + kSelCand);
-    static size_t configured = 0;
-    if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel),
+    static bool configured = false;
+    if (!configured) {
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel<kSelThreads>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kSelMaxLdsRow)));
-        configured = sizeof(float) * kSelMaxLdsRow;
+        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel<kSelThreadsLong>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kSelMaxLdsRow)));
+        configured = true;
     }
-    hipLaunchKernelGGL(select_probes_kernel, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, coarse_parts(ix, q, nq), q, ix->p.d,
-                       ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk, ix->list_len,
-                       plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target, max_wg, share_bufs(ix));
+    if (nlist <= kSelSmallRow)
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreads>, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, coarse_parts(ix, q, nq),
+                           q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk,
+                           ix->list_len, plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target, max_wg, share_bufs(ix));
+    else
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreadsLong>, dim3(nq), dim3(kSelThreadsLong), lds, st, ix->ws_D,
+                           coarse_parts(ix, q, nq), q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d,
+                           ix->p.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target,
+                           max_wg, share_bufs(ix));
     return PIPERAG_OK;
 }
 

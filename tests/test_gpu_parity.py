@@ -448,13 +448,13 @@ def test_batches_larger_than_the_number_of_scan_workgroups():
 
 def long_row_problem(adversarial):
     """40,000 centres (a row of coarse distances too long for the selection's LDS staging) and few vectors.
-    adversarial: the centres close to the queries all sit at list numbers i with i mod 2048 < 512, so that
+    adversarial: the centres close to the queries all sit at list numbers i with i mod 4096 < 512, so that
     bounding the row by minima over interleaved groups of lists keeps far too many of them."""
     rng = np.random.default_rng(77 + adversarial)
     nlist, d, M, N = 40000, 16, 4, 3000
     coarse = rng.normal(0.0, 1.0, (nlist, d)).astype(np.float32)
     if adversarial:
-        far = (np.arange(nlist) % 2048) >= 512
+        far = (np.arange(nlist) % 4096) >= 512
         coarse[far] += np.float32(20.0)
     x = (coarse[rng.integers(0, nlist, N)] + rng.normal(0.0, 0.1, (N, d))).astype(np.float32)
     q = rng.normal(0.0, 1.0 if not adversarial else 0.3, (6, d)).astype(np.float32)
