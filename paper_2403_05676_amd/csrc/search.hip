@@ -1225,6 +1225,10 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     const int k = a.k, KW = a.KW, cap = a.cap;
     const ScanLds s = carve_lds(smem, MP, cap, a.nprobe);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (Workgroups are dealt to the 8 XCDs in turn by their launch number, so the workgroups of a query, consecutive in
+    // the plan, sit on different XCDs.  Taking them from one XCD instead, so that the query's table is fetched into
+    // one L2 rather than eight, was measured: 6 % faster at 32 queries, 3 % slower at 64 queries x 256 probes, equal
+    // elsewhere - not kept.)
     const int wg = blockIdx.x;
     const int4 desc = a.desc[wg];                            // (query, number among its workgroups, their count, counters)
     if (desc.x < 0) return;                                  // spare workgroup (uniform exit)

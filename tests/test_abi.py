@@ -48,6 +48,8 @@ def test_error_paths_without_gpu():
     out = ctypes.c_void_p()
     assert lib.piperag_ivf_load(b"/nonexistent/file", ctypes.byref(ctypes.create_string_buffer(64)), ctypes.byref(out)) == -4
     assert lib.piperag_ivf_ntotal(None) == -1
+    for setter in (lib.piperag_set_scan_streaming, lib.piperag_set_graph_replay, lib.piperag_set_stage_timing):
+        assert setter(None, 1) == -1
 
 
 def test_product_package_does_not_import_the_oracle():
