@@ -446,6 +446,37 @@ def test_batches_larger_than_the_number_of_scan_workgroups():
     run_search_parity(pkg, ix, oidx, q, 3, 5)
 
 
+def test_seeded_random_shapes_match_the_oracle():
+    # a seeded walk over code lengths, sub-vector lengths, list counts, probe counts, k and batch sizes, raw and
+    # residual, with ordinary and streaming loads
+    pkg = P()
+    rng = np.random.default_rng(7)
+    done = 0
+    while done < 20:
+        M = int(rng.choice([1, 2, 4, 8, 16, 24, 32, 48, 64, 96, 128]))
+        d = M * int(rng.choice([1, 2, 3, 4, 6, 8, 12]))
+        N = int(rng.integers(300, 40000))
+        nlist = int(rng.integers(1, min(400, N // 2)))
+        nprobe = int(rng.integers(1, nlist + 1))
+        k = int(rng.choice([1, 2, 5, 10, 64, 100, 128, 129, 300, 1024]))
+        nq = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100]))
+        residual = bool(rng.integers(0, 2))
+        if d < 2 or d > 1024:
+            continue
+        if residual:
+            cfg, x, q, coarse, pq = make_residual_problem(N, d, nlist, M, seed=1000 + done, nq=nq, iters=1)
+            oidx = oracle.make_index_residual(x, coarse, pq)
+        else:
+            cfg, x, q, coarse, pq = make_problem(N, d, nlist, M, seed=1000 + done, nq=nq, iters=1)
+            oidx = oracle.make_index(x, coarse, pq)
+        ix = gpu_index_from_oracle(pkg, oidx, max_nq=nq, max_nprobe=nprobe, max_k=k)
+        run_search_parity(pkg, ix, oidx, q, nprobe, k)
+        ix.set_scan_streaming(1)
+        run_search_parity(pkg, ix, oidx, q[:1], nprobe, k)
+        ix.ivf_free()
+        done += 1
+
+
 def long_row_problem(adversarial):
     """40,000 centres (a row of coarse distances too long for the selection's LDS staging) and few vectors.
     adversarial: the centres close to the queries all sit at list numbers i with i mod 4096 < 512, so that
