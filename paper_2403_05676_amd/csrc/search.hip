@@ -340,9 +340,10 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
     const bool act = tid < 256;
     if (tid == 0) { s_total = 0; s_carry = 0; }
     __syncthreads();
-    long long mine = 0;
+    const long long first_tb = act && tid < nq ? blocks_of(tid) : 0;   // kept for the second use below
+    long long mine = first_tb;
     if (act)
-        for (int q = tid; q < nq; q += 256) mine += blocks_of(q);
+        for (int q = tid + 256; q < nq; q += 256) mine += blocks_of(q);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
     if (act && (tid & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&s_total), (unsigned long long)mine);
@@ -354,7 +355,7 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
         const int q = q0 + tid;
         int32_t sq = 0;
         if (act && q < nq) {
-            const long long tb = blocks_of(q);
+            const long long tb = q0 == 0 ? first_tb : blocks_of(q);
             sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
         }
         int32_t incl = sq;                                 // inclusive scan: within the wave, then over the four waves
@@ -1129,38 +1130,48 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         for (int i = cnt + tid; i < KW; i += nt) store_key(dst + i, kSentinel);
         return;
     }
-    // Order by (distance, id).  Up to one result per thread: every thread counts the results that sort before its
-    // own (the pairs are all different, so the counts are the places) and writes it there - a short loop over
-    // LDS reads that all lanes make at the same address (measured 4 us for 100 results; a bitonic network, over
-    // lane exchanges or in LDS, took 7 us).  More results than threads: bitonic network in LDS.
+    // Order by (distance, id).  Up to one result per thread: the results that sort before a result are counted (the
+    // pairs are all different, so the counts are the places) and it is written there - short loops over LDS reads
+    // that all lanes make at the same address (a bitonic network, over lane exchanges or in LDS, took 7 us for
+    // 100 results).  More results than threads: bitonic network in LDS.
     if (k2 <= nt) {                                              // uniform
-        if (tid < cnt) {
-            const uint32_t d_mine = s_d[tid];
-            const int64_t id_mine = s_id[tid];
-            int place = 0;
+        // nt / k2 threads share the count of one result (each takes a part of the slots, 16 reads at a time so that
+        // they overlap; unused slots hold the largest distance bits and count for nobody) and add their parts up
+        // in LDS; ids are looked at only by a thread that sees the result's distance a second time
+        const int parts = min(nt / k2, k2), span = k2 / parts;   // powers of two; span >= 1
+        const int mine = tid & (k2 - 1), part = tid / k2, j0 = part * span;
+        if (tid < k2) s_hist[tid] = 0;
+        __syncthreads();
+        if (mine < cnt && part < parts) {
+            const uint32_t d_mine = s_d[mine];
+            int before = 0;
             bool tie = false;
-            // over all k2 slots (unused ones hold the largest distance bits and count for nobody), 16 reads at a
-            // time so that they overlap, and without branches: ids are looked at afterwards, and only by a thread
-            // whose distance occurs a second time
-            for (int j = 0; j < k2; j += 16) {                   // k2 is a power of two; below 16 the tail loop runs
-                if (j + 16 > k2) break;
+            int j = j0;
+            for (; j + 16 <= j0 + span; j += 16) {
                 uint32_t dj[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) dj[u] = s_d[j + u];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    place += dj[u] < d_mine ? 1 : 0;
-                    tie |= dj[u] == d_mine && j + u != tid;
+                    before += dj[u] < d_mine ? 1 : 0;
+                    tie |= dj[u] == d_mine && j + u != mine;
                 }
             }
-            for (int j = k2 < 16 ? 0 : k2; j < k2; ++j) {
-                place += s_d[j] < d_mine ? 1 : 0;
-                tie |= s_d[j] == d_mine && j != tid;
+            for (; j < j0 + span; ++j) {
+                before += s_d[j] < d_mine ? 1 : 0;
+                tie |= s_d[j] == d_mine && j != mine;
             }
-            if (tie)
-                for (int j = 0; j < cnt; ++j) place += (s_d[j] == d_mine && s_id[j] < id_mine) ? 1 : 0;
-            out_d[place] = __uint_as_float(d_mine);
-            out_i[place] = id_mine;
+            if (tie) {
+                const int64_t id_mine = s_id[mine];
+                for (int jj = j0; jj < j0 + span; ++jj) before += (s_d[jj] == d_mine && s_id[jj] < id_mine) ? 1 : 0;
+            }
+            if (before) atomicAdd(&s_hist[mine], (unsigned)before);
+        }
+        __syncthreads();
+        if (tid < cnt) {
+            const int place = (int)s_hist[tid];
+            out_d[place] = __uint_as_float(s_d[tid]);
+            out_i[place] = s_id[tid];
         }
         for (int i = cnt + tid; i < k; i += nt) { out_d[i] = __builtin_inff(); out_i[i] = -1; }
         FIN_MARK(4);
