@@ -68,6 +68,31 @@ def assign(x: np.ndarray, c: np.ndarray, return_dist: bool = False):
     return (idx, dist) if return_dist else idx
 
 
+def assign_among(x: np.ndarray, c: np.ndarray, cand: np.ndarray, return_dist: bool = False):
+    """Nearest centre of each row among the centres listed for it (cand: int32 [n, T], negative entries skipped)."""
+    x = _f32(x); c = _f32(c)
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    n, d = x.shape
+    assert cand.ndim == 2 and cand.shape[0] == n and cand.max(initial=-1) < c.shape[0] and np.all((cand >= 0).any(axis=1))
+    idx = np.empty(n, dtype=np.int32)
+    dist = np.empty(n, dtype=np.float32) if return_dist else None
+    _load().oracle_assign_among(_p(x, C.c_float), C.c_int64(n), C.c_int(d), C.c_int64(d), _p(c, C.c_float),
+                                _p(cand, C.c_int32), C.c_int(cand.shape[1]), _p(idx, C.c_int32), _p(dist, C.c_float))
+    return (idx, dist) if return_dist else idx
+
+
+def encode_codes(x: np.ndarray, pq: np.ndarray) -> np.ndarray:
+    """PQ codes uint8 [n, M] of each row of x (the code part of `encode`, without the list assignment)."""
+    x = _f32(x); pq = _f32(pq)
+    n, d = x.shape
+    M, ksub, dsub = pq.shape
+    assert M * dsub == d and ksub <= 256
+    codes = np.empty((n, M), dtype=np.uint8)
+    _load().oracle_encode(_p(x, C.c_float), C.c_int64(n), C.c_int(d), None, C.c_int64(0), _p(pq, C.c_float), C.c_int(M),
+                          C.c_int(ksub), None, _p(codes, C.c_uint8))
+    return codes
+
+
 def kmeans(x: np.ndarray, K: int, init_rows: np.ndarray, iters: int = 10, return_inertia: bool = False):
     """Fixed-iteration Lloyd k-means started from rows `init_rows` of x.  x may be a strided view
     (rows contiguous in their last dimension)."""

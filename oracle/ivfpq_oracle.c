@@ -90,6 +90,37 @@ void oracle_assign(const float *x, int64_t n, int d, int64_t ldx, const float *c
     free(ct);
 }
 
+/* Nearest centre among a given subset of the centres (the same definition as
+ * oracle_assign, restricted): cand[i*T + t], t < T, are centre numbers for row
+ * i; negative entries are skipped; a row needs at least one valid entry.
+ * out_idx[i] = the listed centre with the smallest fp32(dist(x_i, c_j)), the
+ * lowest number on equal values (whatever the order of the entries).  With
+ * every centre listed this is oracle_assign.  It serves tests that have first
+ * ruled out, by other means and with a wide margin, the centres that are far. */
+void oracle_assign_among(const float *x, int64_t n, int d, int64_t ldx, const float *c, const int32_t *cand, int T,
+                         int32_t *out_idx, float *out_dist) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float *xi = x + i * ldx;
+        float best = 0.f;
+        int32_t arg = -1;
+        for (int t = 0; t < T; ++t) {
+            const int32_t j = cand[i * T + t];
+            if (j < 0) continue;
+            const float *cj = c + (int64_t)j * d;
+            double acc = 0.0;
+            for (int u = 0; u < d; ++u) {
+                const double diff = (double)xi[u] - (double)cj[u];
+                acc += diff * diff;
+            }
+            const float v = (float)acc;
+            if (arg < 0 || v < best || (v == best && j < arg)) { best = v; arg = j; }
+        }
+        out_idx[i] = arg;
+        if (out_dist) out_dist[i] = best;
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* Lloyd k-means with a fixed iteration count (reading: the paper does not
  * say how the IVF lists or PQ codebooks are trained; Section 3.2 S3 only

@@ -104,6 +104,32 @@ def test_assign_ties_take_lowest_index():
     assert probes[0].tolist() == [0, 1, 2, 3]
 
 
+def test_assign_among_a_subset_of_the_centres():
+    # pinned by SciPy's distances restricted to the listed centres; entries in any order, negative ones skipped,
+    # equal distances to the lower centre number; with every centre listed it is the full assignment
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((200, 24)).astype(np.float32)
+    c = rng.standard_normal((50, 24)).astype(np.float32)
+    full = cdist(x.astype(np.float64), c.astype(np.float64), "sqeuclidean")
+    cand = np.stack([rng.permutation(50)[:6] for _ in range(200)]).astype(np.int32)
+    cand[::3, 2] = -1
+    idx, dist = oracle.assign_among(x, c, cand, return_dist=True)
+    for i in range(200):
+        valid = cand[i][cand[i] >= 0]
+        want = valid[np.argmin(full[i, valid])]
+        assert idx[i] == want
+        assert abs(dist[i] - full[i, want]) <= 1e-6 * full[i, want]
+    everything = np.stack([rng.permutation(50) for _ in range(200)]).astype(np.int32)
+    assert np.array_equal(oracle.assign_among(x, c, everything), oracle.assign(x, c))
+    # ties: centres 0 and 2 coincide; listed as (2, 0) the answer is still 0
+    c2 = np.array([[1, 0], [0, 1], [1, 0], [-1, 0]], dtype=np.float32)
+    x2 = np.array([[1, 0], [0.5, 0.5]], dtype=np.float32)
+    assert oracle.assign_among(x2, c2, np.array([[2, 0], [2, 1]], dtype=np.int32)).tolist() == [0, 1]
+    # the codes-only entry equals the code part of the full encoding
+    pq = rng.standard_normal((4, 256, 6)).astype(np.float32)
+    assert np.array_equal(oracle.encode_codes(x, pq), oracle.encode(x, c, pq)[1])
+
+
 def test_adc_equals_distance_to_decoded_vector():
     cfg, x, q, coarse, pq = small_problem()
     idx = oracle.make_index(x, coarse, pq)
