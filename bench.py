@@ -22,6 +22,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# The workload a plain `python bench.py` measures: a configuration the roofline target is stated on (the scan of
+# the two large indexes), whose whole run - building 268 M vectors included - stays well inside ten minutes.
+DEFAULT_WORKLOAD = "cfg3"
+PARITY_QUERIES = 32            # queries of the timed batch whose results are compared with the oracle
 
 
 def log(*a):
@@ -159,14 +163,18 @@ def summarize_rocprof(root, command):
 
 
 def stored_traffic(workload):
-    """HBM bytes per scan launch from the committed counter summary (profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", f"adc_scan_traffic_{workload}.txt")
+    """(HBM bytes per scan launch, where the figure comes from) from the committed counter summary under profiles/,
+    or (None, reason).  The figure is not measured by the run that prints it: hardware counters need a run under
+    rocprofv3 --pmc of their own."""
+    rel = os.path.join("profiles", f"adc_scan_traffic_{workload}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, f"no stored counter summary ({rel})"
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+            return float(line.split(":")[1]), (f"stored: {rel} (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc runs of this workload, "
+                                               "each scaled by a plain copy kernel; not measured in this run)")
+    return None, f"{rel} holds no traffic_bytes_per_launch line"
 
 
 def exact_knn(g, cfg, torch, q, k, tile_rows=262144):
@@ -190,7 +198,7 @@ def exact_knn(g, cfg, torch, q, k, tile_rows=262144):
 
 def nprobe_sweep(args, pkg, cfg, torch):
     """Latency against nprobe (single query and batch of 8, p50 of `reps` searches per point, with the linear
-    fit latency = a + b * nprobe of Section 3.3's performance model) and recall@k of 1,000 queries against the
+    fit latency = a + b * nprobe of the performance model of Section 3.2, S3) and recall@k of 1,000 queries against the
     exact neighbours, for nprobe = 1, 2, 4, ... up to the configuration's nprobe."""
     nprobes = [p for p in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if p <= cfg.nprobe]
     ix, g, info = build_index(pkg, cfg, torch, max_nq=64, max_nprobe=max(nprobes), residual=args.residual)
@@ -286,7 +294,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "paper"])
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "paper"])
     ap.add_argument("--batches", type=int, default=8, help="different query batches the steps go round (default 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
@@ -360,6 +368,23 @@ def main():
     scan_ms = float(stage_ms[3])
     scanned_vecs, scanned_bytes = float(step_vecs.mean()), float(step_bytes.mean())
     achieved = step_bytes.sum() / (stage[:, 3].sum() * 1e-3) / 1e9
+    # ---- the scan at other batch sizes of the same index (stage events, median of 10 calls each) ----
+    by_nq = {}
+    ix.set_stage_timing(True)
+    for nq_x in sorted({1, 16, cfg.nq} - {cfg.nq}):
+        if nq_x > cfg.nq:
+            continue
+        fr = []
+        for r in range(12):
+            qs = q_all[(r * nq_x) % (q_all.shape[0] - nq_x + 1):][:nq_x].contiguous()
+            ix.ivfpq_search(qs, cfg.nprobe, cfg.k, out_d[:nq_x], out_i[:nq_x])
+            t_scan = float(ix.stage_times()[3])
+            fr.append((ix.search_stats()[1] / (t_scan * 1e-3) / 1e9, t_scan))
+        fr = fr[2:]
+        by_nq[str(nq_x)] = {"scanned_code_GBps": float(np.median([f[0] for f in fr])),
+                            "frac_of_hbm_peak": float(np.median([f[0] for f in fr])) / HBM_PEAK_GBS,
+                            "scan_ms": float(np.median([f[1] for f in fr])), "calls": len(fr)}
+    ix.set_stage_timing(False)
     ix.ivfpq_search(q, cfg.nprobe, cfg.k, out_d, out_i)      # the outputs checked below are those of the first batch
     torch.cuda.synchronize()
 
@@ -378,6 +403,7 @@ def main():
     p50_1q = float(np.median(lat)) if lat else None
     ix.set_graph_replay(False)
 
+    traffic, traffic_src = stored_traffic(cfg.name)
     result = {
         "metric": "IVF-PQ queries/sec + scanned-code HBM GB/s at nprobe; p50 1-query latency",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -393,10 +419,13 @@ def main():
         "stage_ms": {n: float(v) for n, v in zip(pkg.STAGE_NAMES, stage_ms)},
         "build_s": {k: round(info[k], 2) for k in ("train_s", "encode_s", "finalize_s")},
         "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(cfg.name),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "bytes_per_launch": scanned_bytes, "avg_launch_ms": scan_ms,
                      "note": "the kernel's whole launch: table staging, scan, k-selection, merge of the query's partial "
-                             "results, id gather and sort (there is no separate priming or merge kernel)"},
+                             "results, id gather and sort (there is no separate priming or merge kernel)"
+                             + ("; this index's codes are about the size of the last-level cache, so part of the rate "
+                                "is cache bandwidth, not HBM" if cfg.N * cfg.M <= (512 << 20) else "")},
+        "scan_at_other_batch_sizes": by_nq,
     }
 
     if args.calibrate_copy:
@@ -415,9 +444,13 @@ def main():
         import parity
         coarse_h, pq_h = info["coarse"].cpu().numpy(), info["pq"].cpu().numpy()
         qh = q.cpu().numpy()
+        # a bounded sample: the first ns queries of the first batch (the host copy holds the lists they probe)
+        ns = min(cfg.nq, PARITY_QUERIES)
+        qh = qh[:ns]
         gl0, _ = ix.ivf_coarse(q, cfg.nprobe)
         torch.cuda.synchronize()
-        needed = np.union1d(gl0.cpu().numpy().ravel(), oracle.coarse_search(qh, coarse_h, cfg.nprobe)[0].ravel())
+        gl0 = gl0.cpu().numpy()[:ns]
+        needed = np.union1d(gl0.ravel(), oracle.coarse_search(qh, coarse_h, cfg.nprobe)[0].ravel())
         hidx = host_copy(ix, coarse_h, pq_h, lists=needed, residual=args.residual)   # only the lists either side probes
         oracle.search(hidx, qh, cfg.nprobe, cfg.k)            # warm-up
         times = []
@@ -427,16 +460,14 @@ def main():
             od, oi, oprobes, oscanned = oracle.search(hidx, qh, cfg.nprobe, cfg.k)
             times.append(time.perf_counter() - t1)
         t_cpu = float(np.median(times))
-        result["cpu_baseline"] = {"value": cfg.nq / t_cpu, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-                                  "sample": f"the first {cfg.nq}-query batch of the benchmark, median of {len(times)} runs "
+        result["cpu_baseline"] = {"value": ns / t_cpu, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"the first {ns} queries of the benchmark's first batch, median of {len(times)} runs "
                                             f"({sum(times):.1f} s of CPU work), search only",
                                   "scanned_code_GBps": float(oscanned.sum()) * cfg.M / t_cpu / 1e9}
-        # sanity: the timed GPU configuration agrees with the oracle on this very batch
-        gl, _ = ix.ivf_coarse(q, cfg.nprobe)
-        torch.cuda.synchronize()
-        parity.check_probes(gl.cpu().numpy(), None, qh, coarse_h, cfg.nprobe)
-        ex, rel = parity.check_topk(out_d.cpu().numpy(), out_i.cpu().numpy(), hidx, qh, gl.cpu().numpy(), cfg.k)
-        result["parity_vs_oracle"] = {"queries_with_tie_differences": ex, "max_rel_dist_err": rel}
+        # sanity: the timed GPU configuration agrees with the oracle on these queries of this very batch
+        parity.check_probes(gl0, None, qh, coarse_h, cfg.nprobe)
+        ex, rel = parity.check_topk(out_d.cpu().numpy()[:ns], out_i.cpu().numpy()[:ns], hidx, qh, gl0, cfg.k)
+        result["parity_vs_oracle"] = {"queries_checked": ns, "queries_with_tie_differences": ex, "max_rel_dist_err": rel}
     print(json.dumps(result, default=float), flush=True)
 
 

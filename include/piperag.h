@@ -76,7 +76,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 /* Index training.  The paper does not say how the lists and codebooks are trained (Section 3.2, S3 only
  * states that the database is clustered into nlist lists); this is Lloyd's k-means with a fixed number of
  * iterations: centre j starts as row init_rows_host[j] of x; each iteration assigns every row to its
- * nearest centre (direct-form fp32 distance, lower index on equal values) and replaces each centre by the
+ * nearest centre (as piperag_ivf_add does, see there; lower index on equal values) and replaces each centre by the
  * mean of its rows (coordinate sums are exact 2^-24 fixed-point integers, so the result does not depend on
  * summation order; coordinates must stay below 2^15 in magnitude); a centre without rows keeps its value.
  * x_dev f32: n rows of d coordinates, row stride ldx floats (a column slice of a wider matrix trains one
@@ -88,7 +88,13 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
 /* Database construction (Section 2; Appendix, Software: each vector becomes a list number and M code
  * bytes): encodes n vectors x_dev f32 [n*d] on the GPU and appends them.  list(x) = nearest centre,
  * code[m] = nearest of the 256 centres of sub-quantiser m to the m-th slice of x; on equal distances the
- * lower index.  ids_dev: i64 [n] or NULL for consecutive ids continuing from the number already added.
+ * lower index.  Arithmetic of the decision: with 128 lists or more and d >= 64, |c|^2 - 2 <x, c> from a
+ * matrix-core product whose operands are carried as two fp16 parts each (22 significant bits: every product is
+ * as accurate as an fp32 multiplication) shortlists the two best centres, and the fp32 direct-form distances
+ * sum_t (x_t - c_t)^2 to those two decide; the result can differ from the exact nearest centre only where a
+ * third centre lies within the expanded form's fp32 rounding error (a few 2^-24 |x||c|) of the best.  Smaller
+ * shapes use the direct form throughout.  Codes: fp32 |p|^2 - 2 <x_m, p> on the matrix
+ * cores (direct form when d/M < 4).  ids_dev: i64 [n] or NULL for consecutive ids continuing from the number already added.
  * Enqueues on `stream`; x_dev and ids_dev must stay valid until the stream has passed the call. */
 int piperag_ivf_add(piperag_index *index, const float *x_dev, int64_t n, const int64_t *ids_dev, void *stream);
 

@@ -33,9 +33,10 @@ constexpr uint64_t kSentinel = 0xFFFFFFFFFFFFFFFFull;
 
 void set_error(const char *fmt, ...);
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st);   // squared row norms
-// bf16 hi / lo parts of n rows of d values in the encoder's chunk-major layout; each part holds split_bf16_elems(n, d) elements
-void split_bf16(const float *src, int64_t n, int d, uint16_t *hi, uint16_t *lo, hipStream_t st);
-size_t split_bf16_elems(int64_t n, int d);
+// scaled fp16 hi / lo parts of n rows of d values in the encoder's chunk-major layout; each part holds
+// split_f16_elems(n, d) elements; *amax (device) receives the bits of the largest magnitude, which fixes the scale
+void split_f16(const float *src, int64_t n, int d, uint32_t *amax, uint16_t *hi, uint16_t *lo, hipStream_t st);
+size_t split_f16_elems(int64_t n, int d);
 
 #define PR_CHECK_HIP(expr)                                                                     \
     do {                                                                                       \
@@ -70,6 +71,29 @@ inline int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 // depth rows of the encoder's codebook copy: the coordinates, one row of squared norms, rounded up to even
 inline int pqe_rows(int dsub) { return (dsub + 2) / 2 * 2; }
 
+// Device scratch of one search call.  Sized for (nlist, Mp, max_nq, max_nprobe, max_k) by search_ws_layout, which
+// carves it out of one block of memory; the index owns one, allocated at creation.
+struct SearchWs {
+    float *D;             // [parts][max_nq*nlist] coarse distances, or partial inner products (parts = kCoarseMaxParts up to kCoarseSplitMaxLists lists, else 1)
+    int32_t *probe;       // [max_nq*max_nprobe]
+    float *probe_d;       // [max_nq*max_nprobe]
+    int32_t *pfx;         // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
+    int64_t *scanned;     // [max_nq]
+    int32_t *seg0;        // [max_nq+1] first scan workgroup of each query
+    int4 *desc;           // [kMaxScanWGs+max_nq] (query, number among the query's workgroups, their count, chunk counters in use) of each scan workgroup
+    uint32_t *done;       // [max_nq + kMaxScanWGs + max_nq] finished scan workgroups (or groups of them) per query, then finished workgroups per group
+    uint64_t *part2;      // same shape as part: the queries' lists when a query's workgroups are grouped
+    uint32_t *tb;         // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
+    uint32_t *ctr;        // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
+    float *pcst;          // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
+    int32_t *pblk;        // [max_nq*max_nprobe] first block of each probed list
+    int32_t *plen;        // [max_nq*max_nprobe] length of each probed list
+    uint32_t *thr;        // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
+    float *lut;           // [max_nq*256*Mp], entry [q][j][m]
+    uint64_t *part;       // [(kMaxScanWGs+2*max_nq)*(max_k+64)] key lists of the queries (or of their groups of workgroups): room for max_k+64 keys per scan workgroup
+    int32_t max_nq, max_nprobe, max_k;   // what it is sized for; max_nprobe is the row stride of the probe tables
+};
+
 struct SearchGraph {
     const float *q;
     const int32_t *probes;
@@ -87,7 +111,8 @@ struct piperag_index {
     // trained parameters (device)
     float *centroids;  // [nlist*d]
     float *cnorm;      // [nlist] squared norms of the centres
-    uint16_t *cent_hi, *cent_lo;   // bf16 split of the centres for the encoder, chunk-major (NULL when the shape rules it out)
+    uint16_t *cent_hi, *cent_lo;   // scaled fp16 split of the centres for the encoder, chunk-major (NULL when the shape rules it out)
+    uint32_t *cent_amax;           // [1] bits of the centres' largest magnitude (fixes the scale of the split)
     float *pq;         // [M*256*dsub] sub-quantiser-major (as given)
     float *pqE;        // [M][pqe_rows(dsub)][256] the encoder's copy: pqE[m][t][j] = pq[m][j][t], row dsub = squared norms, then zeros
     float *pqT;        // [256*M*dsub] centre-major copy for the table build: pqT[j][m][t] = pq[m][j][t]
@@ -115,30 +140,17 @@ struct piperag_index {
     int32_t *list_blk;  // [nlist+1] first block of each list
     int32_t *list_len;  // [nlist]
     int64_t max_list_len;
-    uint8_t *rb_codes;  // read-back scratch for piperag_ivf_get_list (allocated on first use)
-    int64_t *rb_ids;
-    // search workspace
-    float *ws_D;          // [parts][max_nq*nlist] coarse distances, or partial inner products (parts = kCoarseMaxParts up to kCoarseSplitMaxLists lists, else 1)
-    int32_t *ws_probe;    // [max_nq*max_nprobe]
-    float *ws_probe_d;    // [max_nq*max_nprobe]
-    int32_t *ws_pfx;      // [max_nq*(max_nprobe+1)] block prefix sums of the probed lists
-    int64_t *ws_scanned;  // [max_nq]
-    int32_t *ws_seg0;     // [max_nq+1] first scan workgroup of each query
-    int4 *ws_desc;        // [kMaxScanWGs+max_nq] (query, number among the query's workgroups, their count, chunk counters in use) of each scan workgroup
-    uint32_t *ws_done;    // [max_nq + kMaxScanWGs + max_nq] finished scan workgroups (or groups of them) per query, then finished workgroups per group
-    uint64_t *ws_part2;   // same shape as ws_part: the queries' lists when a query's workgroups are grouped
-    uint32_t *ws_tb;      // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
-    uint32_t *ws_ctr;     // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
-    float *ws_pcst;       // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
-    int32_t *ws_pblk;     // [max_nq*max_nprobe] first block of each probed list
-    int32_t *ws_plen;     // [max_nq*max_nprobe] length of each probed list
-    uint32_t *ws_thr;     // [max_nq] per-query bound on the k-th best distance (bits), shared by the scan workgroups
-    float *ws_lut;        // [max_nq*256*Mp], entry [q][j][m]
-    uint64_t *ws_part;    // [(kMaxScanWGs+2*max_nq)*(max_k+64)] key lists of the queries (or of their groups of workgroups): room for max_k+64 keys per scan workgroup
+    mutable uint8_t *rb_codes;  // read-back scratch for piperag_ivf_get_list (allocated on first use)
+    mutable int64_t *rb_ids;
+    // search workspace (one allocation, carved by search_ws_layout)
+    SearchWs ws;
+    void *ws_mem;
     float *ws_out_d;      // [max_nq*max_k] scratch outputs (latency profile)
     int64_t *ws_out_i;    // [max_nq*max_k]
     int *flag;            // [1] device flag for argument checks
-    int32_t last_nq;
+    // state that searches (which take the index as const) update
+    mutable int32_t last_nq;
+    mutable const int64_t *last_scanned;   // the scanned-vector counts of the most recent search (in the workspace it used)
     // stage timing
     bool timing;
     hipEvent_t ev[PIPERAG_NSTAGES + 1];
@@ -149,13 +161,20 @@ struct piperag_index {
     hipStream_t cap_stream;       // capture stream for the search graphs
     bool replay;                  // graph replay of repeated calls is enabled
     int streaming;                // scan loads: < 0 by index size, 0 ordinary, > 0 non-temporal
-    SearchGraph graphs[8];
-    uint64_t graph_clock;
-    bool ev_valid;
+    mutable SearchGraph graphs[8];
+    mutable uint64_t graph_clock;
+    mutable bool ev_valid;
 };
 
 namespace piperag {
 // build plumbing shared by index.hip and encode.hip
+// Carves a search workspace for the given shape out of `base` (256-byte aligned; NULL: only the size is wanted)
+// and returns the bytes it takes.
+size_t search_ws_layout(SearchWs *ws, void *base, int nlist, int Mp, int max_nq, int max_nprobe, int max_k, int max_wgs);
+// Per-device set-up of the search and encode kernels (dynamic LDS limits);
+// called at index creation and by entry points that take no index.  Thread-safe.
+int configure_search_kernels(int device);
+int configure_encode_kernels(int device);
 int begin_build(piperag_index *ix, int mode);     // allocates what the build mode needs at its first call; rejects mixing modes
 int place_tile(piperag_index *ix, const int32_t *lists_dev, const uint8_t *codes_dev, const int64_t *ids_dev, int64_t n, hipStream_t st);
 void fill_iota(int64_t *dst, int64_t n, int64_t first, hipStream_t st);

@@ -1,11 +1,17 @@
 // Database construction on the GPU (Section 2, "Database construction"; Appendix "Detailed Evaluation
 // Setup", Software: every vector is assigned to one of nlist inverted lists and quantised into M code
-// bytes).  list(x) = argmin_j ||x - centre_j||^2, code[m] = argmin_j ||x_m - pq[m][j]||^2, both in the
-// direct (difference) form in fp32, lowest index on equal values.
+// bytes).  list(x) = argmin_j ||x - centre_j||^2, code[m] = argmin_j ||x_m - pq[m][j]||^2, lowest index on equal
+// values.  What decides the arg-min: for lists, on shapes the matrix cores take (128 centres or more, d >= 64), a
+// split-fp16 product |c|^2 - 2 <x, c> shortlists two centres per vector and their direct-form fp32 distances
+// sum_t (x_t - c_t)^2 decide between the two; on other shapes the direct form alone.  For codes, with 4 or
+// more coordinates per sub-quantiser, the fp32 matrix-core product |p|^2 - 2 <x_m, p>; below that the direct form.
 #include <stdlib.h>
 
+#include <algorithm>
+#include <mutex>
+
 #include "common.h"
-#include "mfma_bf16x3.h"
+#include "mfma_f16x3.h"
 #include "mfma_tile.h"
 
 using namespace piperag;
@@ -162,10 +168,17 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
 // One workgroup = 128 vectors, a wave = 32 of them; for each sub-quantiser the 256 centres are the row operand of
 // v_mfma_f32_32x32x2f32 and the wave's 32 vectors the column operand: 8 blocks of 32 centres x 32 vectors.  The
 // centres come from the depth-major copy pqE[m][t][j], whose row t = dsub holds the squared norms: with the
-// vectors entered as (-2 x_m, 1) the product is the quantity to minimise itself.  A lane then holds 128 centres
-// of one vector in its own registers and keeps the running best in ascending centre order (strict "<": lower
-// index on equal values); the two lanes that share a vector are combined with one shuffle.  Codes are
-// collected in LDS and written out as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
+// vectors entered as (-2 x_m, 1) the product is the quantity v to minimise itself.  A lane then holds 128 centres
+// of one vector in its own registers and walks them in ascending centre order (strict "<": lower index on equal
+// values); the two lanes that share a vector are combined with lane exchanges.
+// v orders the centres like the distance does up to its rounding errors, which are relative to |x_m||p| and not
+// to the distance, so the decision is made exact the way the list assignment's is: a lane keeps its two
+// smallest v, their centres and its third smallest v; with v1 the pair's smallest, every centre that could be
+// the nearest has v <= v1 + margin (margin = 4 (T + 2) 2^-24 (|x_m|^2 + |p1|^2): twice a bound on the error of a
+// v over T + 2 roundings).  One kept centre within the margin: it is the code.  Several: their direct-form fp32
+// distances sum_t (x_t - p_t)^2 decide, lower index on equal values.  A third smallest v within the margin as
+// well: the lane computes the direct form for all its 128 centres.  Codes are collected in LDS and written out
+// as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
 __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__restrict__ x, int64_t n, int d,
                                                              const float *__restrict__ pqE, int M, int dsub, int T,
                                                              const int32_t *__restrict__ lists, const float *__restrict__ cent,
@@ -181,6 +194,14 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
     const bool live = myrow < n;
     // residual indexes quantise x - c_l (one fp32 subtraction), l the vector's list
     const float *cr = lists && live ? cent + (size_t)lists[myrow] * d : nullptr;
+    auto x_at = [&](int m, int t) -> float {                     // coordinate t of the m-th slice of this lane's vector
+        float v = live ? xr[m * dsub + t] : 0.f;
+        if (cr) v -= cr[m * dsub + t];
+        return v;
+    };
+    auto centre_of = [&](int bi, int r) { return bi * 32 + (r % 4) + 4 * half + 8 * (r / 4); };   // of accumulator register r of block bi
+    const float inf = __builtin_inff();
+    const float margin_scale = 4.f * (float)(T + 2) * 5.9604645e-8f;
     for (int m = 0; m < M; ++m) {
         __syncthreads();                                          // the previous sub-quantiser's centres are no longer read
         const float4 *src = reinterpret_cast<const float4 *>(pqE + (size_t)m * T * kKsub);
@@ -191,31 +212,86 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
         for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bi][r] = 0.f;
+        float xq = 0.f;                                           // 4 x the squared norm of this lane's depth rows of x_m
         for (int p = 0; p < T / 2; ++p) {
             const int t = 2 * p + half;                           // lanes 0-31: depth 2p, lanes 32-63: depth 2p + 1
             float bv = t == dsub ? 1.f : 0.f;                     // the row of norms; padding rows are zero on both sides
             if (t < dsub) {
-                float v = live ? xr[m * dsub + t] : 0.f;
-                if (cr) v -= cr[m * dsub + t];
-                bv = -2.f * v;
+                bv = -2.f * x_at(m, t);
+                xq += bv * bv;
             }
             const float *a = sA + t * kKsub + l32;
 #pragma unroll
             for (int bi = 0; bi < 8; ++bi) acc[bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi * 32], bv, acc[bi], 0, 0, 0);
         }
-        float best = __builtin_inff();
-        int bj = 0;
+        float b1v = inf, b2v = inf, b3v = inf;
+        int b1c = 0, b2c = 0;
 #pragma unroll
         for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float v = acc[bi][r];
-                if (v < best) { best = v; bj = bi * 32 + (r % 4) + 4 * half + 8 * (r / 4); }   // ascending in bi, r
+                if (v < b3v) {                                    // ascending in bi, r = ascending centre
+                    const int c = centre_of(bi, r);
+                    if (v < b2v) {
+                        b3v = b2v;
+                        if (v < b1v) { b2v = b1v; b2c = b1c; b1v = v; b1c = c; } else { b2v = v; b2c = c; }
+                    } else {
+                        b3v = v;
+                    }
+                }
             }
-        const float ov = __shfl_xor(best, 32, 64);
-        const int oj = __shfl_xor(bj, 32, 64);
-        if (ov < best || (ov == best && oj < bj)) bj = oj;
-        if (half == 0) code_s[(wave * 32 + l32) * M + m] = (uint8_t)bj;
+        // the pair's smallest v, its centre and the margin
+        const float o1v = __shfl_xor(b1v, 32, 64), xn = 0.25f * (xq + __shfl_xor(xq, 32, 64));
+        const int o1c = __shfl_xor(b1c, 32, 64);
+        const bool mine_first = b1v < o1v || (b1v == o1v && b1c < o1c);
+        const float v1 = mine_first ? b1v : o1v;
+        int code = mine_first ? b1c : o1c;
+        const float limit = v1 + margin_scale * (xn + sA[dsub * kKsub + code]);
+        const bool more = (mine_first ? b2v : b1v) <= limit;      // a kept centre of mine, other than the pair's first, within the margin
+        const bool incomplete = b3v <= limit;                     // ... or one that was not kept
+        if (__any(more || incomplete)) {                          // seldom: direct-form distances decide
+            float best_d = inf;
+            int best_c = 256;
+            auto direct = [&](int c) {
+                float a2 = 0.f;
+                for (int t = 0; t < dsub; ++t) { const float e1 = x_at(m, t) - sA[t * kKsub + c]; a2 += e1 * e1; }
+                if (a2 < best_d || (a2 == best_d && c < best_c)) { best_d = a2; best_c = c; }
+            };
+            const bool pair_incomplete = __shfl_xor((int)incomplete, 32, 64) != 0 || incomplete;
+            const bool pair_more = __shfl_xor((int)more, 32, 64) != 0 || more;
+            if (pair_incomplete) {                                // every centre of this lane
+#pragma unroll
+                for (int bi = 0; bi < 8; ++bi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[bi][r] = 0.f;
+                for (int t = 0; t < dsub; ++t) {
+                    const float xv = x_at(m, t);
+                    const float *a = sA + t * kKsub + 4 * half;
+#pragma unroll
+                    for (int bi = 0; bi < 8; ++bi)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float e1 = xv - a[bi * 32 + (r % 4) + 8 * (r / 4)];
+                            acc[bi][r] += e1 * e1;
+                        }
+                }
+#pragma unroll
+                for (int bi = 0; bi < 8; ++bi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (acc[bi][r] < best_d) { best_d = acc[bi][r]; best_c = centre_of(bi, r); }
+            } else if (pair_more) {                               // the kept centres within the margin
+                if (b1v <= limit) direct(b1c);
+                if (b2v <= limit) direct(b2c);
+            }
+            if (pair_incomplete || pair_more) {
+                const float od = __shfl_xor(best_d, 32, 64);
+                const int oc = __shfl_xor(best_c, 32, 64);
+                code = (od < best_d || (od == best_d && oc < best_c)) ? oc : best_c;
+            }
+        }
+        if (half == 0) code_s[(wave * 32 + l32) * M + m] = (uint8_t)code;
     }
     __syncthreads();
     uint8_t *dst = out_codes + (size_t)row0 * M;
@@ -306,21 +382,47 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const float *__restric
 }
 
 // rows of x (stride ldx floats) against K centres; 16-byte loads only when every row start is 16-byte aligned
-// bf16 hi / lo parts of an fp32 matrix (n rows of d values, stride ld) in the chunk-major layout of
-// mfma_bf16x3.h; one thread per (row, chunk of 8 values), padding rows and chunks are written as zeros.
-__global__ void split_bf16_kernel(const float *__restrict__ src, int64_t n, int d, int64_t ld, int64_t rows_pad, int nchunks,
-                                  uint16_t *__restrict__ hi, uint16_t *__restrict__ lo) {
+// Largest magnitude of a matrix (n rows of d values, stride ld), as the bit pattern of the fp32 value, by atomic
+// maximum into *out (which the caller has zeroed; bit patterns of non-negative floats order like the values).
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ src, int64_t n, int d, int64_t ld,
+                                                     uint32_t *__restrict__ out) {
+    const int64_t total = n * d;
+    uint32_t m = 0;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / d;
+        m = max(m, __float_as_uint(src[row * ld + (e - row * d)]) & 0x7FFFFFFFu);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(out, m);
+}
+__global__ void zero_u32_kernel(uint32_t *p) { *p = 0u; }
+
+// Power of two s with amax * s in [2^14, 2^15) (1 for a zero matrix), and the exponent of 1 / s.
+__device__ __forceinline__ int split_exponent(uint32_t amax_bits) {        // e with s = 2^e
+    if (amax_bits == 0) return 0;
+    const int ex = min(127, max(-126, (int)(amax_bits >> 23) - 127));      // amax in [2^ex, 2^(ex+1))
+    return 14 - ex;
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(min(127, max(-126, e)) + 127) << 23); }
+
+// Scaled fp16 hi / lo parts of an fp32 matrix (n rows of d values, stride ld) in the chunk-major layout of
+// mfma_f16x3.h; the scale comes from the matrix's largest magnitude (*amax, see absmax_kernel).  One thread per
+// (row, chunk of 8 values), padding rows and chunks are written as zeros.
+__global__ void split_f16_kernel(const float *__restrict__ src, int64_t n, int d, int64_t ld, int64_t rows_pad, int nchunks,
+                                 const uint32_t *__restrict__ amax, uint16_t *__restrict__ hi, uint16_t *__restrict__ lo) {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= rows_pad * nchunks) return;
+    const float scale = pow2f(split_exponent(*amax));
     const int64_t row = e / nchunks;
     const int c = (int)(e % nchunks);
     uint16_t h[8], l[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const int k = c * 8 + t;
-        const float v = (row < n && k < d) ? src[row * ld + k] : 0.f;
-        const __bf16 vh = (__bf16)v;
-        const __bf16 vl = (__bf16)(v - (float)vh);
+        const float v = (row < n && k < d) ? src[row * ld + k] * scale : 0.f;     // exact: a power of two, no overflow by construction
+        const _Float16 vh = (_Float16)v;
+        const _Float16 vl = (_Float16)(v - (float)vh);
         h[t] = __builtin_bit_cast(uint16_t, vh);
         l[t] = __builtin_bit_cast(uint16_t, vl);
     }
@@ -329,116 +431,334 @@ __global__ void split_bf16_kernel(const float *__restrict__ src, int64_t n, int 
     for (int t = 0; t < 8; ++t) { hi[o + t] = h[t]; lo[o + t] = l[t]; }
 }
 
-// Nearest-centre assignment with the split-bf16 tile product: 128 vectors per workgroup against the centres 256
-// at a time.  The centres are the tile's A operand, so a lane holds, for each of its two vector columns, 64
-// centres of the tile in its own registers: the running best (|c|^2 - 2 <x, c>, centre) of a column is kept
-// per lane and compared register by register in ascending centre order (a strict "<" keeps the lower index on
-// equal values); lanes and waves that share a column are combined once at the end.
-__global__ __launch_bounds__(256, 2) void assign_bf16x3_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
-                                                            const uint16_t *__restrict__ xhi, const uint16_t *__restrict__ xlo,
-                                                            int64_t x_rp, const uint16_t *__restrict__ chi,
-                                                            const uint16_t *__restrict__ clo, int64_t c_rp,
-                                                            const float *__restrict__ cnorm, int K,
-                                                            int32_t *__restrict__ out_idx, float *__restrict__ out_dist) {
+// ---- nearest-centre assignment on the matrix cores, with an exact decision -------------------------
+// Stage 1 (assign_f16x3_kernel): the split-fp16 tile product gives v = |c|^2 - 2 <x, c> for every (vector,
+//   centre); per vector and per *source* (one of a fixed partition of the centres into 4 R parts, see below) the
+//   two smallest v and their centres are kept, and the third smallest v as a bound on everything not kept.
+// Stage 2 (assign_finish_kernel): v orders the centres like the distance does, up to its rounding errors, which
+//   are relative to |x||c| and not to the distance.  With v1 the smallest v of a vector, every centre that could
+//   be the nearest has v <= v1 + margin (margin = kAssignMargin (|x|^2 + |c1|^2), a bound on twice the error of a
+//   v: a few 2^-24 per accumulation step of the product, the norms and the final subtraction).  The kept centres
+//   within the margin are compared by their direct-form fp32 distances sum_t (x_t - c_t)^2, lower index on
+//   equal values.  If some source's third smallest v is also within the margin, a candidate may not have been
+//   kept: the vector goes to stage 3.
+// Stage 3 (assign_rows_direct_kernel + assign_rows_finish_kernel): the direct form against every centre for the
+//   vectors stage 2 could not settle (few, unless many centres lie within the rounding error of the nearest one).
+constexpr float kAssignMargin = 4e-5f;
+constexpr int kAssignWords = 9;                // per (vector, centre range): 8 keys (value bits << 32 | centre) and the bound
+
+__device__ __forceinline__ uint32_t ordered_bits(float v) {                 // unsigned order == float order
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float unordered_bits(uint32_t o) {
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+
+// A workgroup takes 128 vectors against the centres of its range, 256 at a time.  The centres are the tile's A
+// operand, so a lane holds, for each of its two vector columns, 64 centres of the tile in its own registers and
+// walks them in ascending centre order (a strict "<" keeps the lower index on equal values); a column's values
+// are spread over four such sources (lanes l and l + 32 of the two wave rows), which meet in LDS at the end.
+// The centres are split over R ranges of `per_range` centres (a multiple of 256); range r writes kAssignWords
+// words for row i at cand[((size_t)r * n + i) * kAssignWords].  grid = (vector tiles rounded up to a multiple of
+// 8) * R workgroups.
+__global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nchunks, const uint16_t *__restrict__ xhi,
+                                                              const uint16_t *__restrict__ xlo, int64_t x_rp,
+                                                              const uint16_t *__restrict__ chi, const uint16_t *__restrict__ clo,
+                                                              int64_t c_rp, const uint32_t *__restrict__ x_amax,
+                                                              const uint32_t *__restrict__ c_amax,
+                                                              const float *__restrict__ cnorm, int K, int R, int per_range,
+                                                              uint64_t *__restrict__ cand) {
     extern __shared__ __align__(16) unsigned char bsmem[];
-    float *s_cn = reinterpret_cast<float *>(bsmem + Bf16x3Tile::kLdsBytes);        // [2][256] centre norms of a tile (+inf: no centre)
-    float *s_bv = s_cn + 2 * Bf16x3Tile::kRowsA;                                    // [128 vectors][2 wave rows]
-    int *s_bj = reinterpret_cast<int *>(s_bv + 2 * Bf16x3Tile::kRowsB);
+    float *s_cn = reinterpret_cast<float *>(bsmem + F16x3Tile::kLdsBytes);        // [2][256] centre norms of a tile (+inf: no centre)
     const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 7;
-    const int64_t row0 = (int64_t)blockIdx.x * Bf16x3Tile::kRowsB;
-    const int nchunks = Bf16x3Tile::chunks_pad(d);
-    float bv[2] = {__builtin_inff(), __builtin_inff()};
-    int bc[2] = {0, 0};
+    // Which (vector tile, centre range) this workgroup takes.  Workgroups are dealt to the 8 XCDs in turn by
+    // their launch number: the R ranges of one vector tile go to workgroups 8 apart, i.e. to one XCD and next to
+    // each other in launch order, so that the tile's vectors are fetched into one L2 and found there by the
+    // other ranges, while the workgroups that walk the same range on that XCD share the centres.
+    const int i = blockIdx.x, g = i / (8 * R), j = i - g * 8 * R;
+    const int tile_v = g * 8 + (j & 7), range = j >> 3;
+    const int64_t row0 = (int64_t)tile_v * F16x3Tile::kRowsB;
+    if (row0 >= n) return;                                     // padding of the last group of 8 tiles (uniform)
+    const int jbeg = range * per_range, jend = min(K, jbeg + per_range);
+    // the tile product holds <x, c> times the two scales, both powers of two: undone exactly
+    const float m2 = -2.f * pow2f(-split_exponent(*x_amax) - split_exponent(*c_amax));
+    const float inf = __builtin_inff();
+    float b1v[2] = {inf, inf}, b2v[2] = {inf, inf}, b3v[2] = {inf, inf};
+    int b1c[2] = {K, K}, b2c[2] = {K, K};                      // K: no centre
     int tile = 0;
-    for (int j0 = 0; j0 < K; j0 += Bf16x3Tile::kRowsA, ++tile) {
-        float *cn = s_cn + (tile & 1) * Bf16x3Tile::kRowsA;    // read after the barriers inside run(); rewritten two tiles later
-        cn[tid] = j0 + tid < K ? cnorm[j0 + tid] : __builtin_inff();
+    for (int j0 = jbeg; j0 < jend; j0 += F16x3Tile::kRowsA, ++tile) {
+        float *cn = s_cn + (tile & 1) * F16x3Tile::kRowsA;     // read after the barriers inside run(); rewritten two tiles later
+        cn[tid] = j0 + tid < jend ? cnorm[j0 + tid] : inf;
         acc16_t acc[4][2];
-        Bf16x3Tile::run(chi, clo, c_rp, j0, xhi, xlo, x_rp, row0, nchunks, bsmem, acc);
+        F16x3Tile::run(chi, clo, c_rp, j0, xhi, xlo, x_rp, row0, nchunks, bsmem, acc);
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int r0 = Bf16x3Tile::acc_row(bi, 4 * g);                     // rows r0 .. r0+3 are registers 4g .. 4g+3
+            for (int gq = 0; gq < 4; ++gq) {
+                const int r0 = F16x3Tile::acc_row(bi, 4 * gq);                     // rows r0 .. r0+3 are registers 4gq .. 4gq+3
                 const float4 nn = *reinterpret_cast<const float4 *>(cn + r0);
                 const float nv[4] = {nn.x, nn.y, nn.z, nn.w};
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int bj = 0; bj < 2; ++bj) {
-                        const float v = nv[t] - 2.f * acc[bi][bj][4 * g + t];
-                        if (v < bv[bj]) { bv[bj] = v; bc[bj] = j0 + r0 + t; }
+                        const float v = nv[t] + m2 * acc[bi][bj][4 * gq + t];
+                        if (v < b3v[bj]) {                     // seldom true once the running values have settled
+                            const int c = j0 + r0 + t;
+                            if (v < b2v[bj]) {
+                                b3v[bj] = b2v[bj];
+                                if (v < b1v[bj]) { b2v[bj] = b1v[bj]; b2c[bj] = b1c[bj]; b1v[bj] = v; b1c[bj] = c; }
+                                else { b2v[bj] = v; b2c[bj] = c; }
+                            } else {
+                                b3v[bj] = v;
+                            }
+                        }
                     }
             }
     }
-    // lanes l and l + 32 hold the same columns (different centres), then the two wave rows
+    __syncthreads();                                           // the tile buffers are free
+    uint64_t *s_key = reinterpret_cast<uint64_t *>(bsmem);     // [128 columns][8 keys + 4 bounds]
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
-        const float ov = __shfl_xor(bv[bj], 32, 64);
-        const int oc = __shfl_xor(bc[bj], 32, 64);
-        if (ov < bv[bj] || (ov == bv[bj] && oc < bc[bj])) { bv[bj] = ov; bc[bj] = oc; }
-        if (lane < 32) {
-            const int col = Bf16x3Tile::acc_col(bj);
-            s_bv[col * 2 + wr] = bv[bj];
-            s_bj[col * 2 + wr] = bc[bj];
-        }
+        const int col = F16x3Tile::acc_col(bj), src = wr * 2 + (lane >> 5);
+        s_key[col * 12 + src * 2] = ((uint64_t)ordered_bits(b1v[bj]) << 32) | (uint32_t)b1c[bj];
+        s_key[col * 12 + src * 2 + 1] = ((uint64_t)ordered_bits(b2v[bj]) << 32) | (uint32_t)b2c[bj];
+        s_key[col * 12 + 8 + src] = (uint64_t)ordered_bits(b3v[bj]);
     }
     __syncthreads();
-    if (tid < Bf16x3Tile::kRowsB && row0 + tid < n) {
-        float v = s_bv[tid * 2];
-        int j = s_bj[tid * 2];
-        const float v1 = s_bv[tid * 2 + 1];
-        const int j1 = s_bj[tid * 2 + 1];
-        if (v1 < v || (v1 == v && j1 < j)) { v = v1; j = j1; }
-        out_idx[row0 + tid] = j;
-        if (out_dist) {
-            float xn = 0.f;
-            const float *xr = x + (row0 + tid) * ldx;
-            for (int t = 0; t < d; ++t) xn += xr[t] * xr[t];
-            out_dist[row0 + tid] = fmaxf(0.f, v + xn);
+    for (int e = tid; e < F16x3Tile::kRowsB * kAssignWords; e += 256) {      // rows of this tile are contiguous in cand
+        const int col = e / kAssignWords, w = e - col * kAssignWords;
+        if (row0 + col >= n) continue;
+        uint64_t word = s_key[col * 12 + w];
+        if (w == 8) {
+#pragma unroll
+            for (int u = 1; u < 4; ++u) word = min(word, s_key[col * 12 + 8 + u]);
         }
+        cand[((size_t)range * n + row0) * kAssignWords + e] = word;
+    }
+}
+
+// One wavefront per vector (see the head of this section).  flist / nflag: rows handed to stage 3 and their
+// count; fkey[pos] is initialised for stage 3's atomic minimum.
+__global__ __launch_bounds__(256) void assign_finish_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
+                                                            const float *__restrict__ cent, const float *__restrict__ cnorm, int K,
+                                                            const uint64_t *__restrict__ cand, int R,
+                                                            int32_t *__restrict__ out_idx, float *__restrict__ out_dist,
+                                                            uint32_t *__restrict__ flist, unsigned long long *__restrict__ fkey,
+                                                            uint32_t *__restrict__ nflag) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const float *xr = x + row * ldx;
+    float xn = 0.f;
+    for (int t = lane; t < d; t += 64) xn += xr[t] * xr[t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) xn += __shfl_xor(xn, off, 64);
+    // this lane's share of the words: entry e = range * kAssignWords + w
+    constexpr int kPerLane = 3;                                // 64 * 3 >= kAssignWords * 16 ranges
+    uint64_t mine[kPerLane];
+    uint64_t k1 = ~0ull;
+    uint32_t t3 = 0xFFFFFFFFu;
+#pragma unroll
+    for (int u = 0; u < kPerLane; ++u) {
+        const int e = lane + 64 * u;
+        mine[u] = ~0ull;
+        if (e < R * kAssignWords) {
+            const int r = e / kAssignWords, w = e - r * kAssignWords;
+            const uint64_t word = cand[((size_t)r * n + row) * kAssignWords + w];
+            if (w == 8) t3 = min(t3, (uint32_t)word);
+            else if ((uint32_t)word < (uint32_t)K) { mine[u] = word; k1 = min(k1, word); }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        k1 = min(k1, (uint64_t)__shfl_xor((unsigned long long)k1, off, 64));
+        t3 = min(t3, (uint32_t)__shfl_xor(t3, off, 64));
+    }
+    const bool any = k1 != ~0ull;                              // false only for values that are not numbers
+    const float v1 = unordered_bits((uint32_t)(k1 >> 32));
+    const float margin = kAssignMargin * (xn + (any ? cnorm[(uint32_t)k1] : 0.f));
+    const float limit = v1 + margin;
+    const bool complete = any && !(unordered_bits(t3) <= limit);
+    // direct-form distance to every kept centre within the margin, one after the other
+    float best_d = __builtin_inff();
+    int best_c = any ? (int)(uint32_t)k1 : 0;
+#pragma unroll
+    for (int u = 0; u < kPerLane; ++u) {
+        const bool have = mine[u] != ~0ull && unordered_bits((uint32_t)(mine[u] >> 32)) <= limit;
+        uint64_t todo = __ballot(have);
+        while (todo) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1;
+            const int c = (int)(uint32_t)__shfl((unsigned long long)mine[u], src, 64);
+            const float *pc = cent + (size_t)c * d;
+            float a = 0.f;
+            for (int t = lane; t < d; t += 64) { const float e1 = xr[t] - pc[t]; a += e1 * e1; }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+            if (a < best_d || (a == best_d && c < best_c)) { best_d = a; best_c = c; }
+        }
+    }
+    if (lane == 0) {
+        out_idx[row] = best_c;
+        if (out_dist) out_dist[row] = best_d;
+        if (!complete) {
+            const uint32_t pos = atomicAdd(nflag, 1u);
+            flist[pos] = (uint32_t)row;
+            fkey[pos] = ~0ull;
+        }
+    }
+}
+
+// Stage 3: direct-form distances of the listed rows to the centres of one split, 64 rows per workgroup at a time
+// (the tiling of assign_kernel); the nearest of a split meets the others' by an atomic minimum on
+// (distance bits << 32 | centre).  grid = (row groups, splits); workgroups beyond the list return at once.
+__global__ __launch_bounds__(256) void assign_rows_direct_kernel(const float *__restrict__ x, int d, int64_t ldx,
+                                                                 const uint32_t *__restrict__ flist, const uint32_t *__restrict__ nflag,
+                                                                 const float *__restrict__ cent, int K, int per_split,
+                                                                 unsigned long long *__restrict__ fkey) {
+    __shared__ __align__(16) float xs[TK * LDT];
+    __shared__ __align__(16) float cs[TK * LDT];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int lr = tid >> 2, lk = (tid & 3) * 4;
+    const int count = (int)*nflag;
+    const int jbeg = blockIdx.y * per_split, jend = min(K, jbeg + per_split);
+    for (int p0 = blockIdx.x * TM; p0 < count; p0 += gridDim.x * TM) {          // uniform
+        const int64_t my_row = p0 + lr < count ? (int64_t)flist[p0 + lr] : -1;
+        float best_d[4];
+        int best_j[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { best_d[i] = __builtin_inff(); best_j[i] = 0x7FFFFFFF; }
+        for (int j0 = jbeg; j0 < jend; j0 += TN) {
+            float acc[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) acc[i][jj] = 0.f;
+            for (int k0 = 0; k0 < d; k0 += TK) {
+                float xv[4], cv[4];
+                const int cr = j0 + lr;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int kk = k0 + lk + i;
+                    xv[i] = (my_row >= 0 && kk < d) ? x[my_row * ldx + kk] : 0.f;
+                    cv[i] = (cr < jend && kk < d) ? cent[(size_t)cr * d + kk] : 0.f;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xs[(lk + i) * LDT + lr] = xv[i];
+                    cs[(lk + i) * LDT + lr] = cv[i];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < TK; ++k) {
+                    const float4 a = *reinterpret_cast<const float4 *>(&xs[k * LDT + ty * 4]);
+                    const float4 b = *reinterpret_cast<const float4 *>(&cs[k * LDT + tx * 4]);
+                    const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const float diff = av[i] - bv[jj];
+                            acc[i][jj] += diff * diff;
+                        }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int jc = j0 + tx * 4 + jj;
+                    if (jc < jend && (acc[i][jj] < best_d[i] || (acc[i][jj] == best_d[i] && jc < best_j[i]))) { best_d[i] = acc[i][jj]; best_j[i] = jc; }
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int pos = p0 + ty * 4 + i;
+            if (pos < count && best_j[i] != 0x7FFFFFFF)
+                atomicMin(&fkey[pos], ((unsigned long long)__float_as_uint(best_d[i]) << 32) | (unsigned)best_j[i]);
+        }
+    }
+}
+__global__ void assign_rows_finish_kernel(const uint32_t *__restrict__ flist, const uint32_t *__restrict__ nflag,
+                                          const unsigned long long *__restrict__ fkey, int32_t *__restrict__ out_idx,
+                                          float *__restrict__ out_dist) {
+    const uint32_t count = *nflag;
+    for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p < count; p += gridDim.x * blockDim.x) {
+        const unsigned long long key = fkey[p];
+        out_idx[flist[p]] = (int32_t)(uint32_t)key;
+        if (out_dist) out_dist[flist[p]] = __uint_as_float((uint32_t)(key >> 32));
     }
 }
 
 // cnorm: squared norms of the centres (f32 [K]) or NULL.  The matrix-core path is taken when the shape pays for
 // it and allows 16-byte loads; otherwise the direct-form VALU kernel runs.
-// chi / clo: bf16 split of the centres (u16 [K*d] each) or NULL.  The matrix-core paths are taken when the shape
-// pays for them and allows 16-byte loads: split-bf16 first, fp32 MFMA second; otherwise the direct-form VALU
+// chi / clo / c_amax: scaled fp16 split of the centres (u16 [K*d] each) and the word its scale follows from, or NULL.  The matrix-core paths are taken when the shape
+// pays for them and allows 16-byte loads: split-fp16 first, fp32 MFMA second; otherwise the direct-form VALU
 // kernel runs.
-void launch_split(const float *src, int64_t n, int d, int64_t ld, uint16_t *hi, uint16_t *lo, hipStream_t st);
+void launch_split(const float *src, int64_t n, int d, int64_t ld, uint32_t *amax, uint16_t *hi, uint16_t *lo, hipStream_t st);
+
+// Centre ranges per vector tile of the split-fp16 assignment: the ranges of a tile run side by side on one XCD
+// (see the kernel), 8 vector tiles x 8 ranges filling its 64 workgroup slots.
+#ifndef PIPERAG_ASSIGN_RANGES
+#define PIPERAG_ASSIGN_RANGES 8
+#endif
+int assign_ranges() { return PIPERAG_ASSIGN_RANGES; }
 
 int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *cent, const float *cnorm, const uint16_t *chi,
-                  const uint16_t *clo, int K, int32_t *out_idx, float *out_dist, hipStream_t st) {
+                  const uint16_t *clo, const uint32_t *c_amax, int K, int32_t *out_idx, float *out_dist, hipStream_t st) {
     const int vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(cent) % 16 == 0);
     const bool mfma = vec4 && cnorm != nullptr && K >= 128 && d >= 64;
-    const bool bf16 = cnorm != nullptr && K >= 128 && d >= 64 && chi != nullptr && clo != nullptr;
-    constexpr size_t kBfLds = Bf16x3Tile::kLdsBytes + sizeof(float) * (2 * Bf16x3Tile::kRowsA + 4 * Bf16x3Tile::kRowsB);
-    if (bf16) {
-        static bool configured = false;
-        if (!configured) {
-            PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_bf16x3_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBfLds));
-            configured = true;
-        }
-        // the vectors are split slice by slice into a scratch area that lives in stream order
-        const int64_t slice = std::max<int64_t>(Bf16x3Tile::kRowPad, ((int64_t)1 << 28) / ((int64_t)Bf16x3Tile::chunks_pad(d) * 8) /
-                                                                         Bf16x3Tile::kRowPad * Bf16x3Tile::kRowPad);
-        const int64_t cap_rows = std::min(slice, Bf16x3Tile::rows_pad(n));
-        const size_t part = Bf16x3Tile::part_elems(cap_rows, d);
-        uint16_t *xs = nullptr;
-        PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&xs), 2 * part * sizeof(uint16_t), st));
-        const int nchunks = Bf16x3Tile::chunks_pad(d);
-        const int64_t c_rp = Bf16x3Tile::rows_pad(K);
+    const bool split16 = cnorm != nullptr && K >= 128 && d >= 64 && chi != nullptr && clo != nullptr && c_amax != nullptr;
+    constexpr size_t kBfLds = F16x3Tile::kLdsBytes + sizeof(float) * 2 * F16x3Tile::kRowsA;
+    if (split16) {
+        // the vectors are split slice by slice into a scratch area that lives in stream order; the shortlist
+        // (two keys per vector and centre range) follows it
+        const int64_t slice = std::max<int64_t>(F16x3Tile::kRowPad, ((int64_t)1 << 28) / ((int64_t)F16x3Tile::chunks_pad(d) * 8) /
+                                                                         F16x3Tile::kRowPad * F16x3Tile::kRowPad);
+        const int64_t cap_rows = std::min(slice, F16x3Tile::rows_pad(n));
+        const size_t part = F16x3Tile::part_elems(cap_rows, d);
+        // centre ranges: multiples of 256 centres, at most kAssignRanges of them
+        const int tiles_c = (K + F16x3Tile::kRowsA - 1) / F16x3Tile::kRowsA;
+        const int R = std::max(1, std::min(std::min(assign_ranges(), 16), tiles_c));
+        const int per_range = (tiles_c + R - 1) / R * F16x3Tile::kRowsA;
+        const int Ruse = (K + per_range - 1) / per_range;
+        const size_t split_bytes = (2 * part * sizeof(uint16_t) + 255) / 256 * 256;
+        const size_t cand_bytes = sizeof(uint64_t) * kAssignWords * (size_t)Ruse * cap_rows;
+        const size_t flist_bytes = (sizeof(uint32_t) * (size_t)cap_rows + 255) / 256 * 256;
+        const size_t fkey_bytes = sizeof(unsigned long long) * (size_t)cap_rows;
+        unsigned char *scratch = nullptr;
+        PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&scratch), split_bytes + cand_bytes + flist_bytes + fkey_bytes + 512, st));
+        uint16_t *xs = reinterpret_cast<uint16_t *>(scratch);
+        uint64_t *cand = reinterpret_cast<uint64_t *>(scratch + split_bytes);
+        uint32_t *flist = reinterpret_cast<uint32_t *>(scratch + split_bytes + cand_bytes);
+        unsigned long long *fkey = reinterpret_cast<unsigned long long *>(scratch + split_bytes + cand_bytes + flist_bytes);
+        uint32_t *x_amax = reinterpret_cast<uint32_t *>(scratch + split_bytes + cand_bytes + flist_bytes + fkey_bytes);
+        uint32_t *nflag = x_amax + 64;
+        const int nchunks = F16x3Tile::chunks_pad(d);
+        const int64_t c_rp = F16x3Tile::rows_pad(K);
+        // stage 3 splits the centres so that even a handful of rows keeps many compute units busy
+        const int per_split = std::max(TN, (K + 63) / 64 / TN * TN), splits = (K + per_split - 1) / per_split;
         for (int64_t a = 0; a < n; a += slice) {
-            const int64_t cnt = std::min(slice, n - a), rp = Bf16x3Tile::rows_pad(cnt);
-            launch_split(x + a * ldx, cnt, d, ldx, xs, xs + part, st);
-            hipLaunchKernelGGL(assign_bf16x3_kernel, dim3((unsigned)((cnt + Bf16x3Tile::kRowsB - 1) / Bf16x3Tile::kRowsB)), dim3(256),
-                               kBfLds, st, x + a * ldx, cnt, d, ldx, xs, xs + part, rp, chi, clo, c_rp, cnorm, K, out_idx + a,
+            const int64_t cnt = std::min(slice, n - a), rp = F16x3Tile::rows_pad(cnt);
+            launch_split(x + a * ldx, cnt, d, ldx, x_amax, xs, xs + part, st);
+            hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, st, nflag);
+            const int64_t tiles_v = (cnt + F16x3Tile::kRowsB - 1) / F16x3Tile::kRowsB;
+            const unsigned grid = (unsigned)((tiles_v + 7) / 8 * 8 * Ruse);
+            hipLaunchKernelGGL(assign_f16x3_kernel, dim3(grid), dim3(256), kBfLds, st, cnt, nchunks, xs, xs + part, rp, chi, clo, c_rp,
+                               x_amax, c_amax, cnorm, K, Ruse, per_range, cand);
+            hipLaunchKernelGGL(assign_finish_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
+                               cnorm, K, cand, Ruse, out_idx + a, out_dist ? out_dist + a : nullptr, flist, fkey, nflag);
+            const unsigned row_groups = (unsigned)std::min<int64_t>((cnt + TM - 1) / TM, 256);
+            hipLaunchKernelGGL(assign_rows_direct_kernel, dim3(row_groups, splits), dim3(256), 0, st, x + a * ldx, d, ldx, flist, nflag,
+                               cent, K, per_split, fkey);
+            hipLaunchKernelGGL(assign_rows_finish_kernel, dim3(64), dim3(256), 0, st, flist, nflag, fkey, out_idx + a,
                                out_dist ? out_dist + a : nullptr);
-            (void)nchunks;
         }
-        PR_CHECK_HIP(hipFreeAsync(xs, st));
+        PR_CHECK_HIP(hipFreeAsync(scratch, st));
         return PIPERAG_OK;
     }
     constexpr int64_t kSlice = 1 << 22;              // rows per launch
@@ -454,13 +774,17 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
     return PIPERAG_OK;
 }
 
-// Splits n rows of d values (stride ld) into the chunk-major bf16 hi / lo parts; each part holds
-// Bf16x3Tile::part_elems(n, d) elements.
-void launch_split(const float *src, int64_t n, int d, int64_t ld, uint16_t *hi, uint16_t *lo, hipStream_t st) {
-    const int64_t rp = Bf16x3Tile::rows_pad(n);
-    const int nchunks = Bf16x3Tile::chunks_pad(d);
-    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((rp * nchunks + 255) / 256)), dim3(256), 0, st, src, n, d, ld, rp, nchunks, hi,
-                       lo);
+// Splits n rows of d values (stride ld) into the chunk-major scaled fp16 hi / lo parts; each part holds
+// F16x3Tile::part_elems(n, d) elements.  amax (device, one word) receives the bits of the matrix's largest magnitude,
+// from which the scale follows; whoever multiplies the parts needs it to undo the scale.
+void launch_split(const float *src, int64_t n, int d, int64_t ld, uint32_t *amax, uint16_t *hi, uint16_t *lo, hipStream_t st) {
+    const int64_t rp = F16x3Tile::rows_pad(n);
+    const int nchunks = F16x3Tile::chunks_pad(d);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, st, amax);
+    const unsigned blocks = (unsigned)std::min<int64_t>(4096, (n * d + 255) / 256);
+    if (blocks > 0) hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, src, n, d, ld, amax);
+    hipLaunchKernelGGL(split_f16_kernel, dim3((unsigned)((rp * nchunks + 255) / 256)), dim3(256), 0, st, src, n, d, ld, rp, nchunks, amax,
+                       hi, lo);
 }
 
 void launch_rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) {
@@ -502,9 +826,30 @@ __global__ void zero_kernel(unsigned long long *__restrict__ p, int64_t n) {
 }  // namespace
 
 namespace piperag {
+// Per device, once: the encoder's kernels may use the whole 160 KiB of LDS as dynamic shared memory.
+int configure_encode_kernels(int device) {
+    static std::mutex mutex;
+    static bool done[64];
+    PR_REQUIRE(device >= 0 && device < 64, PIPERAG_ERR_ARG, "device %d out of range", device);
+    std::lock_guard<std::mutex> lock(mutex);
+    if (done[device]) return PIPERAG_OK;
+    int cur = -1;
+    PR_CHECK_HIP(hipGetDevice(&cur));
+    if (cur != device) PR_CHECK_HIP(hipSetDevice(device));
+    const void *kernels[] = {reinterpret_cast<const void *>(&assign_f16x3_kernel), reinterpret_cast<const void *>(&pq_encode_mfma_kernel),
+                             reinterpret_cast<const void *>(&pq_encode_kernel)};
+    for (const void *k : kernels) {             // whatever the kernel's static LDS leaves of the 160 KiB
+        hipFuncAttributes fa;
+        PR_CHECK_HIP(hipFuncGetAttributes(&fa, k));
+        PR_CHECK_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - (int)fa.sharedSizeBytes));
+    }
+    done[device] = true;
+    if (cur != device && cur >= 0) PR_CHECK_HIP(hipSetDevice(cur));
+    return PIPERAG_OK;
+}
 void rownorm(const float *a, int64_t n, int d, int64_t lda, float *out, hipStream_t st) { launch_rownorm(a, n, d, lda, out, st); }
-void split_bf16(const float *src, int64_t n, int d, uint16_t *hi, uint16_t *lo, hipStream_t st) { launch_split(src, n, d, d, hi, lo, st); }
-size_t split_bf16_elems(int64_t n, int d) { return Bf16x3Tile::part_elems(n, d); }
+void split_f16(const float *src, int64_t n, int d, uint32_t *amax, uint16_t *hi, uint16_t *lo, hipStream_t st) { launch_split(src, n, d, d, amax, hi, lo, st); }
+size_t split_f16_elems(int64_t n, int d) { return F16x3Tile::part_elems(n, d); }
 }  // namespace piperag
 
 namespace {
@@ -522,7 +867,7 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *lis
         assign = true;
     }
     if (assign && lists) {
-        const int rc = launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, p.nlist, lists, nullptr, st);
+        const int rc = launch_assign(x, n, p.d, p.d, ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->cent_amax, p.nlist, lists, nullptr, st);
         if (rc != PIPERAG_OK) { if (tmp_lists) (void)hipFreeAsync(tmp_lists, st); return rc; }
     }
     const int32_t *res_lists = p.residual ? lists : nullptr;
@@ -533,23 +878,13 @@ int encode_impl(const piperag_index *ix, const float *x, int64_t n, int32_t *lis
             if (ix->dsub >= 4) {                                 // matrix cores
                 const int T = pqe_rows(ix->dsub);
                 const size_t lds = sizeof(float) * (size_t)T * kKsub + (size_t)128 * p.M;
-                static size_t configured = 0;
-                if (lds > configured) {
-                    PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&pq_encode_mfma_kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-                    configured = lds;
-                }
+                PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "the encoder needs %zu bytes of LDS (M too large)", lds);
                 hipLaunchKernelGGL(pq_encode_mfma_kernel, dim3((unsigned)((cnt + 127) / 128)), dim3(256), lds, st, x + a * p.d, cnt,
                                    p.d, ix->pqE, p.M, ix->dsub, T, res_lists ? res_lists + a : nullptr, ix->centroids,
                                    out_codes + (size_t)a * p.M);
             } else {
                 const size_t lds = sizeof(float) * 2 * kKsub * ix->dsub + (size_t)256 * p.M;
-                static size_t configured = 0;
-                if (lds > configured) {
-                    PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&pq_encode_kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-                    configured = lds;
-                }
+                PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "the encoder needs %zu bytes of LDS (M too large)", lds);
                 hipLaunchKernelGGL(pq_encode_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), lds, st, x + a * p.d, cnt, p.d,
                                    ix->pq, p.M, ix->dsub, res_lists ? res_lists + a : nullptr, ix->centroids,
                                    out_codes + (size_t)a * p.M);
@@ -583,6 +918,12 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     for (int j = 0; j < K; ++j)
         PR_REQUIRE(init_rows_host[j] >= 0 && init_rows_host[j] < n, PIPERAG_ERR_ARG, "init row %d out of range", j);
     hipStream_t st = (hipStream_t)stream;
+    {
+        int device = 0;
+        PR_CHECK_HIP(hipGetDevice(&device));
+        const int rcc = configure_encode_kernels(device);
+        if (rcc != PIPERAG_OK) return rcc;
+    }
     int64_t *rows = nullptr;
     int32_t *assign = nullptr;
     float *adist = nullptr;
@@ -590,9 +931,10 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     int *count = nullptr;
     float *cnorm = nullptr;
     uint16_t *chi = nullptr, *clo = nullptr;
+    uint32_t *camax = nullptr;
     float *hdist = inertia_out_host ? (float *)malloc(sizeof(float) * (size_t)n) : nullptr;
     auto done = [&](int code) {
-        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count); (void)hipFree(cnorm); (void)hipFree(chi); (void)hipFree(clo);
+        (void)hipFree(rows); (void)hipFree(assign); (void)hipFree(adist); (void)hipFree(sum); (void)hipFree(count); (void)hipFree(cnorm); (void)hipFree(chi); (void)hipFree(clo); (void)hipFree(camax);
         free(hdist);
         return code;
     };
@@ -605,8 +947,9 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
         return done(PIPERAG_ERR_OOM);
     }
     const bool use_split = K >= 128 && d >= 64;
-    if (use_split && (hipMalloc((void **)&chi, sizeof(uint16_t) * Bf16x3Tile::part_elems(K, d)) != hipSuccess ||
-                      hipMalloc((void **)&clo, sizeof(uint16_t) * Bf16x3Tile::part_elems(K, d)) != hipSuccess)) {
+    if (use_split && (hipMalloc((void **)&chi, sizeof(uint16_t) * F16x3Tile::part_elems(K, d)) != hipSuccess ||
+                      hipMalloc((void **)&clo, sizeof(uint16_t) * F16x3Tile::part_elems(K, d)) != hipSuccess ||
+                      hipMalloc((void **)&camax, 256) != hipSuccess)) {
         set_error("out of device memory in piperag_kmeans");
         return done(PIPERAG_ERR_OOM);
     }
@@ -617,8 +960,8 @@ int piperag_kmeans(const float *x_dev, int64_t n, int32_t d, int64_t ldx, int32_
     const int64_t nsum = (int64_t)K * d;
     for (int it = 0; it < iters; ++it) {
         launch_rownorm(centroids_out_dev, K, d, d, cnorm, st);
-        if (use_split) launch_split(centroids_out_dev, K, d, d, chi, clo, st);
-        const int rca = launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, chi, clo, K, assign, adist, st);
+        if (use_split) launch_split(centroids_out_dev, K, d, d, camax, chi, clo, st);
+        const int rca = launch_assign(x_dev, n, d, ldx, centroids_out_dev, cnorm, chi, clo, camax, K, assign, adist, st);
         if (rca != PIPERAG_OK) return done(rca);
         hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st, (unsigned long long *)sum, nsum);
         hipLaunchKernelGGL(zero_kernel, dim3((K / 2 + 256) / 256), dim3(256), 0, st, (unsigned long long *)count, (int64_t)(K + 1) / 2);
@@ -669,7 +1012,7 @@ int piperag_ivf_count(piperag_index *index, const float *x_dev, int64_t n, void 
     PR_CHECK_HIP(hipSetDevice(index->device));
     const piperag_params &p = index->p;
     int32_t *lists = index->st_list + index->nadded;
-    rc = launch_assign(x_dev, n, p.d, p.d, index->centroids, index->cnorm, index->cent_hi, index->cent_lo, p.nlist, lists, nullptr, st);
+    rc = launch_assign(x_dev, n, p.d, p.d, index->centroids, index->cnorm, index->cent_hi, index->cent_lo, index->cent_amax, p.nlist, lists, nullptr, st);
     if (rc != PIPERAG_OK) return rc;
     count_lists(lists, n, index->bd_counts, st);
     index->nadded += n;

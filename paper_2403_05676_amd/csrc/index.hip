@@ -258,31 +258,27 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     const size_t ncent = (size_t)p.nlist * p.d, npq = (size_t)p.M * kKsub * ix->dsub;
     if ((rc = dev_alloc(&ix->centroids, ncent)) || (rc = dev_alloc(&ix->pq, npq)) ||
         (rc = dev_alloc(&ix->list_blk, (size_t)p.nlist + 1)) ||
-        (rc = dev_alloc(&ix->list_len, (size_t)p.nlist)) || (rc = dev_alloc(&ix->ws_D, (size_t)p.max_nq * p.nlist * (p.nlist <= kCoarseSplitMaxLists ? kCoarseMaxParts : 1))) ||
-        (rc = dev_alloc(&ix->ws_probe, (size_t)p.max_nq * p.max_nprobe)) ||
-        (rc = dev_alloc(&ix->ws_probe_d, (size_t)p.max_nq * p.max_nprobe)) ||
-        (rc = dev_alloc(&ix->ws_pfx, (size_t)p.max_nq * (p.max_nprobe + 1))) ||
-        (rc = dev_alloc(&ix->ws_scanned, (size_t)p.max_nq)) || (rc = dev_alloc(&ix->ws_thr, (size_t)p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_seg0, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_desc, (size_t)kMaxScanWGs + p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_tb, (size_t)p.max_nq + 1)) || (rc = dev_alloc(&ix->ws_ctr, (size_t)p.max_nq * kCtrPerQuery * kCtrStride)) || (rc = dev_alloc(&ix->ws_pblk, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_pcst, (size_t)p.max_nq * p.max_nprobe)) || (rc = dev_alloc(&ix->ws_plen, (size_t)p.max_nq * p.max_nprobe)) ||
-        (rc = dev_alloc(&ix->ws_lut, (size_t)p.max_nq * kKsub * ix->Mp)) ||
-        (rc = dev_alloc(&ix->ws_part, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
-        (rc = dev_alloc(&ix->ws_done, (size_t)kMaxScanWGs + 2 * (size_t)p.max_nq)) ||
-        (rc = dev_alloc(&ix->ws_part2, ((size_t)kMaxScanWGs + 2 * (size_t)p.max_nq) * (p.max_k + 64))) ||
+        (rc = dev_alloc(&ix->list_len, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->pqT, npq)) || (rc = dev_alloc(&ix->pqE, (size_t)p.M * pqe_rows(ix->dsub) * kKsub)) || (rc = dev_alloc(&ix->cnorm, (size_t)p.nlist)) ||
         (rc = dev_alloc(&ix->ws_out_d, (size_t)p.max_nq * p.max_k)) ||
         (rc = dev_alloc(&ix->ws_out_i, (size_t)p.max_nq * p.max_k)) || (rc = dev_alloc(&ix->flag, 1)))
         return fail(rc);
-    if (hipMemset(ix->ws_tb, 0, sizeof(uint32_t) * ((size_t)p.max_nq + 1)) != hipSuccess ||   // arrival counter starts at zero
+    if ((rc = configure_search_kernels(ix->device)) || (rc = configure_encode_kernels(ix->device))) return fail(rc);
+    {   // the search workspace: one block, carved up by search_ws_layout
+        const size_t ws_bytes = search_ws_layout(&ix->ws, nullptr, p.nlist, ix->Mp, p.max_nq, p.max_nprobe, p.max_k, kMaxScanWGs);
+        if (hipMalloc(&ix->ws_mem, ws_bytes) != hipSuccess) { set_error("out of device memory for %zu bytes of search workspace", ws_bytes); return fail(PIPERAG_ERR_OOM); }
+        search_ws_layout(&ix->ws, ix->ws_mem, p.nlist, ix->Mp, p.max_nq, p.max_nprobe, p.max_k, kMaxScanWGs);
+    }
+    if (hipMemset(ix->ws.tb, 0, sizeof(uint32_t) * ((size_t)p.max_nq + 1)) != hipSuccess ||   // arrival counter starts at zero
         hipMemcpy(ix->centroids, cent_host, ncent * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ix->pq, pq_host, npq * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
         set_error("upload of trained parameters failed");
         return fail(PIPERAG_ERR_HIP);
     }
     if (p.nlist >= 128 && p.d >= 64) {
-        const size_t nsplit = split_bf16_elems(p.nlist, p.d);
-        if ((rc = dev_alloc(&ix->cent_hi, nsplit)) || (rc = dev_alloc(&ix->cent_lo, nsplit))) return fail(rc);
-        split_bf16(ix->centroids, p.nlist, p.d, ix->cent_hi, ix->cent_lo, nullptr);
+        const size_t nsplit = split_f16_elems(p.nlist, p.d);
+        if ((rc = dev_alloc(&ix->cent_hi, nsplit)) || (rc = dev_alloc(&ix->cent_lo, nsplit)) || (rc = dev_alloc(&ix->cent_amax, 64))) return fail(rc);
+        split_f16(ix->centroids, p.nlist, p.d, ix->cent_amax, ix->cent_hi, ix->cent_lo, nullptr);
     }
     rownorm(ix->centroids, p.nlist, p.d, p.d, ix->cnorm, nullptr);
     if (hipStreamSynchronize(nullptr) != hipSuccess) { set_error("centre norms failed"); return fail(PIPERAG_ERR_HIP); }
@@ -412,8 +408,7 @@ int piperag_ivf_create(const piperag_params *params, const float *centroids_host
 void piperag_ivf_free(piperag_index *ix) {
     if (!ix) return;
     free_staging(ix);
-    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->rb_codes, ix->rb_ids, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->ws_D, ix->ws_probe,
-                    ix->ws_probe_d, ix->ws_pfx, ix->ws_scanned, ix->ws_thr, ix->ws_seg0, ix->ws_desc, ix->ws_tb, ix->ws_ctr, ix->ws_pcst, ix->tx, ix->ws_pblk, ix->ws_plen, ix->ws_lut, ix->ws_part, ix->ws_part2, ix->ws_done, ix->ws_out_d, ix->ws_out_i, ix->flag};
+    void *ptrs[] = {ix->centroids, ix->cnorm, ix->cent_hi, ix->cent_lo, ix->cent_amax, ix->rb_codes, ix->rb_ids, ix->pq, ix->pqT, ix->pqE, ix->codes, ix->ids, ix->list_blk, ix->list_len, ix->tx, ix->ws_mem, ix->ws_out_d, ix->ws_out_i, ix->flag};
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);
@@ -571,7 +566,7 @@ int piperag_ivf_get_list(const piperag_index *ix, int32_t list, int64_t *len_out
     if (len_out) *len_out = len;
     if (len == 0 || (!codes_host && !ids_host)) return PIPERAG_OK;
     // read-back scratch sized for the longest list, allocated on first use and kept with the index
-    piperag_index *mix = const_cast<piperag_index *>(ix);
+    const piperag_index *mix = ix;           // the read-back buffers are mutable members
     if (!mix->rb_codes) {
         const size_t cap = (size_t)std::max<int64_t>(ix->max_list_len, 1);
         if (hipMalloc(reinterpret_cast<void **>(&mix->rb_codes), cap * ix->p.M) != hipSuccess ||

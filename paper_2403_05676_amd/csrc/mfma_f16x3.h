@@ -1,8 +1,11 @@
-// Split-bf16 MFMA tile product for gfx950: dot products <a_i, b_j> of fp32 rows at close to fp32 accuracy on
-// the bf16 matrix cores.  Every fp32 value v is written as hi + lo with hi = bf16(v) and lo = bf16(v - hi)
-// (16 significant bits together); <a, b> ~ <a_hi, b_hi> + <a_hi, b_lo> + <a_lo, b_hi>, accumulated in fp32
-// by three v_mfma_f32_32x32x16_bf16 per 32 x 32 block and 16 depth values.  The dropped lo*lo term and the
-// rounding of lo are 2^-16 relative per product.  Used by the encoder's list assignment.
+// Split-fp16 MFMA tile product for gfx950: dot products <a_i, b_j> of fp32 rows at fp32 accuracy on the fp16
+// matrix cores.  A matrix is scaled by a power of two s so that its largest magnitude lies in [2^14, 2^15), and
+// every scaled value v is written as hi + lo with hi = fp16(v) and lo = fp16(v - hi): 22 significant bits
+// together (|v - hi - lo| <= 2^-24 |v|, or 2^-25 in absolute terms where lo is subnormal, i.e. 2^-39 of the
+// matrix's largest magnitude).  <a, b> ~ <a_hi, b_hi> + <a_hi, b_lo> + <a_lo, b_hi>, accumulated in fp32 by three
+// v_mfma_f32_32x32x16_f16 per 32 x 32 block and 16 depth values; the dropped lo*lo term is 2^-24 relative per
+// product, so each product is as accurate as an fp32 multiplication (3 * 2^-24 |a||b|), and the caller undoes the
+// two scales exactly.  Used by the encoder's list assignment.
 //
 // Operands are split beforehand into the "chunk-major" layout below, so that what a workgroup needs for one
 // depth step is a few contiguous kilobytes (every cache line fetched is used whole; with row-major operands a
@@ -16,7 +19,7 @@
 // blocks.  The accumulator of a block keeps 16 rows of one column per lane, so A should be the operand over
 // which the caller reduces (the centres, for an arg-min): the reduction then runs over a lane's own registers.
 // Depth step 16 = two chunks; lanes 0-31 take the first chunk of the step and lanes 32-63 the second, for A and
-// B alike, which is all a sum over the depth needs.  LDS holds [chunk of the step][row][8 bf16] per part, the
+// B alike, which is all a sum over the depth needs.  LDS holds [chunk of the step][row][8 fp16] per part, the
 // same order as in memory.  Two steps are in flight: one in registers, one in the second LDS buffer.
 #pragma once
 
@@ -26,9 +29,9 @@
 namespace piperag {
 
 typedef float acc16_t __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
-struct Bf16x3Tile {
+struct F16x3Tile {
     static constexpr int kRowsA = 256, kRowsB = 128, kTileK = 16, kRowPad = 256;
     static constexpr int kPartA = 2 * kRowsA * 16, kPartB = 2 * kRowsB * 16;          // bytes of one hi or lo part per step
     static constexpr size_t kLdsBytes = 2 * (2 * (size_t)kPartA + 2 * (size_t)kPartB);  // double-buffered
@@ -90,24 +93,24 @@ struct Bf16x3Tile {
         const int half = lane >> 5, l32 = lane & 31;
         auto multiply = [&](int buf) {
             const int a_off = (half * kRowsA + wr * 128 + l32) * 16, b_off = (half * kRowsB + wc * 64 + l32) * 16;
-            bf16x8_t ah[4], al[4], bh[2], bl[2];
+            f16x8_t ah[4], al[4], bh[2], bl[2];
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) {
-                ah[bi] = *reinterpret_cast<const bf16x8_t *>(sAh[buf] + a_off + bi * 32 * 16);
-                al[bi] = *reinterpret_cast<const bf16x8_t *>(sAl[buf] + a_off + bi * 32 * 16);
+                ah[bi] = *reinterpret_cast<const f16x8_t *>(sAh[buf] + a_off + bi * 32 * 16);
+                al[bi] = *reinterpret_cast<const f16x8_t *>(sAl[buf] + a_off + bi * 32 * 16);
             }
 #pragma unroll
             for (int bj = 0; bj < 2; ++bj) {
-                bh[bj] = *reinterpret_cast<const bf16x8_t *>(sBh[buf] + b_off + bj * 32 * 16);
-                bl[bj] = *reinterpret_cast<const bf16x8_t *>(sBl[buf] + b_off + bj * 32 * 16);
+                bh[bj] = *reinterpret_cast<const f16x8_t *>(sBh[buf] + b_off + bj * 32 * 16);
+                bl[bj] = *reinterpret_cast<const f16x8_t *>(sBl[buf] + b_off + bj * 32 * 16);
             }
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
                 for (int bj = 0; bj < 2; ++bj) {
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[bi], bh[bj], acc[bi][bj], 0, 0, 0);
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[bi], bl[bj], acc[bi][bj], 0, 0, 0);
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[bi], bh[bj], acc[bi][bj], 0, 0, 0);
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[bi], bh[bj], acc[bi][bj], 0, 0, 0);
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[bi], bl[bj], acc[bi][bj], 0, 0, 0);
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[bi], bh[bj], acc[bi][bj], 0, 0, 0);
                 }
         };
 

@@ -9,6 +9,8 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "common.h"
@@ -416,12 +418,6 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 constexpr int kSelThreads = 512;            // rows of up to kSelSmallRow distances
 constexpr int kSelThreadsLong = 1024;       // longer rows: the sweeps over the row are what the selection costs there
 constexpr int kSelSmallRow = 8192;          // (measured: 1024 threads are 8 us faster at 16,384 lists and 4 us slower at 4,096)
-#ifdef PIPERAG_TRACE
-__device__ unsigned long long d_sel_trace[4096 * 8];
-#define SEL_MARK(j) do { if (threadIdx.x == 0) d_sel_trace[blockIdx.x * 8 + (j)] = wall_clock64(); } while (0)
-#else
-#define SEL_MARK(j) do {} while (0)
-#endif
 constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
 constexpr int kSelGroups = 4 * kSelThreadsLong;   // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
 constexpr int kSelCand = 4096;              // ... and room for the keys collected under it
@@ -445,7 +441,6 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
     __shared__ unsigned s_count, s_ncand;
     __shared__ float s_qpart[NT / kWave];
     const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
-    SEL_MARK(0);
     float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
     const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
@@ -517,7 +512,6 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
         row = s_row;
     }
     __syncthreads();
-    SEL_MARK(1);
     auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
     // Rows too long for LDS are cut down first, in two sweeps over global memory with sixteen loads in flight per
     // thread: the centres are dealt to kSelGroups groups (centre i to group i mod kSelGroups) and every group
@@ -599,14 +593,12 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
         }
     }
     __syncthreads();
-    SEL_MARK(2);
     if (np2 <= kWave) {                                      // uniform: up to 64 probes are sorted in the registers of one wave
         if (tid < kWave) wave_sort_u64(s_keys, np2);
         __syncthreads();
     } else {
         block_bitonic_sort_u64(s_keys, np2);
     }
-    SEL_MARK(3);
     for (int i = tid; i < nprobe; i += NT) {
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
         probe_d[(size_t)qi * probe_stride + i] = __uint_as_float((uint32_t)(s_keys[i] >> 32));
@@ -616,7 +608,6 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
     if (mine.pcst)                                           // |q - c|^2 - |q|^2 = |c|^2 - 2 <q, c>
         for (int i = tid; i < nprobe; i += NT) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
     plan_query(probe_at, nprobe, list_blk, list_len, mine);
-    SEL_MARK(4);
     // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
     // workgroup publishes its query's number of blocks with a device-scope store, waits for it to complete and
     // adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
@@ -627,12 +618,10 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
         s_ticket = atomicAdd(arrived, 1u);
     }
     __syncthreads();
-    SEL_MARK(5);
     if (s_ticket != gridDim.x - 1) return;                  // uniform
     auto blocks_of = [&](int q) { return (long long)__hip_atomic_load(&tb[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
     share_plan(blocks_of, (int)gridDim.x, target, max_wg, share);
     if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    SEL_MARK(6);
 }
 
 // Probe lists given by the caller: entries outside 0..nlist-1 and repeats of an earlier entry become -1
@@ -684,10 +673,6 @@ struct ScanArgs {
     const int64_t *ids;
     float *out_d;
     int64_t *out_i;
-#ifdef PIPERAG_TRACE
-    unsigned long long *trace;   // [workgroups][8] timestamps
-    int flags;                   // experiments: 1 = no appends, 2 = no table lookups
-#endif
 };
 
 typedef const __attribute__((address_space(3))) float *lds_cfptr;
@@ -1034,20 +1019,6 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
     }
 }
 
-// Tap: the tables in canonical layout out[(q*M + m)*256 + j].
-__global__ __launch_bounds__(256) void lut_tap_kernel(const float *__restrict__ q, const float *__restrict__ pq, int d, int M,
-                                                      int dsub, float *__restrict__ out) {
-    const int qi = blockIdx.y, m = blockIdx.x, j = threadIdx.x;
-    const float *qs = q + (size_t)qi * d + m * dsub;
-    const float *c = pq + ((size_t)m * kKsub + j) * dsub;
-    float acc = 0.f;
-    for (int t = 0; t < dsub; ++t) {
-        const float diff = qs[t] - c[t];
-        acc += diff * diff;
-    }
-    out[((size_t)qi * M + m) * kKsub + j] = acc;
-}
-
 // Keys that one workgroup writes and another reads within the same launch go through device-scope atomic
 // stores and loads (they bypass the per-XCD caching that is not coherent across the chip), ordered by
 // publish_keys(): wait until this thread's stores are acknowledged, then meet the workgroup; a counter
@@ -1061,12 +1032,6 @@ __device__ __forceinline__ void publish_keys() {
     __syncthreads();
 }
 
-#ifdef PIPERAG_TRACE
-__device__ unsigned long long d_fin_trace[4096 * 8];
-#define FIN_MARK(j) do { if (threadIdx.x == 0) d_fin_trace[blockIdx.x * 8 + (j)] = wall_clock64(); } while (0)
-#else
-#define FIN_MARK(j) do {} while (0)
-#endif
 // Selection from a key list by one workgroup: the k smallest of the keys in list[0..n) (global memory, written by
 // this and other workgroups, all different).  Up to `room` keys are gathered into s_keys first (those within
 // `bound`, which at least k keys are if k exist) and selected there; a longer list is selected in place, one
@@ -1082,7 +1047,6 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
                                  int64_t *__restrict__ out_i, uint64_t *__restrict__ dst, int KW) {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
-    FIN_MARK(0);
     if (FINAL)
         for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
     if (tid == 0) *s_count = 0;
@@ -1109,10 +1073,8 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         __syncthreads();
     }
     auto key_at = [&](int i) { return in_lds ? s_keys[i] : load_key(list + i); };
-    FIN_MARK(1);
     uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
     if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state);
-    FIN_MARK(2);
     if (tid == 0) *s_count = 0;
     __syncthreads();
     for (int i = tid; i < found; i += nt) {
@@ -1124,7 +1086,6 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         }
     }
     __syncthreads();
-    FIN_MARK(3);
     const int cnt = (int)*s_count;
     if (!FINAL) {
         for (int i = cnt + tid; i < KW; i += nt) store_key(dst + i, kSentinel);
@@ -1174,8 +1135,6 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
             out_i[place] = s_id[tid];
         }
         for (int i = cnt + tid; i < k; i += nt) { out_d[i] = __builtin_inff(); out_i[i] = -1; }
-        FIN_MARK(4);
-        FIN_MARK(5);
         return;
     }
     for (int size = 2; size <= k2; size <<= 1) {
@@ -1193,12 +1152,10 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         }
     }
     __syncthreads();
-    FIN_MARK(4);
     for (int i = tid; i < k; i += nt) {
         out_d[i] = i < cnt ? __uint_as_float(s_d[i]) : __builtin_inff();
         out_i[i] = i < cnt ? s_id[i] : -1;
     }
-    FIN_MARK(5);
 }
 
 // Room for keys when the table and candidate areas of the scan kernel's LDS are reused for the final selection
@@ -1246,12 +1203,6 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     const int qi = desc.x;
     const bool lut_at_zero =
         reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) unsigned char *)smem) == 0;
-#ifdef PIPERAG_TRACE
-    unsigned long long *tr = a.trace + (size_t)wg * 8;
-    unsigned nflush = 0;
-    unsigned long long tflush = 0;
-    if (tid == 0) tr[0] = wall_clock64();
-#endif
     // the query's table starts on its way to LDS first (it depends on nothing else), then the probe tables
     ProbeTableRegs<kScanThreads> tables;
     load_probe_tables(a, qi, tables);
@@ -1326,14 +1277,6 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     };
     auto process = [&](const uint4 (&w)[C], const Meta &m) {
         float dist;
-#ifdef PIPERAG_TRACE
-        if (a.flags & 2) {
-            uint32_t x = 0;
-#pragma unroll
-            for (int c = 0; c < C; ++c) x += w[c].x ^ w[c].y ^ w[c].z ^ w[c].w;
-            dist = (float)(x & 0xFFFF) + 1.0f;
-        } else
-#endif
         if (C == 4 && lut_at_zero) dist = block_dist_m64(reinterpret_cast<const uint4 (&)[4]>(w), off4);
         else dist = block_dist_generic<C>(w, s.lut, lane_m);
         // residual index: the table sum is |q - p|^2 for the decoded residual p; adding 2 <c, p> (stored per vector)
@@ -1342,9 +1285,6 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         const uint32_t dbits = __float_as_uint(dist);
         const uint32_t slot = m.gblock * kBlockVecs + lane;
         bool pass = (lane < m.nvalid) && ((((uint64_t)dbits << 32) | slot) <= thr);
-#ifdef PIPERAG_TRACE
-        if (a.flags & 1) pass = false;
-#endif
         append_candidates(pass, dbits, slot, s.cand, &s.misc[0], cap, lane);
     };
 
@@ -1358,9 +1298,6 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     for (int i = 0; i < NSETS; ++i) issue(w[i], meta[i], cb + i);
     lut_copy_end<kScanThreads, MP>(a.lut + (size_t)qi * kKsub * MP, s.lut);
     __syncthreads();
-#ifdef PIPERAG_TRACE
-    if (tid == 0) tr[1] = wall_clock64();
-#endif
     // An episode is a meeting of all waves of the workgroup: every wave joins every episode (from wherever it
     // is in its loop), the two counters are read between two barriers (nobody appends in between), and the
     // buffer is pruned if it is nearly full.  A wave asks for an episode by waiting in one: when the buffer is
@@ -1372,16 +1309,9 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         const int ndone = (int)lds_peek(&s.misc[3]);
         __syncthreads();            // nobody appends again before everybody has read the two counters
         if (n > trigger) {          // uniform: all threads read the same values between the barriers
-#ifdef PIPERAG_TRACE
-            const unsigned long long tf0 = wall_clock64();
-#endif
             const uint64_t T = wg_prune(s, min(n, cap), k);
             thr = min(thr, T);
             if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
-#ifdef PIPERAG_TRACE
-            tflush += wall_clock64() - tf0;
-            ++nflush;
-#endif
         }
         return ndone;
     };
@@ -1414,18 +1344,12 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // out of blocks: tell the others, and keep joining their episodes until every wave is out of blocks
     if (lane == 0) atomicAdd(&s.misc[3], 1u);
     while (episode() != kScanWaves) {}
-#ifdef PIPERAG_TRACE
-    if (tid == 0) { tr[2] = wall_clock64(); tr[5] = nflush; tr[6] = (unsigned long long)TB; tr[7] = tflush; }
-#endif
     int n = min((int)lds_peek(&s.misc[0]), cap);
     if (n > KW) {                   // uniform
         const uint64_t T = wg_prune(s, n, k);
         if (tid == 0) atomicMin(&a.thr[qi], (uint32_t)(T >> 32));
         n = (int)lds_peek(&s.misc[0]);
     }
-#ifdef PIPERAG_TRACE
-    if (tid == 0) tr[3] = wall_clock64();
-#endif
     // What the workgroup still holds goes to its KW slots (padded with kSentinel) of a key list: the query's, or,
     // when the query has more workgroups than one selection can take in LDS (fan), the list of its group of fan
     // consecutive workgroups.  The keys are written before the workgroup adds itself to the count of finished
@@ -1440,15 +1364,9 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     uint32_t *ldone = R == 1 ? &a.qdone[qi] : &a.gdone[wg0 + r];
     uint64_t *mine = list + (size_t)(seg - r * fan) * KW;
     for (int i = tid; i < KW; i += kScanThreads) store_key(mine + i, i < n ? s.cand[i] : kSentinel);
-#ifdef PIPERAG_TRACE
-    if (tid == 0) tr[4] = wall_clock64();
-#endif
     publish_keys();
     if (tid == 0) s.misc[4] = atomicAdd(ldone, 1u);
     __syncthreads();
-#ifdef PIPERAG_TRACE
-    if (tid == 0 && (a.flags & 4)) tr[5] = wall_clock64();
-#endif
     if (s.misc[4] != (unsigned)(gsize - 1)) return;              // uniform
     // the last workgroup of the list: selection in the LDS that held table and candidates
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
@@ -1461,17 +1379,11 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     if (R == 1) {
         select_from_list<true>(list, S * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], a.ids, s_d, s_id, res_d, res_i,
                                nullptr, KW);
-#ifdef PIPERAG_TRACE
-        if (tid == 0 && (a.flags & 4)) tr[6] = wall_clock64();
-#endif
         return;
     }
     uint64_t *list2 = a.part2 + (size_t)wg0 * KW;                // the query's list: KW slots per group
     select_from_list<false>(list, gsize * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], nullptr, nullptr, nullptr,
                             nullptr, nullptr, list2 + (size_t)r * KW, KW);
-#ifdef PIPERAG_TRACE
-    if (tid == 0 && (a.flags & 4)) tr[6] = wall_clock64();
-#endif
     publish_keys();
     if (tid == 0) s.misc[4] = atomicAdd(&a.qdone[qi], 1u);
     __syncthreads();
@@ -1479,43 +1391,36 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     bound = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     select_from_list<true>(list2, R * KW, a.room, k, bound, s_keys, s.hist, s.state, &s.misc[0], a.ids, s_d, s_id, res_d, res_i,
                            nullptr, KW);
-#ifdef PIPERAG_TRACE
-    if (tid == 0 && (a.flags & 4)) tr[7] = wall_clock64();
-#endif
 }
 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 template <int DSUB>
-void launch_lut_build_d(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
+void launch_lut_build_d(const piperag_index *ix, const float *q, int nq, float *lut, hipStream_t st) {
     hipLaunchKernelGGL((lut_build_kernel<DSUB>), dim3(4, nq), dim3(256), sizeof(float) * ix->p.d, st, q, ix->pqT, ix->p.d, ix->p.M,
-                       ix->dsub, ix->Mp, ix->ws_lut);
+                       ix->dsub, ix->Mp, lut);
 }
 
-void launch_lut_build(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
+void launch_lut_build(const piperag_index *ix, const float *q, int nq, float *lut, hipStream_t st) {
     switch (ix->dsub) {                      // common slice widths get their loads unrolled at compile time
-        case 4: launch_lut_build_d<4>(ix, q, nq, st); break;
-        case 6: launch_lut_build_d<6>(ix, q, nq, st); break;
-        case 8: launch_lut_build_d<8>(ix, q, nq, st); break;
-        case 12: launch_lut_build_d<12>(ix, q, nq, st); break;
-        case 16: launch_lut_build_d<16>(ix, q, nq, st); break;
-        default: launch_lut_build_d<0>(ix, q, nq, st); break;
+        case 4: launch_lut_build_d<4>(ix, q, nq, lut, st); break;
+        case 6: launch_lut_build_d<6>(ix, q, nq, lut, st); break;
+        case 8: launch_lut_build_d<8>(ix, q, nq, lut, st); break;
+        case 12: launch_lut_build_d<12>(ix, q, nq, lut, st); break;
+        case 16: launch_lut_build_d<16>(ix, q, nq, lut, st); break;
+        default: launch_lut_build_d<0>(ix, q, nq, lut, st); break;
     }
 }
+
+// code blocks in flight per wave: as many as fit without register spills (the residual variant holds one more
+// value per lane and block)
+template <int C, bool RES>
+constexpr int scan_nsets() { return C <= (RES ? 3 : 4) ? 4 : (C <= 6 ? 2 : 1); }
 
 template <int C, bool RES, bool STREAM>
 int launch_scan_rs(const ScanArgs &a, int G, size_t lds, hipStream_t st) {
-    // code blocks in flight per wave: as many as fit without register spills (the residual variant holds one more
-    // value per lane and block)
-    constexpr int NSETS = C <= (RES ? 3 : 4) ? 4 : (C <= 6 ? 2 : 1);
-    static size_t configured = 0;
-    if (lds > configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&adc_scan_kernel<C, NSETS, RES, STREAM>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
-    }
-    hipLaunchKernelGGL((adc_scan_kernel<C, NSETS, RES, STREAM>), dim3(G), dim3(kScanThreads), lds, st, a);
+    hipLaunchKernelGGL((adc_scan_kernel<C, scan_nsets<C, RES>(), RES, STREAM>), dim3(G), dim3(kScanThreads), lds, st, a);
     return PIPERAG_OK;
 }
 template <int C>
@@ -1537,12 +1442,30 @@ int launch_scan(const ScanArgs &a, bool stream, int G, size_t lds, hipStream_t s
         default: PR_REQUIRE(false, PIPERAG_ERR_ARG, "unsupported M");           \
     }
 
-PlanOut plan_bufs(const piperag_index *ix) {
-    return PlanOut{ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->ws_scanned, ix->ws_thr, ix->p.residual ? ix->ws_pcst : nullptr,
-                   ix->ws_done};
+// Kernels that may need more dynamic LDS than the default limit get the device's whole 160 KiB allowed.
+constexpr int kMaxLds = 160 * 1024;
+template <class K>
+hipError_t allow_lds(K kernel) {            // whatever the kernel's static LDS leaves of the 160 KiB
+    hipFuncAttributes fa;
+    const hipError_t e = hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(kernel));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kMaxLds - (int)fa.sharedSizeBytes);
+}
+template <int C>
+hipError_t allow_lds_scan() {
+    hipError_t e = allow_lds(&adc_scan_kernel<C, scan_nsets<C, false>(), false, false>);
+    if (e == hipSuccess) e = allow_lds(&adc_scan_kernel<C, scan_nsets<C, false>(), false, true>);
+    if (e == hipSuccess) e = allow_lds(&adc_scan_kernel<C, scan_nsets<C, true>(), true, false>);
+    if (e == hipSuccess) e = allow_lds(&adc_scan_kernel<C, scan_nsets<C, true>(), true, true>);
+    return e;
 }
 
-ShareOut share_bufs(const piperag_index *ix) { return ShareOut{ix->ws_seg0, ix->ws_desc, ix->ws_ctr, ix->ws_done + ix->p.max_nq}; }
+PlanOut plan_bufs(const piperag_index *ix, const SearchWs &ws) {
+    return PlanOut{ws.pfx, ws.pblk, ws.plen, ws.scanned, ws.thr, ix->p.residual ? ws.pcst : nullptr, ws.done};
+}
+
+ShareOut share_bufs(const SearchWs &ws) { return ShareOut{ws.seg0, ws.desc, ws.ctr, ws.done + ws.max_nq}; }
 
 // Parts of the depth the matrix-core coarse quantiser is split into for this shape (0: the row-wise kernel
 // runs instead and writes finished distances).
@@ -1556,31 +1479,24 @@ int coarse_parts(const piperag_index *ix, const float *q, int nq) {
     return parts;
 }
 
-int launch_select(const piperag_index *ix, const float *q, int nq, int nprobe, int target, int max_wg, hipStream_t st) {
+int launch_select(const piperag_index *ix, const SearchWs &ws, const float *q, int nq, int nprobe, int target, int max_wg,
+                  hipStream_t st) {
     const int nlist = ix->p.nlist;
     const int stage = nlist <= kSelMaxLdsRow;
     const size_t lds = stage ? sizeof(float) * (size_t)nlist : sizeof(uint64_t) * (kSelGroups + kSelCand);
-    static bool configured = false;
-    if (!configured) {
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel<kSelThreads>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kSelMaxLdsRow)));
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&select_probes_kernel<kSelThreadsLong>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kSelMaxLdsRow)));
-        configured = true;
-    }
     if (nlist <= kSelSmallRow)
-        hipLaunchKernelGGL(select_probes_kernel<kSelThreads>, dim3(nq), dim3(kSelThreads), lds, st, ix->ws_D, coarse_parts(ix, q, nq),
-                           q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d, ix->p.max_nprobe, ix->list_blk,
-                           ix->list_len, plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target, max_wg, share_bufs(ix));
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreads>, dim3(nq), dim3(kSelThreads), lds, st, ws.D, coarse_parts(ix, q, nq),
+                           q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ws.probe, ws.probe_d, ws.max_nprobe, ix->list_blk,
+                           ix->list_len, plan_bufs(ix, ws), ws.tb, ws.tb + ws.max_nq, target, max_wg, share_bufs(ws));
     else
-        hipLaunchKernelGGL(select_probes_kernel<kSelThreadsLong>, dim3(nq), dim3(kSelThreadsLong), lds, st, ix->ws_D,
-                           coarse_parts(ix, q, nq), q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ix->ws_probe, ix->ws_probe_d,
-                           ix->p.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix), ix->ws_tb, ix->ws_tb + ix->p.max_nq, target,
-                           max_wg, share_bufs(ix));
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreadsLong>, dim3(nq), dim3(kSelThreadsLong), lds, st, ws.D,
+                           coarse_parts(ix, q, nq), q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ws.probe, ws.probe_d,
+                           ws.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix, ws), ws.tb, ws.tb + ws.max_nq, target,
+                           max_wg, share_bufs(ws));
     return PIPERAG_OK;
 }
 
-int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t st) {
+int launch_coarse(const piperag_index *ix, const SearchWs &ws, const float *q, int nq, hipStream_t st) {
     constexpr int QT = 4;
     const int d = ix->p.d, nlist = ix->p.nlist;
     const int parts = coarse_parts(ix, q, nq);
@@ -1588,7 +1504,7 @@ int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t s
         const int dper = (d / parts + 31) / 32 * 32;
         hipLaunchKernelGGL(coarse_mfma_kernel, dim3((nlist + CoarseTile::kRowsB - 1) / CoarseTile::kRowsB,
                                                     (nq + CoarseTile::kRowsA - 1) / CoarseTile::kRowsA, parts),
-                           dim3(256), 0, st, q, nq, ix->centroids, nlist, d, dper, ix->ws_D);
+                           dim3(256), 0, st, q, nq, ix->centroids, nlist, d, dper, ws.D);
         return PIPERAG_OK;
     }
     // one query (the serving case) gets a kernel of its own: a quarter of the lookups and lane reductions
@@ -1596,34 +1512,16 @@ int launch_coarse(const piperag_index *ix, const float *q, int nq, hipStream_t s
     const int groups = std::min((nlist + 15) / 16, 2048);   // a workgroup's 4 waves take 4 centres each per turn
     const dim3 grid(groups, (nq + QTr - 1) / QTr);
     const size_t lds = sizeof(float) * QTr * d;
-    static size_t configured = 48 * 1024;
-    if (sizeof(float) * QT * d > configured) {
-        const int want = (int)(sizeof(float) * QT * d);
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 4, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<QT, 1, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<1, 4, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
-        PR_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_rowwise_kernel<1, 1, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, want));
-        configured = want;
-    }
     if (d % 4 == 0 && QTr == 1)
-        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ws.D, nq, nlist, d);
     else if (d % 4 == 0)
-        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 4, 4>), grid, dim3(256), lds, st, q, ix->centroids, ws.D, nq, nlist, d);
     else if (QTr == 1)
-        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+        hipLaunchKernelGGL((coarse_rowwise_kernel<1, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ws.D, nq, nlist, d);
     else
-        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ix->ws_D, nq, nlist, d);
+        hipLaunchKernelGGL((coarse_rowwise_kernel<QT, 1, 4>), grid, dim3(256), lds, st, q, ix->centroids, ws.D, nq, nlist, d);
     return PIPERAG_OK;
 }
-
-#ifdef PIPERAG_TRACE
-unsigned long long *g_trace_buf = nullptr;
-int g_trace_n = 0;
-#endif
 
 int check_search_args(const piperag_index *ix, const void *q, int32_t nq, int32_t nprobe, int32_t k, const void *od,
                       const void *oi) {
@@ -1632,59 +1530,58 @@ int check_search_args(const piperag_index *ix, const void *q, int32_t nq, int32_
     PR_REQUIRE(nq >= 0, PIPERAG_ERR_ARG, "nq = %d is negative", nq);
     if (nq == 0) return PIPERAG_OK;
     PR_REQUIRE(q && od && oi, PIPERAG_ERR_ARG, "queries / output pointer is NULL");
-    PR_REQUIRE(nq <= ix->p.max_nq, PIPERAG_ERR_LIMIT, "nq = %d exceeds max_nq = %d", nq, ix->p.max_nq);
     PR_REQUIRE(nprobe >= 1 && k >= 1, PIPERAG_ERR_ARG, "nprobe = %d and k = %d must be >= 1", nprobe, k);
     PR_REQUIRE(nprobe <= ix->p.nlist, PIPERAG_ERR_ARG, "nprobe = %d exceeds nlist = %d", nprobe, ix->p.nlist);
+    return PIPERAG_OK;
+}
+int check_search_limits(const piperag_index *ix, int32_t nq, int32_t nprobe, int32_t k) {
+    PR_REQUIRE(nq <= ix->p.max_nq, PIPERAG_ERR_LIMIT, "nq = %d exceeds max_nq = %d", nq, ix->p.max_nq);
     PR_REQUIRE(nprobe <= ix->p.max_nprobe, PIPERAG_ERR_LIMIT, "nprobe = %d exceeds max_nprobe = %d", nprobe, ix->p.max_nprobe);
     PR_REQUIRE(k <= ix->p.max_k, PIPERAG_ERR_LIMIT, "k = %d exceeds max_k = %d", k, ix->p.max_k);
     return PIPERAG_OK;
 }
 
-// Enqueues one search on st (kernel launches and event operations only: it can be captured into a graph).
-int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t *probes, int32_t nprobe, int32_t k, float *out_d,
-                   int64_t *out_i, hipStream_t st) {
+// Scan workgroups a search call asks the plan for: two per compute unit, or for large batches about 8 per query.
+int scan_target_wgs(int nq) { return std::min(kMaxScanWGs, std::max(kTargetScanWGs, 8 * nq)); }
+
+// Enqueues one search on st, with `ws` as its scratch (kernel launches and event operations only: it can be
+// captured into a graph).  fork: the tables are built on the index's side stream beside the selection;
+// otherwise on st itself (no events of the index are touched, and stage timing is not recorded).
+int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool fork, const float *q, int32_t nq, const int32_t *probes,
+                   int32_t nprobe, int32_t k, float *out_d, int64_t *out_i, hipStream_t st) {
     int rc = PIPERAG_OK;
-    const int pstride = ix->p.max_nprobe;
-    const bool tm = ix->timing;
+    const int pstride = ws.max_nprobe;
+    const bool tm = ix->timing && fork;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
     // The coarse quantiser is enqueued first (the whole call waits for it); then the fork: the tables need only the
     // queries and are built on the side stream beside the selection.
-    if (!probes && (rc = launch_coarse(ix, q, nq, st)) != PIPERAG_OK) return rc;
+    if (!probes && (rc = launch_coarse(ix, ws, q, nq, st)) != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
-    PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));
-    PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
-    launch_lut_build(ix, q, nq, ix->side);
-    PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
-    static const int wgs_override = [] {                    // tuning override, read once
-        const char *e = getenv("PIPERAG_SCAN_WGS");
-        const int v = e ? atoi(e) : 0;
-        return v > 0 && v <= kMaxScanWGs ? v : 0;
-    }();
-    const int target_wgs = wgs_override ? wgs_override : std::min(kMaxScanWGs, std::max(kTargetScanWGs, 8 * nq));
+    if (fork) {
+        PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));
+        PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+        launch_lut_build(ix, q, nq, ws.lut, ix->side);
+        PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
+    } else {
+        launch_lut_build(ix, q, nq, ws.lut, st);
+    }
+    const int target_wgs = scan_target_wgs(nq);
     const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
     if (!probes) {
-        if ((rc = launch_select(ix, q, nq, nprobe, target_wgs, G, st)) != PIPERAG_OK) return rc;
+        if ((rc = launch_select(ix, ws, q, nq, nprobe, target_wgs, G, st)) != PIPERAG_OK) return rc;
     } else {
-        hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ix->ws_probe, pstride,
-                           ix->list_blk, ix->list_len, plan_bufs(ix));
-        hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ix->ws_pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ix));
+        hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ws.probe, pstride,
+                           ix->list_blk, ix->list_len, plan_bufs(ix, ws));
+        hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ws.pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ws));
         if (ix->p.residual)
             hipLaunchKernelGGL(probe_const_kernel, dim3(nprobe, nq), dim3(64), 0, st, q, ix->centroids, ix->cnorm, ix->p.d,
-                               ix->ws_probe, pstride, ix->ws_pcst);
+                               ws.probe, pstride, ws.pcst);
     }
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
-    ScanArgs a{ix->codes, ix->ws_lut, ix->ws_pfx, ix->ws_pblk, ix->ws_plen, ix->p.residual ? ix->ws_pcst : nullptr,
-               ix->p.residual ? ix->tx : nullptr, ix->ws_part, ix->ws_thr, ix->ws_desc, ix->ws_ctr, nprobe, pstride, k, KW};
-#ifdef PIPERAG_TRACE
-    static unsigned long long *trace_buf = nullptr;
-    if (!trace_buf) PR_CHECK_HIP(hipMalloc((void **)&trace_buf, 8 * sizeof(unsigned long long) * 8192));
-    PR_CHECK_HIP(hipMemsetAsync(trace_buf, 0, 8 * sizeof(unsigned long long) * 8192, st));
-    a.trace = trace_buf;
-    { const char *e = getenv("PIPERAG_DEBUG_FLAGS"); a.flags = e ? atoi(e) : 0; }
-    g_trace_buf = trace_buf; g_trace_n = G;
-#endif
-    PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
+    ScanArgs a{ix->codes, ws.lut, ws.pfx, ws.pblk, ws.plen, ix->p.residual ? ws.pcst : nullptr,
+               ix->p.residual ? ix->tx : nullptr, ws.part, ws.thr, ws.desc, ws.ctr, nprobe, pstride, k, KW};
+    if (fork) PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
     // Candidate slots: as many as kCandRoom beyond the keys kept, but fewer if that lets two workgroups share a
     // compute unit's 160 KiB of LDS (long probe tables would otherwise push the second one out).
@@ -1695,17 +1592,17 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
     }
     a.cap = KW + room;
     // the query's last workgroup selects the results in the LDS that held its table and candidates
-    a.qdone = ix->ws_done;
+    a.qdone = ws.done;
     a.room = reduce_room_keys(ix->Mp, a.cap, k);
     // groups of workgroups whose keys fit one selection; if two levels do not cover a query's workgroups (very large
     // k with short codes), there are no groups and a long list is selected in global memory
     a.fan = std::max(1, a.room / KW);
     if ((long long)a.fan * a.fan < G) a.fan = G;
-    a.gdone = ix->ws_done + ix->p.max_nq;
-    a.part2 = ix->ws_part2;
+    a.gdone = ws.done + ws.max_nq;
+    a.part2 = ws.part2;
     a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
     const size_t lds = scan_lds_bytes(ix->Mp, a.cap, nprobe);
-    PR_REQUIRE(lds <= 160 * 1024, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
+    PR_REQUIRE(lds <= (size_t)kMaxLds, PIPERAG_ERR_LIMIT, "scan needs %zu bytes of LDS (M, k, nprobe too large together)", lds);
     // Indexes far larger than the last-level cache are streamed: nothing read now is still cached when it is needed
     // again.  Measured with 64-byte codes: +4 % to +6 % at 16 GiB and 64 GiB of codes in 65,536 lists (0.25 and 1 MiB
     // per list on average) for 1 to 256 queries; but -4 % for batches of 8 and 64 queries on 192 GB of codes in 16,384
@@ -1726,14 +1623,17 @@ int enqueue_search(piperag_index *ix, const float *q, int32_t nq, const int32_t 
 // captured into a graph the second time it is seen and replayed with one launch from then on (measured: 8 us
 // less per waited-for call, but 10 us more per call in a back-to-back loop, hence opt-in).  The graph holds
 // only kernel nodes and the fork / join of the table build.  Stage timing keeps the plain path.
-int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int32_t *probes, int32_t nprobe, int32_t k,
+// The index is const for the caller: what a search changes is its workspace in device memory and the members
+// declared mutable (statistics, event state, graph cache).
+int search_impl(const piperag_index *ix, const float *q, int32_t nq, const int32_t *probes, int32_t nprobe, int32_t k,
                 float *out_d, int64_t *out_i, hipStream_t st) {
-    piperag_index *ix = const_cast<piperag_index *>(cix);   // workspace, timing state and graph cache are mutable
     int rc = check_search_args(ix, q, nq, nprobe, k, out_d, out_i);
     if (rc != PIPERAG_OK || nq == 0) return rc;
+    if ((rc = check_search_limits(ix, nq, nprobe, k)) != PIPERAG_OK) return rc;
     PR_CHECK_HIP(hipSetDevice(ix->device));
     ix->last_nq = nq;
-    if (ix->timing || !ix->replay) return enqueue_search(ix, q, nq, probes, nprobe, k, out_d, out_i, st);
+    ix->last_scanned = ix->ws.scanned;
+    if (ix->timing || !ix->replay) return enqueue_search(ix, ix->ws, true, q, nq, probes, nprobe, k, out_d, out_i, st);
     SearchGraph *slot = nullptr, *oldest = &ix->graphs[0];
     for (SearchGraph &g : ix->graphs) {
         if (g.seen && g.q == q && g.probes == probes && g.nq == nq && g.nprobe == nprobe && g.k == k && g.out_d == out_d &&
@@ -1744,13 +1644,13 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     if (!slot) {                                            // first time: remember the call, run it plainly
         if (oldest->exec) { (void)hipGraphExecDestroy(oldest->exec); }
         *oldest = SearchGraph{q, probes, nq, nprobe, k, out_d, out_i, nullptr, ++ix->graph_clock, 1};
-        return enqueue_search(ix, q, nq, probes, nprobe, k, out_d, out_i, st);
+        return enqueue_search(ix, ix->ws, true, q, nq, probes, nprobe, k, out_d, out_i, st);
     }
     slot->stamp = ++ix->graph_clock;
     if (!slot->exec) {                                      // second time: capture
         hipGraph_t graph = nullptr;
         PR_CHECK_HIP(hipStreamBeginCapture(ix->cap_stream, hipStreamCaptureModeRelaxed));
-        rc = enqueue_search(ix, q, nq, probes, nprobe, k, out_d, out_i, ix->cap_stream);
+        rc = enqueue_search(ix, ix->ws, true, q, nq, probes, nprobe, k, out_d, out_i, ix->cap_stream);
         const hipError_t e = hipStreamEndCapture(ix->cap_stream, &graph);
         if (rc != PIPERAG_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
         if (e != hipSuccess || !graph) { set_error("graph capture failed: %s", hipGetErrorString(e)); return PIPERAG_ERR_HIP; }
@@ -1762,7 +1662,70 @@ int search_impl(const piperag_index *cix, const float *q, int32_t nq, const int3
     return PIPERAG_OK;
 }
 
+// lut[q][j][Mp] (the scan's layout) -> out[q][m][j] (canonical), m < M.
+__global__ __launch_bounds__(256) void lut_canonical_kernel(const float *__restrict__ lut, int M, int Mp, float *__restrict__ out) {
+    const int qi = blockIdx.y, m = blockIdx.x, j = threadIdx.x;
+    out[((size_t)qi * M + m) * kKsub + j] = lut[((size_t)qi * kKsub + j) * Mp + m];
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_dev_mutex;
+bool g_search_configured[kMaxDevices];
+
 }  // namespace
+
+namespace piperag {
+
+size_t search_ws_layout(SearchWs *ws, void *base, int nlist, int Mp, int max_nq, int max_nprobe, int max_k, int max_wgs) {
+    unsigned char *b = static_cast<unsigned char *>(base);
+    size_t off = 0;
+    const size_t nq = (size_t)max_nq, np = (size_t)max_nprobe, wgs = (size_t)max_wgs;
+    auto take = [&](auto **field, size_t count) {            // every array starts on a 256-byte boundary
+        using T = std::remove_reference_t<decltype(**field)>;
+        *field = b ? reinterpret_cast<T *>(b + off) : nullptr;
+        off = (off + count * sizeof(T) + 255) / 256 * 256;
+    };
+    take(&ws->D, nq * nlist * (nlist <= kCoarseSplitMaxLists ? kCoarseMaxParts : 1));
+    take(&ws->probe, nq * np);
+    take(&ws->probe_d, nq * np);
+    take(&ws->pfx, nq * (np + 1));
+    take(&ws->scanned, nq);
+    take(&ws->seg0, nq + 1);
+    take(&ws->desc, wgs + nq);
+    take(&ws->done, wgs + 2 * nq);
+    take(&ws->tb, nq + 1);
+    take(&ws->ctr, nq * kCtrPerQuery * kCtrStride);
+    take(&ws->pcst, nq * np);
+    take(&ws->pblk, nq * np);
+    take(&ws->plen, nq * np);
+    take(&ws->thr, nq);
+    take(&ws->lut, nq * kKsub * Mp);
+    take(&ws->part, (wgs + 2 * nq) * ((size_t)max_k + kKeepSlack));
+    take(&ws->part2, (wgs + 2 * nq) * ((size_t)max_k + kKeepSlack));
+    ws->max_nq = max_nq; ws->max_nprobe = max_nprobe; ws->max_k = max_k;
+    return off;
+}
+
+int configure_search_kernels(int device) {
+    PR_REQUIRE(device >= 0 && device < kMaxDevices, PIPERAG_ERR_ARG, "device %d out of range", device);
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (g_search_configured[device]) return PIPERAG_OK;
+    int cur = -1;
+    PR_CHECK_HIP(hipGetDevice(&cur));
+    if (cur != device) PR_CHECK_HIP(hipSetDevice(device));
+    PR_CHECK_HIP(allow_lds_scan<1>()); PR_CHECK_HIP(allow_lds_scan<2>()); PR_CHECK_HIP(allow_lds_scan<3>());
+    PR_CHECK_HIP(allow_lds_scan<4>()); PR_CHECK_HIP(allow_lds_scan<5>()); PR_CHECK_HIP(allow_lds_scan<6>());
+    PR_CHECK_HIP(allow_lds_scan<7>()); PR_CHECK_HIP(allow_lds_scan<8>());
+    PR_CHECK_HIP(allow_lds(&select_probes_kernel<kSelThreads>));
+    PR_CHECK_HIP(allow_lds(&select_probes_kernel<kSelThreadsLong>));
+    PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<4, 4, 4>)); PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<4, 1, 4>));
+    PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<1, 4, 4>)); PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<1, 1, 4>));
+    g_search_configured[device] = true;
+    if (cur != device && cur >= 0) PR_CHECK_HIP(hipSetDevice(cur));
+    return PIPERAG_OK;
+}
+
+}  // namespace piperag
 
 // ------------------------------------------------------------------------------------------------
 // C ABI
@@ -1782,7 +1745,7 @@ int piperag_ivfpq_search_probes(const piperag_index *index, const float *queries
 
 int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
                        int32_t *out_lists_dev, float *out_dist_dev, void *stream) {
-    piperag_index *ix = const_cast<piperag_index *>(index);
+    const piperag_index *ix = index;
     PR_REQUIRE(ix != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     PR_REQUIRE(nq >= 0, PIPERAG_ERR_ARG, "nq = %d is negative", nq);
     if (nq == 0) return PIPERAG_OK;
@@ -1792,14 +1755,15 @@ int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int
     PR_REQUIRE(nprobe <= ix->p.max_nprobe, PIPERAG_ERR_LIMIT, "nprobe = %d exceeds max_nprobe = %d", nprobe, ix->p.max_nprobe);
     hipStream_t st = (hipStream_t)stream;
     PR_CHECK_HIP(hipSetDevice(ix->device));
-    const int rc = launch_coarse(ix, queries_dev, nq, st);
+    const SearchWs &ws = ix->ws;
+    const int rc = launch_coarse(ix, ws, queries_dev, nq, st);
     if (rc != PIPERAG_OK) return rc;
-    const int rc2 = launch_select(ix, queries_dev, nq, nprobe, kTargetScanWGs, std::max(kTargetScanWGs, (int)nq), st);
+    const int rc2 = launch_select(ix, ws, queries_dev, nq, nprobe, kTargetScanWGs, std::max(kTargetScanWGs, (int)nq), st);
     if (rc2 != PIPERAG_OK) return rc2;
-    PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ix->ws_probe, sizeof(int32_t) * ix->p.max_nprobe,
+    PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ws.probe, sizeof(int32_t) * ws.max_nprobe,
                                   sizeof(int32_t) * nprobe, nq, hipMemcpyDeviceToDevice, st));
     if (out_dist_dev)
-        PR_CHECK_HIP(hipMemcpy2DAsync(out_dist_dev, sizeof(float) * nprobe, ix->ws_probe_d, sizeof(float) * ix->p.max_nprobe,
+        PR_CHECK_HIP(hipMemcpy2DAsync(out_dist_dev, sizeof(float) * nprobe, ws.probe_d, sizeof(float) * ws.max_nprobe,
                                       sizeof(float) * nprobe, nq, hipMemcpyDeviceToDevice, st));
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
@@ -1810,33 +1774,22 @@ int piperag_ivf_lut(const piperag_index *index, const float *queries_dev, int32_
     PR_REQUIRE(nq >= 0, PIPERAG_ERR_ARG, "nq = %d is negative", nq);
     if (nq == 0) return PIPERAG_OK;
     PR_REQUIRE(queries_dev && out_lut_dev, PIPERAG_ERR_ARG, "queries / output pointer is NULL");
+    PR_REQUIRE(nq <= index->p.max_nq, PIPERAG_ERR_LIMIT, "nq = %d exceeds max_nq = %d", nq, index->p.max_nq);
     PR_CHECK_HIP(hipSetDevice(index->device));
-    hipLaunchKernelGGL(lut_tap_kernel, dim3(index->p.M, nq), dim3(256), 0, (hipStream_t)stream, queries_dev, index->pq,
-                       index->p.d, index->p.M, index->dsub, out_lut_dev);
+    // the tables exactly as a search builds them (same kernel, same workspace), then rearranged for the caller
+    launch_lut_build(index, queries_dev, nq, index->ws.lut, (hipStream_t)stream);
+    hipLaunchKernelGGL(lut_canonical_kernel, dim3(index->p.M, nq), dim3(kKsub), 0, (hipStream_t)stream, index->ws.lut, index->p.M,
+                       index->Mp, out_lut_dev);
     PR_CHECK_HIP(hipGetLastError());
     return PIPERAG_OK;
 }
 
-#ifdef PIPERAG_TRACE
-__attribute__((visibility("default"))) int piperag_debug_fin_trace(unsigned long long *out_host, int nwg) {
-    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(d_fin_trace), sizeof(unsigned long long) * 8 * nwg) == hipSuccess ? 0 : -1;
-}
-__attribute__((visibility("default"))) int piperag_debug_sel_trace(unsigned long long *out_host, int nwg) {
-    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(d_sel_trace), sizeof(unsigned long long) * 8 * nwg) == hipSuccess ? 0 : -1;
-}
-__attribute__((visibility("default"))) int piperag_debug_trace(unsigned long long *out_host, int max_wg) {
-    const int n = g_trace_n < max_wg ? g_trace_n : max_wg;
-    if (hipMemcpy(out_host, g_trace_buf, sizeof(unsigned long long) * 8 * n, hipMemcpyDeviceToHost) != hipSuccess) return -1;
-    return n;
-}
-#endif
-
 int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, int64_t *scanned_code_bytes) {
     PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     int64_t total = 0;
-    if (index->last_nq > 0) {
+    if (index->last_nq > 0 && index->last_scanned) {
         std::vector<int64_t> h(index->last_nq);
-        PR_CHECK_HIP(hipMemcpy(h.data(), index->ws_scanned, sizeof(int64_t) * h.size(), hipMemcpyDeviceToHost));
+        PR_CHECK_HIP(hipMemcpy(h.data(), index->last_scanned, sizeof(int64_t) * h.size(), hipMemcpyDeviceToHost));
         for (int64_t v : h) total += v;
     }
     if (scanned_vectors) *scanned_vectors = total;

@@ -117,3 +117,63 @@ def check_encoding(gpu_lists, gpu_codes, x, coarse, pq, residual=False):
             a, b = table[o_codes[i, m]], table[gpu_codes[i, m]]
             assert close(a, b), f"row {i} sub-quantiser {m}: code {gpu_codes[i, m]} vs oracle {o_codes[i, m]} ({b} vs {a})"
     return len(bad_l), len(bad_c)
+
+
+def check_lists_screened(gpu_lists, x_dev, x_host, coarse, max_cand=8, block=16384):
+    """List numbers of many rows against the oracle, at a cost that allows a million rows against 65,536 centres
+    (the plain oracle does a few hundred such rows per second).  A library matrix product on the GPU (torch, fp32;
+    harness code, not the library under test) first rules out the centres that are far from a row: those whose
+    |c|^2 - 2<x, c> exceeds the row's smallest by more than a margin of 50 times the tolerance, taken relative to
+    the distance, plus 1e-5 (|x|^2 + max |c|^2) for the product's own rounding.  The oracle (plain loops, fp64
+    accumulation) then picks the nearest of the centres left, `oracle.assign_among`; rows with more than max_cand
+    centres left go to the plain oracle over all centres.  Differences from the library's list numbers are excused
+    exactly as in check_encoding: only if the oracle's own two distances are within tolerance.
+    Returns (rows whose list differs, rows given to the plain oracle)."""
+    import torch
+    torch.backends.cuda.matmul.allow_tf32 = False
+    n = x_host.shape[0]
+    cd = torch.from_numpy(np.ascontiguousarray(coarse)).cuda()
+    cn = (cd.double() ** 2).sum(1).float()
+    cmax = float(cn.max())
+    o_lists = np.empty(n, dtype=np.int32)
+    n_full = 0
+    for a in range(0, n, block):
+        xb = x_dev[a:a + block]
+        xn = (xb.double() ** 2).sum(1).float()
+        v = cn[None, :] - 2.0 * (xb @ cd.T)
+        best = v.min(dim=1).values
+        margin = 50 * RTOL * torch.clamp(best + xn, min=0.0) + 1e-5 * (xn + cmax)
+        mask = v <= (best + margin)[:, None]
+        counts = mask.sum(1)
+        few = counts <= max_cand
+        cand = torch.full((xb.shape[0], max_cand), -1, dtype=torch.int32, device="cuda")
+        rows, cols = torch.nonzero(mask & few[:, None], as_tuple=True)            # row-major order: runs of one row
+        first = torch.zeros(xb.shape[0] + 1, dtype=torch.int64, device="cuda")
+        first[1:] = torch.cumsum(torch.where(few, counts, torch.zeros_like(counts)), 0)
+        cand[rows, (torch.arange(rows.shape[0], device="cuda") - first[rows]).long()] = cols.int()
+        few_h, cand_h = few.cpu().numpy(), cand.cpu().numpy()
+        xs = x_host[a:a + block]
+        out = np.empty(xs.shape[0], dtype=np.int32)
+        if few_h.any():
+            out[few_h] = oracle.assign_among(xs[few_h], coarse, cand_h[few_h])
+        if not few_h.all():
+            out[~few_h] = oracle.assign(xs[~few_h], coarse)
+            n_full += int((~few_h).sum())
+        o_lists[a:a + block] = out
+    bad = np.nonzero(gpu_lists != o_lists)[0]
+    for i in bad:
+        d = oracle.coarse_search(x_host[i:i + 1], coarse[[o_lists[i], gpu_lists[i]]], 2)[1][0]
+        assert close(d[0], d[1]), f"row {i}: list {gpu_lists[i]} vs oracle {o_lists[i]}, distances {d}"
+    return len(bad), n_full
+
+
+def check_codes(gpu_codes, x_host, pq):
+    """Code bytes against the plain oracle; differences only where the oracle's two table entries are within tolerance.
+    Returns the number of differing bytes."""
+    o_codes = oracle.encode_codes(x_host, pq)
+    bad = np.argwhere(gpu_codes != o_codes)
+    for i, m in bad:
+        table = oracle.lut(x_host[i:i + 1], pq)[0, m]
+        a, b = table[o_codes[i, m]], table[gpu_codes[i, m]]
+        assert close(a, b), f"row {i} sub-quantiser {m}: code {gpu_codes[i, m]} vs oracle {o_codes[i, m]} ({b} vs {a})"
+    return len(bad)

@@ -45,6 +45,8 @@ def test_counter_summary_gives_mean_min_max_per_dispatch(tmp_path):
 
 
 def test_stored_traffic_reads_the_committed_summary():
-    t = bench.stored_traffic("cfg1")
+    t, src = bench.stored_traffic("cfg1")
     assert t is not None and 1e8 < t < 1e9            # bytes per scan launch at cfg1: a few hundred MB
-    assert bench.stored_traffic("no_such_workload") is None
+    assert src.startswith("stored: profiles/adc_scan_traffic_cfg1.txt") and "not measured in this run" in src
+    t, src = bench.stored_traffic("no_such_workload")
+    assert t is None and "no stored counter summary" in src

@@ -298,6 +298,9 @@ def test_latency_profile_and_stage_times(cfg0):
     qd = dev(q[:1])
     p50, fit = ix.latency_profile(qd, [1, 2, 4, 8, 16, 32, 64], 10, reps=5)
     assert np.all(p50 > 0) and fit[0] > 0              # positive intercept: the index scan (Section 3.1, O3)
+    # the line is the least-squares fit of the returned medians (Section 3.2, S3: linear regression on nprobe)
+    slope, intercept = np.polyfit(np.array([1, 2, 4, 8, 16, 32, 64], dtype=np.float64), p50.astype(np.float64), 1)
+    assert abs(fit[1] - slope) <= 1e-4 * abs(slope) + 1e-7 and abs(fit[0] - intercept) <= 1e-4 * abs(intercept) + 1e-7
     ix.set_stage_timing(True)
     ix.ivfpq_search(qd, 8, 10)
     t = ix.stage_times()
@@ -356,6 +359,49 @@ def test_long_lists_exercise_the_in_loop_candidate_pruning():
     # one query spread over more than a hundred workgroups: their keys are merged in two levels
     run_search_parity(pkg, ix, oidx, q[:1], 4, 100)
     run_search_parity(pkg, ix, oidx, q[:2], 4, 1)
+
+
+def test_list_assignment_on_tight_clusters():
+    # Clusters 12 times tighter than the benchmark's (sigma 0.02 against centres of norm ~ sqrt(768)): the distance
+    # to the nearest centres is ~2,500 times smaller than |x||c|, which is what the rounding errors of the
+    # expanded form |c|^2 - 2<x, c> are relative to.  A 16-significant-bit product would misplace vectors here by
+    # far more than the tolerance; the shortlist product must be as accurate as fp32 and the direct-form
+    # comparison of the two shortlisted centres must settle the rest.
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(32768, 768, 1024, 64, seed=31, ncomp=64, sigma=0.02, iters=2, nq=4)
+    ix = pkg.Index.ivf_create(coarse, pq, cfg.N)
+    gl, gc = ix.ivf_encode(dev(x))
+    torch.cuda.synchronize()
+    nl, nc = parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), x, coarse, pq)
+    # how tight: the median ratio of |x||c| to the distance to the assigned centre
+    ol, od = oracle.assign(x, coarse, return_dist=True)
+    ratio = np.median(np.linalg.norm(x, axis=1) * np.linalg.norm(coarse[ol], axis=1) / np.maximum(od, 1e-30))
+    print(f"tight clusters: |x||c| / distance = {ratio:.0f} (median); {nl} list and {nc} code-byte differences, all at ties")
+    assert ratio > 1000
+    assert nl <= 8                       # all excused as ties by check_encoding, and few
+
+
+def test_cross_workgroup_merge_is_repeatable():
+    # One query spread over several hundred workgroups, merged in two levels (groups of workgroups, then the
+    # groups): the keys cross workgroups through device-scope stores ordered by a counter.  200 identical searches
+    # must each equal the first bit for bit, and the first must match the oracle; stops at the first mismatch.
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(400000, 64, 4, 64, seed=123, nq=4, sigma=0.5, ncomp=4)
+    oidx = oracle.make_index(x, coarse, pq)
+    ix = gpu_index_from_oracle(pkg, oidx, max_nq=4, max_nprobe=4, max_k=128)
+    for nq in (1, 3):
+        qd = dev(q[:nq])
+        run_search_parity(pkg, ix, oidx, q[:nq], 4, 100)
+        d0, i0 = ix.ivfpq_search(qd, 4, 100)
+        torch.cuda.synchronize()
+        d0, i0 = d0.clone(), i0.clone()
+        od = torch.empty_like(d0)
+        oi = torch.empty_like(i0)
+        for rep in range(200):
+            od.fill_(-1.0); oi.fill_(-5)
+            ix.ivfpq_search(qd, 4, 100, od, oi)
+            torch.cuda.synchronize()
+            assert torch.equal(od, d0) and torch.equal(oi, i0), f"repeat {rep} of the {nq}-query search differs from the first"
 
 
 def test_many_vectors_with_identical_codes_tie_at_the_kth_distance():
