@@ -139,6 +139,23 @@ void piperag_ivf_free(piperag_index *index);
 int piperag_ivfpq_search(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
                          int32_t k, float *out_dist_dev, int64_t *out_ids_dev, void *stream);
 
+/* For callers that cannot allocate device memory or create streams and events (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): the same search as piperag_ivfpq_search, same kernels, same
+ * results, but every intermediate (coarse distances, probe tables, lookup tables, partial results, counters)
+ * lives in a static device array of PIPERAG_STATIC_SCRATCH_BYTES that the library's code object brings with it
+ * (each GPU the library runs on holds its own copy until the process ends), and all work goes to `stream`
+ * itself (the tables are not built on a side stream).  The call allocates nothing and ignores the index's
+ * max_nq / max_nprobe / max_k: it is limited by the array instead - the scratch needed grows with nq * nlist,
+ * nq * 256 * M and (512 + 10 * nq) * (k + 64); a call that needs more returns PIPERAG_ERR_LIMIT (e.g. nq = 16,
+ * nprobe = 128, k = 100 on 65,536 lists with 64-byte codes needs 7 MiB).  The index must have been created in
+ * this process (creation sets up the array's address on the index's device).  All calls on one GPU share that
+ * GPU's array: two such calls that overlap in time on one GPU, from any streams or indexes, race; calls on one
+ * stream are safe.  piperag_search_stats afterwards reports this call.  Stage timing and graph replay do not
+ * apply. */
+#define PIPERAG_STATIC_SCRATCH_BYTES (16u << 20)
+int piperag_ivfpq_search_static(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
+                                int32_t k, float *out_dist_dev, int64_t *out_ids_dev, void *stream);
+
 /* The performance model's retrieval side (Section 3.2, S3: search latency is modelled by linear
  * regression on nprobe): runs the search above for each nprobes_host[i] (`reps` timed repetitions after
  * two warm-up runs, HIP events on `stream`), writes the median latency in milliseconds to

@@ -53,6 +53,7 @@ def load_library() -> C.CDLL:
         "piperag_ivf_place": [vp, vp, i64, vp, vp],
         "piperag_ivf_save": [vp, C.c_char_p],
         "piperag_ivfpq_search": [vp, vp, i32, i32, i32, vp, vp, vp],
+        "piperag_ivfpq_search_static": [vp, vp, i32, i32, i32, vp, vp, vp],
         "piperag_latency_profile": [vp, vp, i32, vp, i32, i32, i32, vp, vp, vp],
         "piperag_max_nprobe": [vp, C.c_float, C.c_float, i32, vp, vp, vp],
         "piperag_project_latency": [vp, vp, i32, C.c_float, C.c_float, vp, vp],
@@ -215,6 +216,12 @@ class Index:
             out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
         _check(load_library().piperag_ivfpq_search(self._h, _dev(queries, torch.float32), nq, nprobe, k,
                                                    _dev(out_dist, torch.float32), _dev(out_ids, torch.int64), _stream()))
+        return out_dist, out_ids
+
+    def ivfpq_search_static(self, queries: torch.Tensor, nprobe: int, k: int, out_dist: torch.Tensor, out_ids: torch.Tensor):
+        """piperag_ivfpq_search_static: the caller passes every buffer; nothing is allocated on either side."""
+        _check(load_library().piperag_ivfpq_search_static(self._h, _dev(queries, torch.float32), queries.shape[0], nprobe, k,
+                                                          _dev(out_dist, torch.float32), _dev(out_ids, torch.int64), _stream()))
         return out_dist, out_ids
 
     def ivfpq_search_probes(self, queries: torch.Tensor, probes: torch.Tensor, k: int):

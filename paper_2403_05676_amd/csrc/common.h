@@ -72,7 +72,8 @@ inline int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 inline int pqe_rows(int dsub) { return (dsub + 2) / 2 * 2; }
 
 // Device scratch of one search call.  Sized for (nlist, Mp, max_nq, max_nprobe, max_k) by search_ws_layout, which
-// carves it out of one block of memory; the index owns one, allocated at creation.
+// carves it out of one block of memory: the index owns one (allocated at creation), the entry point for callers
+// that cannot allocate carves another out of a static device array.
 struct SearchWs {
     float *D;             // [parts][max_nq*nlist] coarse distances, or partial inner products (parts = kCoarseMaxParts up to kCoarseSplitMaxLists lists, else 1)
     int32_t *probe;       // [max_nq*max_nprobe]
@@ -171,7 +172,7 @@ namespace piperag {
 // Carves a search workspace for the given shape out of `base` (256-byte aligned; NULL: only the size is wanted)
 // and returns the bytes it takes.
 size_t search_ws_layout(SearchWs *ws, void *base, int nlist, int Mp, int max_nq, int max_nprobe, int max_k, int max_wgs);
-// Per-device set-up of the search and encode kernels (dynamic LDS limits);
+// Per-device set-up of the search and encode kernels (dynamic LDS limits, the static scratch array's address);
 // called at index creation and by entry points that take no index.  Thread-safe.
 int configure_search_kernels(int device);
 int configure_encode_kernels(int device);

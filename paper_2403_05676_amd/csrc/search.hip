@@ -1668,11 +1668,23 @@ __global__ __launch_bounds__(256) void lut_canonical_kernel(const float *__restr
     out[((size_t)qi * M + m) * kKsub + j] = lut[((size_t)qi * kKsub + j) * Mp + m];
 }
 
+__global__ void clear_u32_kernel(uint32_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 constexpr int kMaxDevices = 64;
 std::mutex g_dev_mutex;
 bool g_search_configured[kMaxDevices];
+void *g_scratch_ptr[kMaxDevices];           // per device: address of its copy of the static scratch array
 
 }  // namespace
+
+// ---- scratch for callers that cannot allocate ---------------------------------------------------
+// One array per GPU, in the code object's own device memory, held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address that call returns (one per device, kept in
+// g_scratch_ptr) is what kernels and host calls are given.
+static __device__ __align__(256) unsigned char scratch[PIPERAG_STATIC_SCRATCH_BYTES];
 
 namespace piperag {
 
@@ -1720,6 +1732,11 @@ int configure_search_kernels(int device) {
     PR_CHECK_HIP(allow_lds(&select_probes_kernel<kSelThreadsLong>));
     PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<4, 4, 4>)); PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<4, 1, 4>));
     PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<1, 4, 4>)); PR_CHECK_HIP(allow_lds(&coarse_rowwise_kernel<1, 1, 4>));
+    // this device's copy of the static scratch array
+    void *ptr = nullptr;
+    PR_CHECK_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    PR_REQUIRE(ptr != nullptr && reinterpret_cast<uintptr_t>(ptr) % 256 == 0, PIPERAG_ERR_HIP, "static scratch array has no usable device address");
+    g_scratch_ptr[device] = ptr;
     g_search_configured[device] = true;
     if (cur != device && cur >= 0) PR_CHECK_HIP(hipSetDevice(cur));
     return PIPERAG_OK;
@@ -1741,6 +1758,36 @@ int piperag_ivfpq_search_probes(const piperag_index *index, const float *queries
                                 int32_t nprobe, int32_t k, float *out_dist_dev, int64_t *out_ids_dev, void *stream) {
     PR_REQUIRE(probes_dev != nullptr || nq == 0, PIPERAG_ERR_ARG, "probes_dev is NULL");
     return search_impl(index, queries_dev, nq, probes_dev, nprobe, k, out_dist_dev, out_ids_dev, (hipStream_t)stream);
+}
+
+int piperag_ivfpq_search_static(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe, int32_t k,
+                                float *out_dist_dev, int64_t *out_ids_dev, void *stream) {
+    int rc = check_search_args(index, queries_dev, nq, nprobe, k, out_dist_dev, out_ids_dev);
+    if (rc != PIPERAG_OK || nq == 0) return rc;
+    PR_REQUIRE(nq <= 65535 && nprobe <= kMaxNprobe && k <= kMaxK, PIPERAG_ERR_LIMIT,
+               "nq = %d, nprobe = %d, k = %d: beyond 65535 / %d / %d", nq, nprobe, k, kMaxNprobe, kMaxK);
+    PR_CHECK_HIP(hipSetDevice(index->device));
+    // the scratch is carved for exactly this call's sizes; what does not fit the static array is refused
+    SearchWs ws;
+    const int wgs = std::max(scan_target_wgs(nq), (int)nq);
+    const size_t need = search_ws_layout(&ws, nullptr, index->p.nlist, index->Mp, nq, nprobe, k, wgs);
+    PR_REQUIRE(need <= (size_t)PIPERAG_STATIC_SCRATCH_BYTES, PIPERAG_ERR_LIMIT,
+               "this search needs %zu bytes of scratch; the static scratch array holds %zu (smaller nq, nprobe or k)", need,
+               (size_t)PIPERAG_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        ptr = index->device >= 0 && index->device < kMaxDevices ? g_scratch_ptr[index->device] : nullptr;
+    }
+    PR_REQUIRE(ptr != nullptr, PIPERAG_ERR_HIP, "the static scratch array was not set up on device %d", index->device);
+    search_ws_layout(&ws, ptr, index->p.nlist, index->Mp, nq, nprobe, k, wgs);
+    hipStream_t st = (hipStream_t)stream;
+    // the array keeps the last call's contents, laid out for that call's sizes: the count of finished selections
+    // must start at zero (everything else is written before it is read)
+    hipLaunchKernelGGL(clear_u32_kernel, dim3(1), dim3(64), 0, st, ws.tb + nq, 1);
+    index->last_nq = nq;
+    index->last_scanned = ws.scanned;
+    return enqueue_search(index, ws, false, queries_dev, nq, nullptr, nprobe, k, out_dist_dev, out_ids_dev, st);
 }
 
 int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
