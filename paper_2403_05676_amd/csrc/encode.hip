@@ -455,14 +455,14 @@ __device__ __forceinline__ float unordered_bits(uint32_t o) {
     return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
 }
 
-// A workgroup takes 128 vectors against the centres of its range, 256 at a time.  The centres are the tile's A
+// A workgroup (8 waves) takes 256 vectors against the centres of its range, 256 at a time.  The centres are the tile's A
 // operand, so a lane holds, for each of its two vector columns, 64 centres of the tile in its own registers and
 // walks them in ascending centre order (a strict "<" keeps the lower index on equal values); a column's values
 // are spread over four such sources (lanes l and l + 32 of the two wave rows), which meet in LDS at the end.
 // The centres are split over R ranges of `per_range` centres (a multiple of 256); range r writes kAssignWords
 // words for row i at cand[((size_t)r * n + i) * kAssignWords].  grid = (vector tiles rounded up to a multiple of
 // 8) * R workgroups.
-__global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nchunks, const uint16_t *__restrict__ xhi,
+__global__ __launch_bounds__(F16x3Tile::kThreads, 1) void assign_f16x3_kernel(int64_t n, int nchunks, const uint16_t *__restrict__ xhi,
                                                               const uint16_t *__restrict__ xlo, int64_t x_rp,
                                                               const uint16_t *__restrict__ chi, const uint16_t *__restrict__ clo,
                                                               int64_t c_rp, const uint32_t *__restrict__ x_amax,
@@ -471,7 +471,7 @@ __global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nch
                                                               uint64_t *__restrict__ cand) {
     extern __shared__ __align__(16) unsigned char bsmem[];
     float *s_cn = reinterpret_cast<float *>(bsmem + F16x3Tile::kLdsBytes);        // [2][256] centre norms of a tile (+inf: no centre)
-    const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 7;
+    const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 8;
     // Which (vector tile, centre range) this workgroup takes.  Workgroups are dealt to the 8 XCDs in turn by
     // their launch number: the R ranges of one vector tile go to workgroups 8 apart, i.e. to one XCD and next to
     // each other in launch order, so that the tile's vectors are fetched into one L2 and found there by the
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nch
     int tile = 0;
     for (int j0 = jbeg; j0 < jend; j0 += F16x3Tile::kRowsA, ++tile) {
         float *cn = s_cn + (tile & 1) * F16x3Tile::kRowsA;     // read after the barriers inside run(); rewritten two tiles later
-        cn[tid] = j0 + tid < jend ? cnorm[j0 + tid] : inf;
+        if (tid < F16x3Tile::kRowsA) cn[tid] = j0 + tid < jend ? cnorm[j0 + tid] : inf;
         acc16_t acc[4][2];
         F16x3Tile::run(chi, clo, c_rp, j0, xhi, xlo, x_rp, row0, nchunks, bsmem, acc);
 #pragma unroll
@@ -518,7 +518,7 @@ __global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nch
             }
     }
     __syncthreads();                                           // the tile buffers are free
-    uint64_t *s_key = reinterpret_cast<uint64_t *>(bsmem);     // [128 columns][8 keys + 4 bounds]
+    uint64_t *s_key = reinterpret_cast<uint64_t *>(bsmem);     // [256 columns][8 keys + 4 bounds]
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
         const int col = F16x3Tile::acc_col(bj), src = wr * 2 + (lane >> 5);
@@ -527,7 +527,7 @@ __global__ __launch_bounds__(256, 2) void assign_f16x3_kernel(int64_t n, int nch
         s_key[col * 12 + 8 + src] = (uint64_t)ordered_bits(b3v[bj]);
     }
     __syncthreads();
-    for (int e = tid; e < F16x3Tile::kRowsB * kAssignWords; e += 256) {      // rows of this tile are contiguous in cand
+    for (int e = tid; e < F16x3Tile::kRowsB * kAssignWords; e += F16x3Tile::kThreads) {   // rows of this tile are contiguous in cand
         const int col = e / kAssignWords, w = e - col * kAssignWords;
         if (row0 + col >= n) continue;
         uint64_t word = s_key[col * 12 + w];
@@ -748,7 +748,7 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
             hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, st, nflag);
             const int64_t tiles_v = (cnt + F16x3Tile::kRowsB - 1) / F16x3Tile::kRowsB;
             const unsigned grid = (unsigned)((tiles_v + 7) / 8 * 8 * Ruse);
-            hipLaunchKernelGGL(assign_f16x3_kernel, dim3(grid), dim3(256), kBfLds, st, cnt, nchunks, xs, xs + part, rp, chi, clo, c_rp,
+            hipLaunchKernelGGL(assign_f16x3_kernel, dim3(grid), dim3(F16x3Tile::kThreads), kBfLds, st, cnt, nchunks, xs, xs + part, rp, chi, clo, c_rp,
                                x_amax, c_amax, cnorm, K, Ruse, per_range, cand);
             hipLaunchKernelGGL(assign_finish_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
                                cnorm, K, cand, Ruse, out_idx + a, out_dist ? out_dist + a : nullptr, flist, fkey, nflag);

@@ -15,9 +15,12 @@
 // rows_pad = rows rounded up to kRowPad, the number of 8-value chunks rounded up to even; padding holds zeros,
 // so the tile product needs no bounds checks.
 //
-// Shape: workgroup = 4 waves as 2 x 2; the tile is 256 rows of A by 128 rows of B; a wave owns 128 x 64 = 4 x 2
-// blocks.  The accumulator of a block keeps 16 rows of one column per lane, so A should be the operand over
-// which the caller reduces (the centres, for an arg-min): the reduction then runs over a lane's own registers.
+// Shape: workgroup = 8 waves as 2 x 4; the tile is 256 rows of A by 256 rows of B; a wave owns 128 x 64 = 4 x 2
+// blocks.  (The product is bound by the traffic of its operands from beyond the 4 MiB L2 of an XCD, which is
+// proportional to 1 / rows of A + 1 / rows of B per multiply-add: measured with a 256 x 128 tile, 52 % to 60 % of
+// the L2 requests missed, 4.4 TB/s from the fabric, whatever the order of the tiles.)  The accumulator of a block
+// keeps 16 rows of one column per lane, so A should be the operand over which the caller reduces (the centres,
+// for an arg-min): the reduction then runs over a lane's own registers.
 // Depth step 16 = two chunks; lanes 0-31 take the first chunk of the step and lanes 32-63 the second, for A and
 // B alike, which is all a sum over the depth needs.  LDS holds [chunk of the step][row][8 fp16] per part, the
 // same order as in memory.  Two steps are in flight: one in registers, one in the second LDS buffer.
@@ -32,7 +35,7 @@ typedef float acc16_t __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 struct F16x3Tile {
-    static constexpr int kRowsA = 256, kRowsB = 128, kTileK = 16, kRowPad = 256;
+    static constexpr int kRowsA = 256, kRowsB = 256, kTileK = 16, kRowPad = 256, kThreads = 512;
     static constexpr int kPartA = 2 * kRowsA * 16, kPartB = 2 * kRowsB * 16;          // bytes of one hi or lo part per step
     static constexpr size_t kLdsBytes = 2 * (2 * (size_t)kPartA + 2 * (size_t)kPartB);  // double-buffered
 
@@ -41,14 +44,14 @@ struct F16x3Tile {
     // elements (uint16) of one part of a split matrix
     __host__ __device__ static size_t part_elems(int64_t rows, int d) { return (size_t)chunks_pad(d) * (size_t)rows_pad(rows) * 8; }
 
-    // Rows a_row0 .. +255 of A against rows b_row0 .. +127 of B over the whole depth; both row ranges lie within
+    // Rows a_row0 .. +255 of A against rows b_row0 .. +255 of B over the whole depth; both row ranges lie within
     // the padded matrices.  a_rp / b_rp: padded row counts; nchunks: chunks_pad(d).
     // acc[bi][bj]: block rows 32*bi.., columns 32*bj.. of this wave's 128 x 64 patch.
     __device__ static void run(const uint16_t *__restrict__ a_hi, const uint16_t *__restrict__ a_lo, int64_t a_rp, int64_t a_row0,
                                const uint16_t *__restrict__ b_hi, const uint16_t *__restrict__ b_lo, int64_t b_rp, int64_t b_row0,
                                int nchunks, unsigned char *s_mem, acc16_t (&acc)[4][2]) {
         const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-        const int wr = wave >> 1, wc = wave & 1;
+        const int wr = wave >> 2, wc = wave & 3;
         unsigned char *sAh[2] = {s_mem, s_mem + kPartA * 2 + kPartB * 2};
         unsigned char *sAl[2] = {sAh[0] + kPartA, sAh[1] + kPartA};
         unsigned char *sBh[2] = {sAh[0] + 2 * kPartA, sAh[1] + 2 * kPartA};
@@ -60,33 +63,28 @@ struct F16x3Tile {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
-        // per step and part: A is 2 chunks x 256 rows = 512 pieces of 16 bytes (2 per thread: chunk p, row tid),
-        // B is 2 x 128 = 256 pieces (1 per thread: chunk tid / 128, row tid % 128); LDS offset = piece * 16
-        struct Regs { uint4 ah[2], al[2], bh, bl; };
+        // per step and part: A is 2 chunks x 256 rows = 512 pieces of 16 bytes, B likewise: one piece of each per
+        // thread (chunk tid / 256, row tid % 256); LDS offset = piece * 16
+        struct Regs { uint4 ah, al, bh, bl; };
         const uint4 zero4 = {0u, 0u, 0u, 0u};
-        const uint4 *pa_hi = reinterpret_cast<const uint4 *>(a_hi) + a_row0 + tid;
-        const uint4 *pa_lo = reinterpret_cast<const uint4 *>(a_lo) + a_row0 + tid;
-        const uint4 *pb_hi = reinterpret_cast<const uint4 *>(b_hi) + (int64_t)(tid >> 7) * b_rp + b_row0 + (tid & 127);
-        const uint4 *pb_lo = reinterpret_cast<const uint4 *>(b_lo) + (int64_t)(tid >> 7) * b_rp + b_row0 + (tid & 127);
+        const int pc = tid >> 8, pr = tid & 255;
+        const uint4 *pa_hi = reinterpret_cast<const uint4 *>(a_hi) + (int64_t)pc * a_rp + a_row0 + pr;
+        const uint4 *pa_lo = reinterpret_cast<const uint4 *>(a_lo) + (int64_t)pc * a_rp + a_row0 + pr;
+        const uint4 *pb_hi = reinterpret_cast<const uint4 *>(b_hi) + (int64_t)pc * b_rp + b_row0 + pr;
+        const uint4 *pb_lo = reinterpret_cast<const uint4 *>(b_lo) + (int64_t)pc * b_rp + b_row0 + pr;
         auto fetch = [&](Regs &rg, int c0) {            // c0: first chunk of the step
             if (c0 < nchunks) {                         // uniform
-#pragma unroll
-                for (int p = 0; p < 2; ++p) {
-                    rg.ah[p] = pa_hi[(int64_t)(c0 + p) * a_rp];
-                    rg.al[p] = pa_lo[(int64_t)(c0 + p) * a_rp];
-                }
+                rg.ah = pa_hi[(int64_t)c0 * a_rp];
+                rg.al = pa_lo[(int64_t)c0 * a_rp];
                 rg.bh = pb_hi[(int64_t)c0 * b_rp];
                 rg.bl = pb_lo[(int64_t)c0 * b_rp];
             } else {
-                rg.ah[0] = rg.ah[1] = rg.al[0] = rg.al[1] = rg.bh = rg.bl = zero4;
+                rg.ah = rg.al = rg.bh = rg.bl = zero4;
             }
         };
         auto stash = [&](const Regs &rg, int buf) {
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                *reinterpret_cast<uint4 *>(sAh[buf] + (p * kRowsA + tid) * 16) = rg.ah[p];
-                *reinterpret_cast<uint4 *>(sAl[buf] + (p * kRowsA + tid) * 16) = rg.al[p];
-            }
+            *reinterpret_cast<uint4 *>(sAh[buf] + tid * 16) = rg.ah;
+            *reinterpret_cast<uint4 *>(sAl[buf] + tid * 16) = rg.al;
             *reinterpret_cast<uint4 *>(sBh[buf] + tid * 16) = rg.bh;
             *reinterpret_cast<uint4 *>(sBl[buf] + tid * 16) = rg.bl;
         };
@@ -139,11 +137,11 @@ struct F16x3Tile {
     // Row of A and row of B (both within the workgroup tile) of accumulator register r of block (bi, bj) for this lane.
     __device__ static __forceinline__ int acc_row(int bi, int r) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        return (wave >> 1) * 128 + bi * 32 + (r % 4) + 4 * (lane >> 5) + 8 * (r / 4);
+        return (wave >> 2) * 128 + bi * 32 + (r % 4) + 4 * (lane >> 5) + 8 * (r / 4);
     }
     __device__ static __forceinline__ int acc_col(int bj) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        return (wave & 1) * 64 + bj * 32 + (lane & 31);
+        return (wave & 3) * 64 + bj * 32 + (lane & 31);
     }
 };
 

@@ -119,7 +119,7 @@ def check_encoding(gpu_lists, gpu_codes, x, coarse, pq, residual=False):
     return len(bad_l), len(bad_c)
 
 
-def check_lists_screened(gpu_lists, x_dev, x_host, coarse, max_cand=8, block=16384):
+def check_lists_screened(gpu_lists, x_dev, x_host, coarse, max_cand=64, block=16384):
     """List numbers of many rows against the oracle, at a cost that allows a million rows against 65,536 centres
     (the plain oracle does a few hundred such rows per second).  A library matrix product on the GPU (torch, fp32;
     harness code, not the library under test) first rules out the centres that are far from a row: those whose
