@@ -227,30 +227,31 @@ def nprobe_sweep(args, pkg, cfg, torch):
 
 
 def overlap_demo(args, pkg, cfg, torch):
-    """Performance-model-driven retrieval (Section 3.2, S3) on one GPU: the latency line fitted by
-    piperag_latency_profile is inverted for the time a synthetic generation step takes, and the chosen search is
-    run on a second stream while that step runs on the first.  The generation step stands in for the decoder: per
-    token one pass over a weight matrix plus a read of a key/value cache that grows with the sequence length
-    (memory-bound, like decoding), so its duration T(C) grows linearly in the sequence length."""
+    """Performance-model-driven retrieval (Section 3.2, S3) hidden behind generation (S1) on one GPU.  The paper
+    runs the retrieval on a server of its own; here the search gets a slice of the compute units (a stream with
+    a compute-unit mask, piperag_stream_create_cu_slice) and the generation step the rest.  The latency line is
+    fitted by piperag_latency_profile on the search's own stream (so it is the line of the slice), inverted by
+    piperag_max_nprobe for the time a synthetic generation step takes, and the chosen search is run beside
+    that step.  The generation step stands in for the decoder: per token one pass over a weight matrix plus a
+    read of a key/value cache that grows with the sequence length (memory-bound, like decoding), so its
+    duration T(C) grows linearly in the sequence length.  One table per size of the search's slice."""
     cap = min(1024, cfg.nlist)
     ix, g, info = build_index(pkg, cfg, torch, max_nq=1, max_nprobe=cap)
     q1 = g.queries(1)
-    nprobes = [p for p in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if p <= cap]
-    p50, fit = ix.latency_profile(q1, nprobes, cfg.k, reps=50)
-    log(f"[overlap] latency fit: {fit[0]:.4f} ms + {fit[1] * 1e3:.3f} us * nprobe")
+    nprobes = sorted({int(p) for p in np.linspace(64, cap, 16)})      # the range the choice falls in, evenly spaced
     W = torch.randn((8192, 8192), dtype=torch.float32, device="cuda")             # 256 MiB of "weights"
     x = torch.randn(8192, dtype=torch.float32, device="cuda")
     kv = torch.randn((16384, 4096), dtype=torch.float32, device="cuda")           # 16 KiB of cache per position
     out_d = torch.empty((1, cfg.k), dtype=torch.float32, device="cuda")
     out_i = torch.empty((1, cfg.k), dtype=torch.int64, device="cuda")
-    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ncu = torch.cuda.get_device_properties(0).multi_processor_count
 
     def generate(L, tokens=2):
         for _ in range(tokens):
             torch.mv(W, x)
             kv[:L].sum(dim=0)
 
-    def timed(fn_a, fn_b, reps=30):
+    def timed(sa, sb, fn_a, fn_b, reps=30):
         ts = []
         for r in range(reps + 5):
             torch.cuda.synchronize()
@@ -269,24 +270,58 @@ def overlap_demo(args, pkg, cfg, torch):
                 ts.append((ta, tb))
         return np.median(np.array(ts), axis=0)
 
-    rows = []
-    for L in (1024, 4096, 8192, 16384):
-        t_gen = float(timed(lambda: generate(L), None)[0])
-        nprobe, fits, pred = pkg.max_nprobe(fit, t_gen, cap)
-        search = lambda: ix.ivfpq_search(q1, nprobe, cfg.k, out_d, out_i)
-        t_ret = float(timed(None, search)[1])
-        both = timed(lambda: generate(L), search)
-        rows.append({"seq_len": L, "t_gen_ms": t_gen, "nprobe": nprobe, "fits": fits, "predicted_ret_ms": pred,
-                     "t_ret_alone_ms": t_ret, "t_gen_overlapped_ms": float(both[0]), "t_ret_overlapped_ms": float(both[1])})
-        log(f"[overlap] {rows[-1]}")
-    print("| sequence length | T(C) alone ms | nprobe chosen | predicted retrieval ms | retrieval alone ms | "
-          "T(C) with retrieval beside it ms | retrieval beside T(C) ms | hidden |")
-    print("|---|---|---|---|---|---|---|---|")
-    for r in rows:
-        hidden = r["t_ret_overlapped_ms"] <= r["t_gen_overlapped_ms"]
-        print(f"| {r['seq_len']} | {r['t_gen_ms']:.3f} | {r['nprobe']} | {r['predicted_ret_ms']:.3f} | {r['t_ret_alone_ms']:.3f} | "
-              f"{r['t_gen_overlapped_ms']:.3f} | {r['t_ret_overlapped_ms']:.3f} | {'yes' if hidden else 'no'} |")
-    print(json.dumps({"workload": cfg.name, "fit_ms": {"a": float(fit[0]), "b": float(fit[1])}, "rows": rows}), flush=True)
+    tables = []
+    for slice_cus in args.overlap_cus:
+        if slice_cus == 0:                               # no partition: both streams may use every compute unit
+            sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        else:
+            sb = pkg.stream_create_cu_slice(0, slice_cus)               # the search's slice ...
+            sa = pkg.stream_create_cu_slice(slice_cus, ncu - slice_cus)  # ... and the rest for the generation step
+        ix.set_compute_units(slice_cus)                  # launches sized to the slice (0: the whole device)
+        # The latency line is fitted under the conditions it is used in (the paper fits it on the deployment
+        # hardware): while generation steps run on the other stream and share the memory system with the search.
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sa):
+            for _ in range(1500):                        # about 0.4 s of queued generation work
+                generate(8192)
+        with torch.cuda.stream(sb):
+            p50, fit = ix.latency_profile(q1, nprobes, cfg.k, reps=20)
+        busy = not sa.query()                            # the generation stream was still busy when the profile ended
+        torch.cuda.synchronize()
+        log(f"[overlap] p50 ms by nprobe (generation beside it: {busy}): " + ", ".join(f"{p}: {t:.3f}" for p, t in zip(nprobes, p50)))
+        assert busy, "the latency profile outlasted the queued generation steps"
+        log(f"[overlap] search on {slice_cus or ncu} compute units: latency fit {fit[0]:.4f} ms + {fit[1] * 1e3:.3f} us * nprobe")
+        full = torch.cuda.Stream()
+        rows = []
+        for L in (1024, 4096, 8192, 16384):
+            t_gen_full = float(timed(full, None, lambda: generate(L), None)[0])      # the step with the whole GPU to itself
+            t_gen = float(timed(sa, None, lambda: generate(L), None)[0])             # ... and on its share of the compute units
+            nprobe, fits, pred = pkg.max_nprobe(fit, t_gen, cap)
+            search = lambda: ix.ivfpq_search(q1, nprobe, cfg.k, out_d, out_i)
+            t_ret = float(timed(None, sb, None, search)[1])
+            both = timed(sa, sb, lambda: generate(L), search)
+            rows.append({"seq_len": L, "t_gen_whole_gpu_ms": t_gen_full, "t_gen_ms": t_gen, "nprobe": nprobe, "fits": fits,
+                         "predicted_ret_ms": pred, "t_ret_alone_ms": t_ret, "t_gen_overlapped_ms": float(both[0]),
+                         "t_ret_overlapped_ms": float(both[1])})
+            log(f"[overlap] {rows[-1]}")
+        print(f"\nsearch on {slice_cus} of {ncu} compute units, generation on the other {ncu - slice_cus}" if slice_cus else
+              f"\nno partition: both streams on all {ncu} compute units")
+        print(f"latency line of the search: {fit[0]:.4f} ms + {fit[1] * 1e3:.3f} us x nprobe")
+        print("| sequence length | T(C), whole GPU, alone ms | T(C) on its share, alone ms | nprobe chosen | predicted retrieval ms | "
+              "retrieval alone ms | T(C) with retrieval beside it ms | retrieval beside T(C) ms | hidden | T(C) slowed by |")
+        print("|---|---|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            hidden = r["t_ret_overlapped_ms"] <= r["t_gen_overlapped_ms"]
+            slow = r["t_gen_overlapped_ms"] / r["t_gen_whole_gpu_ms"] - 1.0
+            print(f"| {r['seq_len']} | {r['t_gen_whole_gpu_ms']:.3f} | {r['t_gen_ms']:.3f} | {r['nprobe']} | {r['predicted_ret_ms']:.3f} | "
+                  f"{r['t_ret_alone_ms']:.3f} | {r['t_gen_overlapped_ms']:.3f} | {r['t_ret_overlapped_ms']:.3f} | "
+                  f"{'yes' if hidden else 'no'} | {100 * slow:+.1f} % |")
+        tables.append({"search_cus": slice_cus, "fit_ms": {"a": float(fit[0]), "b": float(fit[1])}, "rows": rows})
+        if slice_cus:
+            torch.cuda.synchronize()
+            pkg.stream_destroy(sa)
+            pkg.stream_destroy(sb)
+    print(json.dumps({"workload": cfg.name, "tables": tables}), flush=True)
 
 
 def main():
@@ -306,6 +341,8 @@ def main():
                     help="instead of the bench line: latency and recall against nprobe on the chosen workload (meant for cfg2)")
     ap.add_argument("--overlap", action="store_true",
                     help="instead of the bench line: retrieval sized by the latency model, run beside a synthetic generation step")
+    ap.add_argument("--overlap-cus", type=lambda t: [int(v) for v in t.split(",")], default=[0, 48, 64, 96],
+                    help="with --overlap: compute units given to the search stream, one table per value (0 = no partition)")
     ap.add_argument("--summarize", metavar="DIR", help="write a text summary of rocprofv3 CSV output found under DIR and exit")
     ap.add_argument("--command", default="", help="with --summarize: the command line that produced DIR")
     args = ap.parse_args()

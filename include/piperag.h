@@ -190,6 +190,17 @@ int piperag_project_latency(const float *inference_ms_host, const float *retriev
                             float inference_speedup, float retrieval_speedup, double *out_sequential_ms,
                             double *out_pipelined_ms);
 
+/* A stream whose kernels run only on compute units first_cu .. first_cu + ncu - 1 of the current device
+ * (numbered as the driver's compute-unit mask numbers them; on this GPU consecutive numbers go round the XCDs),
+ * at the default priority.  The paper hides the retrieval behind the generation of the next tokens by running it
+ * on a server of its own (Section 3.2, S1); on one GPU the same is had by giving the search such a stream and the
+ * generation a stream on the remaining compute units: every call of this library that takes a stream then runs
+ * in that slice (the lookup tables of piperag_ivfpq_search are built on a side stream of the index, outside it;
+ * piperag_ivfpq_search_static keeps everything on the given stream).  piperag_latency_profile on the same stream
+ * gives the latency line of the slice.  *out_stream is a hipStream_t; destroy it with piperag_stream_destroy. */
+int piperag_stream_create_cu_slice(int32_t first_cu, int32_t ncu, void **out_stream);
+int piperag_stream_destroy(void *stream);
+
 /* ---- stage taps (each step of the search path by itself, for checking) ------------------- */
 
 /* Coarse quantiser (the index-scan term of the latency model, Section 3.2, S3): the nprobe closest
@@ -256,6 +267,12 @@ int piperag_set_graph_replay(piperag_index *index, int enable);
  * ordinary loads; mode > 0: always non-temporal loads.  Results do not depend on the mode.  Cached graphs
  * of repeated calls are dropped. */
 int piperag_set_scan_streaming(piperag_index *index, int mode);
+
+/* Compute units the searches on this index may use: ncu <= 0 (default) all of the device's, else that many -
+ * for searches given a stream from piperag_stream_create_cu_slice.  The selection and scan launches are sized to
+ * it (two scan workgroups per compute unit; 512 workgroups on a 32-unit slice would run in eight rounds, each
+ * paying the launch's fixed costs).  Results do not depend on it.  Cached graphs of repeated calls are dropped. */
+int piperag_set_compute_units(piperag_index *index, int32_t ncu);
 
 /* Number of vectors in the index. */
 int64_t piperag_ivf_ntotal(const piperag_index *index);

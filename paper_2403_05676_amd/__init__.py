@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     kmeans,
     max_nprobe,
     project_latency,
+    stream_create_cu_slice,
+    stream_destroy,
     PiperagError,
     lib_path,
     load_library,

@@ -67,7 +67,10 @@ def load_library() -> C.CDLL:
         "piperag_set_stage_timing": [vp, C.c_int],
         "piperag_set_graph_replay": [vp, C.c_int],
         "piperag_set_scan_streaming": [vp, C.c_int],
+        "piperag_set_compute_units": [vp, i32],
         "piperag_stage_times": [vp, vp],
+        "piperag_stream_create_cu_slice": [i32, i32, C.POINTER(vp)],
+        "piperag_stream_destroy": [vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -117,6 +120,17 @@ def project_latency(inference_ms, retrieval_ms, inference_speedup: float = 1.0, 
     _check(load_library().piperag_project_latency(ti.ctypes.data, tr.ctypes.data, ti.shape[0], float(inference_speedup),
                                                   float(retrieval_speedup), C.addressof(seq), C.addressof(pipe)))
     return seq.value, pipe.value
+
+
+def stream_create_cu_slice(first_cu: int, ncu: int) -> torch.cuda.ExternalStream:
+    """piperag_stream_create_cu_slice, wrapped for torch (the handle stays valid until stream_destroy)."""
+    h = C.c_void_p()
+    _check(load_library().piperag_stream_create_cu_slice(int(first_cu), int(ncu), C.byref(h)))
+    return torch.cuda.ExternalStream(h.value)
+
+
+def stream_destroy(stream: torch.cuda.ExternalStream) -> None:
+    _check(load_library().piperag_stream_destroy(C.c_void_p(stream.cuda_stream)))
 
 
 def kmeans(x: torch.Tensor, K: int, init_rows: np.ndarray, iters: int = 10, return_inertia: bool = False):
@@ -292,6 +306,9 @@ class Index:
 
     def set_scan_streaming(self, mode: int) -> None:
         _check(load_library().piperag_set_scan_streaming(self._h, int(mode)))
+
+    def set_compute_units(self, ncu: int) -> None:
+        _check(load_library().piperag_set_compute_units(self._h, int(ncu)))
 
     def stage_times(self) -> np.ndarray:
         out = np.empty(NSTAGES, dtype=np.float32)

@@ -84,7 +84,9 @@ struct SearchWs {
     int4 *desc;           // [kMaxScanWGs+max_nq] (query, number among the query's workgroups, their count, chunk counters in use) of each scan workgroup
     uint32_t *done;       // [max_nq + kMaxScanWGs + max_nq] finished scan workgroups (or groups of them) per query, then finished workgroups per group
     uint64_t *part2;      // same shape as part: the queries' lists when a query's workgroups are grouped
-    uint32_t *tb;         // [max_nq+1] blocks of each query as published by the selection, then the count of finished selections (zero between searches)
+    uint32_t *tb;         // [2*max_nq+1] blocks of each query as published by the selection; then the count of finished selections and a ticket
+                          // per query for its selection workgroups (both zero between searches)
+    uint64_t *selcand;    // [max(max_nq * slices a long row needs, 512) * max_nprobe] candidate probes of the queries' selection workgroups
     uint32_t *ctr;        // [max_nq*kCtrPerQuery*kCtrStride] chunk counters of each query (one per 128 bytes)
     float *pcst;          // [max_nq*max_nprobe] residual indexes: |c_l|^2 - 2 <q, c_l> of each probed list
     int32_t *pblk;        // [max_nq*max_nprobe] first block of each probed list
@@ -162,6 +164,7 @@ struct piperag_index {
     hipStream_t cap_stream;       // capture stream for the search graphs
     bool replay;                  // graph replay of repeated calls is enabled
     int streaming;                // scan loads: < 0 by index size, 0 ordinary, > 0 non-temporal
+    int ncu;                      // compute units the searches may use (sizes the selection and scan launches)
     mutable SearchGraph graphs[8];
     mutable uint64_t graph_clock;
     mutable bool ev_valid;

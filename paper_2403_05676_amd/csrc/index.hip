@@ -254,6 +254,10 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     int rc = PIPERAG_OK;
     auto fail = [&](int code) { piperag_ivf_free(ix); return code; };
     if (hipGetDevice(&ix->device) != hipSuccess) { set_error("hipGetDevice failed"); return fail(PIPERAG_ERR_HIP); }
+    if (hipDeviceGetAttribute(&ix->ncu, hipDeviceAttributeMultiprocessorCount, ix->device) != hipSuccess || ix->ncu < 1) {
+        set_error("cannot read the number of compute units");
+        return fail(PIPERAG_ERR_HIP);
+    }
     const piperag_params &p = ix->p;
     const size_t ncent = (size_t)p.nlist * p.d, npq = (size_t)p.M * kKsub * ix->dsub;
     if ((rc = dev_alloc(&ix->centroids, ncent)) || (rc = dev_alloc(&ix->pq, npq)) ||
@@ -269,7 +273,7 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
         if (hipMalloc(&ix->ws_mem, ws_bytes) != hipSuccess) { set_error("out of device memory for %zu bytes of search workspace", ws_bytes); return fail(PIPERAG_ERR_OOM); }
         search_ws_layout(&ix->ws, ix->ws_mem, p.nlist, ix->Mp, p.max_nq, p.max_nprobe, p.max_k, kMaxScanWGs);
     }
-    if (hipMemset(ix->ws.tb, 0, sizeof(uint32_t) * ((size_t)p.max_nq + 1)) != hipSuccess ||   // arrival counter starts at zero
+    if (hipMemset(ix->ws.tb, 0, sizeof(uint32_t) * (2 * (size_t)p.max_nq + 1)) != hipSuccess ||   // arrival counter starts at zero
         hipMemcpy(ix->centroids, cent_host, ncent * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ix->pq, pq_host, npq * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
         set_error("upload of trained parameters failed");

@@ -1,6 +1,8 @@
 // Host-side arithmetic of the paper's performance models: the choice of the search space under a latency
 // budget (Section 3.2, S3) and the projection of end-to-end latency onto faster hardware (Appendix "Performance
-// Modeling for Future Hardware").  No GPU work.
+// Modeling for Future Hardware").  No GPU work - except the two calls at the end, which create and destroy a
+// stream that owns a slice of the compute units, so that a search can run beside a generation step on one GPU
+// the way the paper runs it on a server of its own (Section 3.2, S1).
 #include "common.h"
 
 #include <cmath>
@@ -53,6 +55,29 @@ int piperag_project_latency(const float *inference_ms_host, const float *retriev
     }
     *out_sequential_ms = seq;
     *out_pipelined_ms = pipe;
+    return PIPERAG_OK;
+}
+
+int piperag_stream_create_cu_slice(int32_t first_cu, int32_t ncu, void **out_stream) {
+    PR_REQUIRE(out_stream != nullptr, PIPERAG_ERR_ARG, "out_stream is NULL");
+    *out_stream = nullptr;
+    int device = 0, total = 0;
+    PR_CHECK_HIP(hipGetDevice(&device));
+    PR_CHECK_HIP(hipDeviceGetAttribute(&total, hipDeviceAttributeMultiprocessorCount, device));
+    PR_REQUIRE(first_cu >= 0 && ncu >= 1 && first_cu + ncu <= total, PIPERAG_ERR_ARG,
+               "compute units %d..%d are not within the device's %d", first_cu, first_cu + ncu - 1, total);
+    uint32_t mask[32] = {0};
+    PR_REQUIRE(total <= 32 * 32, PIPERAG_ERR_LIMIT, "more compute units than the mask holds");
+    for (int cu = first_cu; cu < first_cu + ncu; ++cu) mask[cu >> 5] |= 1u << (cu & 31);
+    hipStream_t st = nullptr;
+    PR_CHECK_HIP(hipExtStreamCreateWithCUMask(&st, (uint32_t)((total + 31) / 32), mask));
+    *out_stream = st;
+    return PIPERAG_OK;
+}
+
+int piperag_stream_destroy(void *stream) {
+    PR_REQUIRE(stream != nullptr, PIPERAG_ERR_ARG, "stream is NULL");
+    PR_CHECK_HIP(hipStreamDestroy((hipStream_t)stream));
     return PIPERAG_OK;
 }
 

@@ -135,27 +135,6 @@ __device__ void wave_sort_u64(uint64_t *keys, int n) {
     if (lane < n) keys[lane] = key;
 }
 
-// In-place ascending bitonic sort of n (power of two) 64-bit keys in LDS by the whole workgroup.
-__device__ void block_bitonic_sort_u64(uint64_t *keys, int n) {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    // up to 128 keys are sorted by one wavefront, whose lanes run in lockstep: no workgroup barriers between steps
-    const bool one_wave = n <= 2 * kWave;
-    __syncthreads();
-    for (int size = 2; size <= n; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (one_wave) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); else __syncthreads();
-            for (int i = tid; i < (n >> 1) && (!one_wave || tid < kWave); i += nt) {
-                const int lo = 2 * i - (i & (stride - 1));
-                const int hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t a = keys[lo], b = keys[hi];
-                if ((a > b) == up) { keys[lo] = b; keys[hi] = a; }
-            }
-        }
-    }
-    __syncthreads();
-}
-
 // ------------------------------------------------------------------------------------------------
 // Stage 0: coarse distances  D[q][j] = || query_q - centre_j ||^2  (direct form, fp32)
 // One wavefront per JT centres at a time; the lanes split the coordinates (VEC floats per lane per 64*VEC
@@ -327,7 +306,9 @@ struct ShareOut {
     int4 *desc;
     uint32_t *ctr;
     uint32_t *gdone;            // [workgroups] finished workgroups per group of workgroups (zeroed here)
+    int fan;                    // workgroups whose keys one selection can merge (more per query: a second level, ~9 us)
 };
+constexpr int kSoftBlocksPerWG = 64;   // a query that would get a few more workgroups than `fan` gets `fan`, up to this many blocks each
 
 // The sharing itself, by the first 256 threads of the calling workgroup (all of its threads must call it: it
 // has barriers).  blocks_of(q) = number of blocks of query q.
@@ -359,6 +340,9 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
         if (act && q < nq) {
             const long long tb = q0 == 0 ? first_tb : blocks_of(q);
             sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
+            // a small scan spread over a few more workgroups than one selection merges would pay a second merge
+            // level for nothing
+            if (sq > o.fan && tb <= (long long)o.fan * kSoftBlocksPerWG) sq = o.fan;
         }
         int32_t incl = sq;                                 // inclusive scan: within the wave, then over the four waves
 #pragma unroll
@@ -411,38 +395,67 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
     share_plan(blocks_of, nq, target, max_wg, o);
 }
 
-// Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  One workgroup
-// of NT threads per query (512 for rows of up to 8,192 distances, 1024 for longer ones): selection of the nprobe-th smallest key (distance bits << 32 | list; distances
-// are >= 0 so their bit patterns order like the values), compaction, bitonic sort.  The row of D is staged in
-// LDS (dynamic, nlist * 4 bytes) for the rounds of the selection when it fits (stage_row != 0).
-constexpr int kSelThreads = 512;            // rows of up to kSelSmallRow distances
-constexpr int kSelThreadsLong = 1024;       // longer rows: the sweeps over the row are what the selection costs there
-constexpr int kSelSmallRow = 8192;          // (measured: 1024 threads are 8 us faster at 16,384 lists and 4 us slower at 4,096)
-constexpr int kSelMaxLdsRow = 32768;        // centres whose distances fit the LDS staging (128 KiB)
-constexpr int kSelGroups = 4 * kSelThreadsLong;   // longer rows: groups whose minima give the first bound (>= kMaxNprobe) ...
-constexpr int kSelCand = 4096;              // ... and room for the keys collected under it
-static_assert(kSelGroups >= kMaxNprobe, "the bound is the nprobe-th smallest group minimum");
+// Keys that one workgroup writes and another reads within the same launch go through device-scope atomic
+// stores and loads (they bypass the per-XCD caching that is not coherent across the chip), ordered by
+// publish_keys(): wait until this thread's stores are acknowledged, then meet the workgroup; a counter
+// increment after that tells the others.  No cache-wide write-back or invalidation is involved (a full fence
+// by every finishing workgroup costs far more than the merge itself).
+__device__ __forceinline__ void store_key(uint64_t *p, uint64_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint64_t load_key(const uint64_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void publish_keys() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): loads and stores of this thread are complete
+    __syncthreads();
+}
+
+// Per query, the nprobe smallest D[q][.] ordered by (distance, list), then the query's plan.  G workgroups of NT
+// threads per query (512 for slices of up to 8,192 distances, 1024 for longer ones), each with a slice of the
+// row: it finishes the slice's distances (partial products summed in a fixed order, norms added), stages them in
+// LDS, and selects the slice's min(nprobe, length) smallest keys (distance bits << 32 | list; distances are >= 0,
+// so their bit patterns order like the values).  G = 1: those are the probes.  G > 1 (small batches, so that the
+// selection is spread over the chip, and rows longer than the LDS staging): the slice's keys go to the query's
+// candidate list, and the query's last workgroup to finish (a ticket per query) selects among the G * nprobe
+// candidates.  The probes are then sorted, written out, and turned into the query's plan; the workgroup that
+// finishes the last query shares the scan workgroups out over the queries (saves a launch).
+constexpr int kSelThreads = 512;            // slices of up to kSelSmallRow distances
+constexpr int kSelThreadsLong = 1024;       // longer slices (measured on whole rows: 1024 threads are 8 us faster at 16,384 distances, 4 us slower at 4,096)
+constexpr int kSelSmallRow = 8192;
+constexpr int kSelMaxLdsRow = 32768;        // distances that fit the LDS staging (128 KiB); also the keys of a second-level selection (8 bytes each, half as many)
+// Measured (selection kernel, us, nprobe 32; one query / 64 queries): whole rows of 4,096 distances 12.8 / 20.4, of
+// 16,384 21.9 / 23.4, of 65,536 (two slices at least) 33.5 / 40.6; slices of 2,048: 16.6 / 21.6, 18.3 / 21.5, 18.6 / 30.2.
+// Every selection costs a dozen barrier-separated steps whatever its size, so slicing pays only for long rows.
+constexpr int kSelMinSlice = 4096;          // a slice is at least this long
+constexpr int kSelTargetWGs = 2048;         // batches get up to this many selection workgroups in all
+constexpr int kSelSecondLevel = 4096;       // ... as long as the second level has no more candidates than this (its cost is theirs)
+
+// Workgroups per query for a batch (host and workspace sizing use the same rule).
+inline int select_groups(int nlist, int nq, int nprobe, int ncu) {
+    const int need = (nlist + kSelMaxLdsRow - 1) / kSelMaxLdsRow;                  // so that a slice fits the staging
+    const int np2 = nprobe <= 2 ? 2 : 1 << (32 - __builtin_clz((unsigned)(nprobe - 1)));
+    const int cap = std::max(1, std::min(std::min(kSelSecondLevel / np2, nlist / kSelMinSlice), 64));   // second level stays small; slices not too short
+    return std::max(need, std::min(cap, std::min(kSelTargetWGs, 8 * ncu) / std::max(1, nq)));
+}
 
 template <int NT>
-__global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D, int nparts,
-                                                                    const float *__restrict__ q, int d,
-                                                                    const float *__restrict__ cn, int nlist, int nprobe,
-                                                                    int stage_row, int32_t *__restrict__ probe,
-                                                                    float *__restrict__ probe_d, int probe_stride,
-                                                                    const int32_t *__restrict__ list_blk,
-                                                                    const int32_t *__restrict__ list_len, PlanOut plan,
-                                                                    uint32_t *__restrict__ tb, uint32_t *__restrict__ arrived,
-                                                                    int target, int max_wg, ShareOut share) {
+__global__ __launch_bounds__(NT) void select_probes_kernel(const float *__restrict__ D, int nparts, int nq, int G, int slice_len,
+                                                           int cand_in_lds, const float *__restrict__ q, int d,
+                                                           const float *__restrict__ cn, int nlist, int nprobe,
+                                                           int32_t *__restrict__ probe, float *__restrict__ probe_d,
+                                                           int probe_stride, const int32_t *__restrict__ list_blk,
+                                                           const int32_t *__restrict__ list_len, PlanOut plan,
+                                                           uint64_t *__restrict__ selcand, uint32_t *__restrict__ qticket,
+                                                           uint32_t *__restrict__ tb, uint32_t *__restrict__ arrived,
+                                                           int target, int max_wg, ShareOut share) {
     extern __shared__ __align__(16) unsigned char sel_smem[];
     __shared__ unsigned s_ticket;
     __shared__ unsigned s_hist[256];
     __shared__ unsigned long long s_state[8];
     __shared__ uint64_t s_keys[kMaxNprobe];
-    __shared__ unsigned s_count, s_ncand;
+    __shared__ unsigned s_count;
     __shared__ float s_qpart[NT / kWave];
-    const int qi = blockIdx.x, tid = threadIdx.x, nq = gridDim.x;
-    float *grow = D + (size_t)qi * nlist;                    // the query's row of distances (of part 0, with parts)
-    const uint32_t *row = reinterpret_cast<const uint32_t *>(grow);
+    const int qi = blockIdx.x / G, g = blockIdx.x - qi * G, tid = threadIdx.x;
+    const int i_beg = g * slice_len, i_end = min(nlist, i_beg + slice_len), len = max(0, i_end - i_beg);
+    const float *grow = D + (size_t)qi * nlist;              // the query's row of distances (of part 0, with parts)
     const int np2 = max(2, 1 << (32 - __clz(nprobe - 1)));   // next power of two >= nprobe (>= 2)
     for (int i = tid; i < np2; i += NT) s_keys[i] = kSentinel;
     if (tid == 0) s_count = 0;
@@ -465,12 +478,12 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
     // round trip instead of two)
     constexpr int US = 8;
     float pd[US], pc[US];
-    if (stage_row && nparts > 0) {
+    if (nparts > 0) {
 #pragma unroll
         for (int u = 0; u < US; ++u) {
-            const int i = tid + u * NT;
-            pd[u] = i < nlist ? dot_of(i) : 0.f;
-            pc[u] = i < nlist ? cn[i] : 0.f;
+            const int i = i_beg + tid + u * NT;
+            pd[u] = i < i_end ? dot_of(i) : 0.f;
+            pc[u] = i < i_end ? cn[i] : 0.f;
         }
     }
     float qn = 0.f;
@@ -485,119 +498,101 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
         for (int w = 0; w < NT / kWave; ++w) qn += s_qpart[w];    // the same order in every thread
     }
     auto finish = [&](float dot, float cnorm) -> float { return fmaxf(0.f, qn + cnorm - 2.f * dot); };
-    auto dist_of = [&](int i) -> float { return finish(dot_of(i), cn[i]); };
-    if (stage_row) {
-        uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);
-        for (int i0 = tid; i0 < nlist; i0 += US * NT) {
-            uint32_t v[US];
-            if (nparts > 0 && i0 != tid) {                   // later sweeps (uniform)
-#pragma unroll
-                for (int u = 0; u < US; ++u) {
-                    const int i = i0 + u * NT;
-                    pd[u] = i < nlist ? dot_of(i) : 0.f;
-                    pc[u] = i < nlist ? cn[i] : 0.f;
-                }
-            }
+    uint32_t *s_row = reinterpret_cast<uint32_t *>(sel_smem);    // the slice's distance bits
+    const uint32_t *drow = reinterpret_cast<const uint32_t *>(grow);
+    for (int i0 = tid; i0 < len; i0 += US * NT) {
+        uint32_t v[US];
+        if (nparts > 0 && i0 != tid) {                       // later sweeps (uniform)
 #pragma unroll
             for (int u = 0; u < US; ++u) {
-                const int i = i0 + u * NT;
-                v[u] = nparts > 0 ? __float_as_uint(finish(pd[u], pc[u])) : (i < nlist ? row[i] : 0u);
-            }
-#pragma unroll
-            for (int u = 0; u < US; ++u) {
-                const int i = i0 + u * NT;
-                if (i < nlist) s_row[i] = v[u];
+                const int i = i_beg + i0 + u * NT;
+                pd[u] = i < i_end ? dot_of(i) : 0.f;
+                pc[u] = i < i_end ? cn[i] : 0.f;
             }
         }
-        row = s_row;
+#pragma unroll
+        for (int u = 0; u < US; ++u) {
+            const int i = i_beg + i0 + u * NT;
+            v[u] = nparts > 0 ? __float_as_uint(finish(pd[u], pc[u])) : (i < i_end ? drow[i] : 0u);
+        }
+#pragma unroll
+        for (int u = 0; u < US; ++u)
+            if (i0 + u * NT < len) s_row[i0 + u * NT] = v[u];
     }
     __syncthreads();
-    auto key_at = [&](int i) { return ((uint64_t)row[i] << 32) | (uint32_t)i; };
-    // Rows too long for LDS are cut down first, in two sweeps over global memory with sixteen loads in flight per
-    // thread: the centres are dealt to kSelGroups groups (centre i to group i mod kSelGroups) and every group
-    // keeps its smallest key; the nprobe-th smallest of those minima is an upper bound of the nprobe-th smallest
-    // key of the row (the minima are nprobe different keys of the row at or below it), so the second sweep
-    // collects every key up to that bound - about kSelGroups * -ln(1 - nprobe / kSelGroups) of them for
-    // exchangeable distances - and the selection runs on the collected keys in LDS.  (Selecting on the row itself
-    // takes five or more sweeps of dependent loads.)  More than kSelCand collected keys: the row is used after all.
-    bool from_cand = false;
-    uint64_t *s_cand = reinterpret_cast<uint64_t *>(sel_smem) + kSelGroups;
-    if (!stage_row) {
-        uint64_t *s_gmin = reinterpret_cast<uint64_t *>(sel_smem);
-        constexpr int U = 16;
-        static_assert(U % 4 == 0, "a thread owns four groups: tid + NT * (0..3)");
-        constexpr int kGroups = 4 * NT;
-        uint64_t gm[4] = {kSentinel, kSentinel, kSentinel, kSentinel};
-        for (int i0 = tid; i0 < nlist; i0 += U * NT) {
-            float v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * NT;
-                v[u] = i < nlist ? (nparts > 0 ? dist_of(i) : grow[i]) : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * NT;
-                if (i < nlist) {
-                    if (nparts > 0) grow[i] = v[u];         // the distances replace part 0 in place (re-read by this thread only)
-                    const uint64_t key = ((uint64_t)__float_as_uint(v[u]) << 32) | (uint32_t)i;
-                    gm[u & 3] = key < gm[u & 3] ? key : gm[u & 3];
-                }
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) s_gmin[g * NT + tid] = gm[g];
-        if (tid == 0) s_ncand = 0;
-        __syncthreads();
-        auto gmin_at = [&](int i) { return s_gmin[i]; };
-        const uint64_t T0 = block_select_kth(gmin_at, kGroups, nprobe, s_hist, s_state);
-        for (int i0 = tid; i0 < nlist; i0 += U * NT) {
-            uint32_t v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * NT;
-                v[u] = i < nlist ? row[i] : 0xFFFFFFFFu;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u * NT;
-                const uint64_t key = ((uint64_t)v[u] << 32) | (uint32_t)i;
-                if (i < nlist && key <= T0) {
-                    const unsigned slot = atomicAdd(&s_ncand, 1u);
-                    if (slot < (unsigned)kSelCand) s_cand[slot] = key;
-                }
+    if (len > 0) {   // first level: the slice's min(nprobe, len) smallest keys (uniform)
+        auto key_at = [&](int i) { return ((uint64_t)s_row[i] << 32) | (uint32_t)(i_beg + i); };
+        const uint64_t T = block_select_kth(key_at, len, min(nprobe, len), s_hist, s_state);
+        for (int i = tid; i < len; i += NT) {
+            const uint64_t key = key_at(i);
+            if (key <= T) {                                  // exactly min(nprobe, len) keys qualify (keys are distinct)
+                const unsigned slot = atomicAdd(&s_count, 1u);
+                if (slot < (unsigned)np2) s_keys[slot] = key;
             }
         }
         __syncthreads();
-        from_cand = s_ncand <= (unsigned)kSelCand;         // uniform
     }
-    if (from_cand) {
-        const int ncand = (int)s_ncand;
-        auto cand_at = [&](int i) { return s_cand[i]; };
+    if (G > 1) {                                             // uniform
+        // the slice's keys (padded with the sentinel) join the query's candidates; the last slice to arrive goes on
+        uint64_t *mine = selcand + ((size_t)qi * G + g) * nprobe;
+        for (int i = tid; i < nprobe; i += NT) store_key(mine + i, s_keys[i]);
+        publish_keys();
+        if (tid == 0) s_ticket = atomicAdd(&qticket[qi], 1u);
+        __syncthreads();
+        if (s_ticket != (unsigned)(G - 1)) return;          // uniform
+        if (tid == 0) { __hip_atomic_store(&qticket[qi], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); s_count = 0; }
+        // G * nprobe candidates: in LDS when they fit there (the slice is no longer needed), else where they are
+        uint64_t *s_cand = reinterpret_cast<uint64_t *>(sel_smem);
+        const uint64_t *all = selcand + (size_t)qi * G * nprobe;
+        const int ncand = G * nprobe;
+        const bool in_lds = cand_in_lds != 0;                // uniform
+        if (in_lds) {
+            for (int i0 = tid; i0 < ncand; i0 += 8 * NT) {   // 8 loads in flight per thread
+                uint64_t key[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) key[u] = i0 + u * NT < ncand ? load_key(all + i0 + u * NT) : kSentinel;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (i0 + u * NT < ncand) s_cand[i0 + u * NT] = key[u];
+            }
+        }
+        for (int i = tid; i < np2; i += NT) s_keys[i] = kSentinel;
+        __syncthreads();
+        auto cand_at = [&](int i) { return in_lds ? s_cand[i] : load_key(all + i); };
         const uint64_t T = block_select_kth(cand_at, ncand, nprobe, s_hist, s_state);
         for (int i = tid; i < ncand; i += NT) {
-            const uint64_t key = s_cand[i];
-            if (key <= T) {                                // exactly nprobe keys qualify (keys are distinct)
+            const uint64_t key = cand_at(i);
+            if (key <= T && key != kSentinel) {              // exactly nprobe keys qualify (nprobe <= nlist)
                 const unsigned slot = atomicAdd(&s_count, 1u);
                 if (slot < (unsigned)np2) s_keys[slot] = key;
             }
         }
-    } else {
-        const uint64_t T = block_select_kth(key_at, nlist, nprobe, s_hist, s_state);
-        for (int i = tid; i < nlist; i += NT) {
-            const uint64_t key = key_at(i);
-            if (key <= T) {
-                const unsigned slot = atomicAdd(&s_count, 1u);
-                if (slot < (unsigned)np2) s_keys[slot] = key;
-            }
-        }
+        __syncthreads();
     }
-    __syncthreads();
     if (np2 <= kWave) {                                      // uniform: up to 64 probes are sorted in the registers of one wave
         if (tid < kWave) wave_sort_u64(s_keys, np2);
         __syncthreads();
     } else {
-        block_bitonic_sort_u64(s_keys, np2);
+        // More: every key's place is the number of keys below it (the keys are all different), counted with reads
+        // that all lanes make at the same LDS address - one pass instead of the 36 to 55 barrier-separated steps of
+        // a bitonic network.  The sorted keys pass through the dynamic LDS (free by now, at least 8 * np2 bytes).
+        uint64_t *s_sorted = reinterpret_cast<uint64_t *>(sel_smem);
+        __syncthreads();
+        for (int i = tid; i < nprobe; i += NT) {
+            const uint64_t key = s_keys[i];
+            int below = 0;
+            for (int j0 = 0; j0 < nprobe; j0 += 8) {
+                uint64_t other[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) other[u] = s_keys[min(j0 + u, nprobe - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) below += (j0 + u < nprobe && other[u] < key) ? 1 : 0;
+            }
+            s_sorted[below] = key;
+        }
+        __syncthreads();
+        for (int i = tid; i < nprobe; i += NT) s_keys[i] = s_sorted[i];
+        __syncthreads();
     }
     for (int i = tid; i < nprobe; i += NT) {
         probe[(size_t)qi * probe_stride + i] = (int32_t)(s_keys[i] & 0xFFFFFFFFu);
@@ -608,9 +603,9 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
     if (mine.pcst)                                           // |q - c|^2 - |q|^2 = |c|^2 - 2 <q, c>
         for (int i = tid; i < nprobe; i += NT) mine.pcst[i] = __uint_as_float((uint32_t)(s_keys[i] >> 32)) - qn;
     plan_query(probe_at, nprobe, list_blk, list_len, mine);
-    // The workgroup that finishes last shares the scan workgroups out over the queries (saves a launch): every
-    // workgroup publishes its query's number of blocks with a device-scope store, waits for it to complete and
-    // adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
+    // The workgroup that finishes the last query shares the scan workgroups out over the queries (saves a launch):
+    // every query's workgroup publishes its number of blocks with a device-scope store, waits for it to complete
+    // and adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
     __syncthreads();
     if (tid == 0) {
         __hip_atomic_store(&tb[qi], (uint32_t)mine.pfx[nprobe], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -618,9 +613,9 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(float *__restrict__ D
         s_ticket = atomicAdd(arrived, 1u);
     }
     __syncthreads();
-    if (s_ticket != gridDim.x - 1) return;                  // uniform
-    auto blocks_of = [&](int q) { return (long long)__hip_atomic_load(&tb[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    share_plan(blocks_of, (int)gridDim.x, target, max_wg, share);
+    if (s_ticket != (unsigned)(nq - 1)) return;             // uniform
+    auto blocks_of = [&](int qq) { return (long long)__hip_atomic_load(&tb[qq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    share_plan(blocks_of, nq, target, max_wg, share);
     if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -960,9 +955,10 @@ __device__ __forceinline__ void store_probe_tables(const ScanArgs &a, const Scan
 // ------------------------------------------------------------------------------------------------
 
 // One table entry: squared distance between dsub query coordinates and dsub centre coordinates.  DSUB > 0
-// fixes dsub at compile time (all loads of several entries can then be in flight together).
+// fixes dsub at compile time (all loads of several entries can then be in flight together; the query's
+// coordinates are in registers).
 template <int DSUB>
-__device__ __forceinline__ float lut_entry(const float *__restrict__ qs, const float *__restrict__ c, int dsub) {
+__device__ __forceinline__ float lut_entry(const float *qs, const float *__restrict__ c, int dsub) {
     float acc = 0.f;
     if (DSUB > 0) {
         float cv[DSUB > 0 ? DSUB : 1];
@@ -991,45 +987,38 @@ __device__ __forceinline__ float lut_entry(const float *__restrict__ qs, const f
     return acc;
 }
 
-// Table build: workgroup (x, q) computes the rows j = 64x .. 64x+63 of query q's table, a wave 16 of them, 8 at
-// a time so that their loads overlap; lane <-> sub-quantiser, so the reads of pqT[j][m][.] and the writes of
-// lut[q][j][m] are contiguous.  grid = (4, nq), 256 threads.
+// Table build: workgroup (x, q) computes kKsub / gridDim.x rows j of query q's table, a wave a quarter of them, 8
+// at a time so that their loads overlap; lane <-> sub-quantiser, so the reads of pqT[j][m][.] and the writes of
+// lut[q][j][m] are contiguous.  A lane's slice of the query stays in registers for all its rows when dsub is
+// known at compile time (read from LDS per entry, lanes dsub words apart collide on the banks: measured 75 % of
+// the LDS cycles at dsub = 12); otherwise it is read from global memory, where it sits in the first-level cache.
+// grid = (4, 8 or 16 workgroups per query, nq), 256 threads.
 template <int DSUB>
 __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict__ q, const float *__restrict__ pqT, int d, int M,
                                                         int dsub, int Mp, float *__restrict__ lut_out) {
-    extern __shared__ __align__(16) unsigned char lsmem[];
-    float *s_q = reinterpret_cast<float *>(lsmem);      // [d] the query
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = blockIdx.y;
-    for (int t = tid; t < d; t += 256) s_q[t] = q[(size_t)qi * d + t];
-    __syncthreads();
+    const int rows_per_wave = kKsub / (int)gridDim.x / 4;      // 16, 8 or 4
     float *out = lut_out + (size_t)qi * kKsub * Mp;
     for (int m = lane; m < Mp; m += kWave) {
-        const float *qs = s_q + m * dsub;
+        const float *qg = q + (size_t)qi * d + (size_t)min(m, M - 1) * dsub;
+        float qr[DSUB > 0 ? DSUB : 1];
+        if (DSUB > 0) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int j0 = blockIdx.x * 64 + wave * 16 + it * 8;
+            for (int t = 0; t < DSUB; ++t) qr[t] = qg[t];
+        }
+        const float *qs = DSUB > 0 ? qr : qg;
+        for (int j0 = blockIdx.x * 4 * rows_per_wave + wave * rows_per_wave, it = 0; it < rows_per_wave; it += 8, j0 += 8) {
             float e[8];
+            const int nj = min(8, rows_per_wave - it);         // 8, or 4 with 16 workgroups per query (uniform)
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj)
-                e[jj] = m < M ? lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub) : 0.f;
+                e[jj] = (m < M && jj < nj) ? lut_entry<DSUB>(qs, pqT + ((size_t)(j0 + jj) * M + m) * dsub, dsub) : 0.f;
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) out[(size_t)(j0 + jj) * Mp + m] = e[jj];
+            for (int jj = 0; jj < 8; ++jj)
+                if (jj < nj) out[(size_t)(j0 + jj) * Mp + m] = e[jj];
         }
     }
-}
-
-// Keys that one workgroup writes and another reads within the same launch go through device-scope atomic
-// stores and loads (they bypass the per-XCD caching that is not coherent across the chip), ordered by
-// publish_keys(): wait until this thread's stores are acknowledged, then meet the workgroup; a counter
-// increment after that tells the others.  No cache-wide write-back or invalidation is involved (a full fence
-// by every finishing workgroup costs far more than the merge itself).
-__device__ __forceinline__ void store_key(uint64_t *p, uint64_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ uint64_t load_key(const uint64_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void publish_keys() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): loads and stores of this thread are complete
-    __syncthreads();
 }
 
 // Selection from a key list by one workgroup: the k smallest of the keys in list[0..n) (global memory, written by
@@ -1398,8 +1387,9 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 // ------------------------------------------------------------------------------------------------
 template <int DSUB>
 void launch_lut_build_d(const piperag_index *ix, const float *q, int nq, float *lut, hipStream_t st) {
-    hipLaunchKernelGGL((lut_build_kernel<DSUB>), dim3(4, nq), dim3(256), sizeof(float) * ix->p.d, st, q, ix->pqT, ix->p.d, ix->p.M,
-                       ix->dsub, ix->Mp, lut);
+    const int per_query = nq >= 64 ? 4 : (nq >= 16 ? 8 : 16);     // workgroups per query: enough of them for small batches
+    hipLaunchKernelGGL((lut_build_kernel<DSUB>), dim3(per_query, nq), dim3(256), 0, st, q, ix->pqT, ix->p.d, ix->p.M, ix->dsub,
+                       ix->Mp, lut);
 }
 
 void launch_lut_build(const piperag_index *ix, const float *q, int nq, float *lut, hipStream_t st) {
@@ -1465,7 +1455,7 @@ PlanOut plan_bufs(const piperag_index *ix, const SearchWs &ws) {
     return PlanOut{ws.pfx, ws.pblk, ws.plen, ws.scanned, ws.thr, ix->p.residual ? ws.pcst : nullptr, ws.done};
 }
 
-ShareOut share_bufs(const SearchWs &ws) { return ShareOut{ws.seg0, ws.desc, ws.ctr, ws.done + ws.max_nq}; }
+ShareOut share_bufs(const SearchWs &ws, int fan) { return ShareOut{ws.seg0, ws.desc, ws.ctr, ws.done + ws.max_nq, fan}; }
 
 // Parts of the depth the matrix-core coarse quantiser is split into for this shape (0: the row-wise kernel
 // runs instead and writes finished distances).
@@ -1479,20 +1469,30 @@ int coarse_parts(const piperag_index *ix, const float *q, int nq) {
     return parts;
 }
 
-int launch_select(const piperag_index *ix, const SearchWs &ws, const float *q, int nq, int nprobe, int target, int max_wg,
+int launch_select(const piperag_index *ix, const SearchWs &ws, const float *q, int nq, int nprobe, int target, int max_wg, int fan,
                   hipStream_t st) {
     const int nlist = ix->p.nlist;
-    const int stage = nlist <= kSelMaxLdsRow;
-    const size_t lds = stage ? sizeof(float) * (size_t)nlist : sizeof(uint64_t) * (kSelGroups + kSelCand);
-    if (nlist <= kSelSmallRow)
-        hipLaunchKernelGGL(select_probes_kernel<kSelThreads>, dim3(nq), dim3(kSelThreads), lds, st, ws.D, coarse_parts(ix, q, nq),
-                           q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ws.probe, ws.probe_d, ws.max_nprobe, ix->list_blk,
-                           ix->list_len, plan_bufs(ix, ws), ws.tb, ws.tb + ws.max_nq, target, max_wg, share_bufs(ws));
+    const int G = select_groups(nlist, nq, nprobe, ix->ncu);
+    const int slice_len = ((nlist + G - 1) / G + 3) / 4 * 4;
+    const int np2 = next_pow2(std::max(2, nprobe));
+    // the candidates of a query's slices are selected in LDS when they fit (they do, unless the row is so long that
+    // the slices LDS allows, times nprobe, exceed it: more than half a million lists with nprobe 1024)
+    const size_t cand_bytes = G > 1 ? sizeof(uint64_t) * (size_t)G * nprobe : 0;
+    const int cand_in_lds = cand_bytes <= sizeof(float) * kSelMaxLdsRow;
+    const size_t lds = std::max(std::max(sizeof(float) * (size_t)slice_len, cand_in_lds ? cand_bytes : 0), sizeof(uint64_t) * (size_t)np2);
+    PR_REQUIRE(slice_len <= kSelMaxLdsRow && np2 <= kMaxNprobe, PIPERAG_ERR_LIMIT,
+               "probe selection does not fit: nlist = %d, nprobe = %d", nlist, nprobe);
+    uint32_t *arrived = ws.tb + ws.max_nq, *qticket = ws.tb + ws.max_nq + 1;
+    if (slice_len <= kSelSmallRow)
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreads>, dim3(nq * G), dim3(kSelThreads), lds, st, ws.D, coarse_parts(ix, q, nq),
+                           nq, G, slice_len, cand_in_lds, q, ix->p.d, ix->cnorm, nlist, nprobe, ws.probe, ws.probe_d, ws.max_nprobe,
+                           ix->list_blk, ix->list_len, plan_bufs(ix, ws), ws.selcand, qticket, ws.tb, arrived, target, max_wg,
+                           share_bufs(ws, fan));
     else
-        hipLaunchKernelGGL(select_probes_kernel<kSelThreadsLong>, dim3(nq), dim3(kSelThreadsLong), lds, st, ws.D,
-                           coarse_parts(ix, q, nq), q, ix->p.d, ix->cnorm, nlist, nprobe, stage, ws.probe, ws.probe_d,
-                           ws.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix, ws), ws.tb, ws.tb + ws.max_nq, target,
-                           max_wg, share_bufs(ws));
+        hipLaunchKernelGGL(select_probes_kernel<kSelThreadsLong>, dim3(nq * G), dim3(kSelThreadsLong), lds, st, ws.D,
+                           coarse_parts(ix, q, nq), nq, G, slice_len, cand_in_lds, q, ix->p.d, ix->cnorm, nlist, nprobe, ws.probe, ws.probe_d,
+                           ws.max_nprobe, ix->list_blk, ix->list_len, plan_bufs(ix, ws), ws.selcand, qticket, ws.tb, arrived,
+                           target, max_wg, share_bufs(ws, fan));
     return PIPERAG_OK;
 }
 
@@ -1541,8 +1541,9 @@ int check_search_limits(const piperag_index *ix, int32_t nq, int32_t nprobe, int
     return PIPERAG_OK;
 }
 
-// Scan workgroups a search call asks the plan for: two per compute unit, or for large batches about 8 per query.
-int scan_target_wgs(int nq) { return std::min(kMaxScanWGs, std::max(kTargetScanWGs, 8 * nq)); }
+// Scan workgroups a search call asks the plan for: two per compute unit the search may use (the whole chip unless
+// piperag_set_compute_units says otherwise), or for large batches about 8 per query.
+int scan_target_wgs(int nq, int ncu) { return std::min(kMaxScanWGs, std::max(std::min(kTargetScanWGs, 2 * ncu), 8 * nq)); }
 
 // Enqueues one search on st, with `ws` as its scratch (kernel launches and event operations only: it can be
 // captured into a graph).  fork: the tables are built on the index's side stream beside the selection;
@@ -1553,51 +1554,55 @@ int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool fork, const
     const int pstride = ws.max_nprobe;
     const bool tm = ix->timing && fork;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
-    // The coarse quantiser is enqueued first (the whole call waits for it); then the fork: the tables need only the
-    // queries and are built on the side stream beside the selection.
+    // The tables need only the queries: with the fork they are built on the side stream beside the coarse
+    // quantiser and the selection, and joined before the scan.
+    if (fork) PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));                 // the fork point: before the coarse quantiser ...
     if (!probes && (rc = launch_coarse(ix, ws, q, nq, st)) != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
-    if (fork) {
-        PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));
+    if (fork) {                                                              // ... which is submitted first all the same
         PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
         launch_lut_build(ix, q, nq, ws.lut, ix->side);
         PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
     } else {
         launch_lut_build(ix, q, nq, ws.lut, st);
     }
-    const int target_wgs = scan_target_wgs(nq);
+    const int target_wgs = scan_target_wgs(nq, ix->ncu);
     const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
+    const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
+    // Candidate slots of a scan workgroup: as many as kCandRoom beyond the keys kept, but fewer if that lets two
+    // workgroups share a compute unit's 160 KiB of LDS (long probe tables would otherwise push the second one out).
+    int cand_room = kCandRoom;
+    {
+        const size_t half = 80 * 1024, fixed = scan_lds_bytes(ix->Mp, KW, nprobe);
+        if (fixed + 8 * (size_t)kCandRoom > half && fixed + 8 * (size_t)kCandRoomMin <= half) cand_room = (int)((half - fixed) / 8);
+    }
+    const int cap = KW + cand_room;
+    // the query's last workgroup selects the results in the LDS that held its table and candidates: `room` keys,
+    // i.e. the keys of `fan` workgroups; more workgroups per query are merged in groups of fan first; if two levels
+    // do not cover a query's workgroups (very large k with short codes), there are no groups and a long list is
+    // selected in global memory
+    const int room = reduce_room_keys(ix->Mp, cap, k);
+    int fan = std::max(1, room / KW);
+    if ((long long)fan * fan < G) fan = G;
     if (!probes) {
-        if ((rc = launch_select(ix, ws, q, nq, nprobe, target_wgs, G, st)) != PIPERAG_OK) return rc;
+        if ((rc = launch_select(ix, ws, q, nq, nprobe, target_wgs, G, fan, st)) != PIPERAG_OK) return rc;
     } else {
         hipLaunchKernelGGL(copy_probes_kernel, dim3(nq), dim3(64), 0, st, probes, nprobe, ix->p.nlist, ws.probe, pstride,
                            ix->list_blk, ix->list_len, plan_bufs(ix, ws));
-        hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ws.pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ws));
+        hipLaunchKernelGGL(share_kernel, dim3(1), dim3(256), 0, st, ws.pfx, pstride, nprobe, nq, target_wgs, G, share_bufs(ws, fan));
         if (ix->p.residual)
             hipLaunchKernelGGL(probe_const_kernel, dim3(nprobe, nq), dim3(64), 0, st, q, ix->centroids, ix->cnorm, ix->p.d,
                                ws.probe, pstride, ws.pcst);
     }
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
-    const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
     ScanArgs a{ix->codes, ws.lut, ws.pfx, ws.pblk, ws.plen, ix->p.residual ? ws.pcst : nullptr,
                ix->p.residual ? ix->tx : nullptr, ws.part, ws.thr, ws.desc, ws.ctr, nprobe, pstride, k, KW};
     if (fork) PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
-    // Candidate slots: as many as kCandRoom beyond the keys kept, but fewer if that lets two workgroups share a
-    // compute unit's 160 KiB of LDS (long probe tables would otherwise push the second one out).
-    int room = kCandRoom;
-    {
-        const size_t half = 80 * 1024, fixed = scan_lds_bytes(ix->Mp, KW, nprobe);
-        if (fixed + 8 * (size_t)kCandRoom > half && fixed + 8 * (size_t)kCandRoomMin <= half) room = (int)((half - fixed) / 8);
-    }
-    a.cap = KW + room;
-    // the query's last workgroup selects the results in the LDS that held its table and candidates
+    a.cap = cap;
     a.qdone = ws.done;
-    a.room = reduce_room_keys(ix->Mp, a.cap, k);
-    // groups of workgroups whose keys fit one selection; if two levels do not cover a query's workgroups (very large
-    // k with short codes), there are no groups and a long list is selected in global memory
-    a.fan = std::max(1, a.room / KW);
-    if ((long long)a.fan * a.fan < G) a.fan = G;
+    a.room = room;
+    a.fan = fan;
     a.gdone = ws.done + ws.max_nq;
     a.part2 = ws.part2;
     a.ids = ix->ids; a.out_d = out_d; a.out_i = out_i;
@@ -1705,7 +1710,9 @@ size_t search_ws_layout(SearchWs *ws, void *base, int nlist, int Mp, int max_nq,
     take(&ws->seg0, nq + 1);
     take(&ws->desc, wgs + nq);
     take(&ws->done, wgs + 2 * nq);
-    take(&ws->tb, nq + 1);
+    take(&ws->tb, 2 * nq + 1);
+    // selection workgroups of a batch: at most 64 per query and kSelTargetWGs in all, unless long rows need more
+    take(&ws->selcand, std::max(nq * (size_t)((nlist + kSelMaxLdsRow - 1) / kSelMaxLdsRow), std::min((size_t)kSelTargetWGs, nq * 64)) * np);
     take(&ws->ctr, nq * kCtrPerQuery * kCtrStride);
     take(&ws->pcst, nq * np);
     take(&ws->pblk, nq * np);
@@ -1769,7 +1776,7 @@ int piperag_ivfpq_search_static(const piperag_index *index, const float *queries
     PR_CHECK_HIP(hipSetDevice(index->device));
     // the scratch is carved for exactly this call's sizes; what does not fit the static array is refused
     SearchWs ws;
-    const int wgs = std::max(scan_target_wgs(nq), (int)nq);
+    const int wgs = std::max(scan_target_wgs(nq, index->ncu), (int)nq);
     const size_t need = search_ws_layout(&ws, nullptr, index->p.nlist, index->Mp, nq, nprobe, k, wgs);
     PR_REQUIRE(need <= (size_t)PIPERAG_STATIC_SCRATCH_BYTES, PIPERAG_ERR_LIMIT,
                "this search needs %zu bytes of scratch; the static scratch array holds %zu (smaller nq, nprobe or k)", need,
@@ -1783,8 +1790,8 @@ int piperag_ivfpq_search_static(const piperag_index *index, const float *queries
     search_ws_layout(&ws, ptr, index->p.nlist, index->Mp, nq, nprobe, k, wgs);
     hipStream_t st = (hipStream_t)stream;
     // the array keeps the last call's contents, laid out for that call's sizes: the count of finished selections
-    // must start at zero (everything else is written before it is read)
-    hipLaunchKernelGGL(clear_u32_kernel, dim3(1), dim3(64), 0, st, ws.tb + nq, 1);
+    // and the per-query tickets behind it must start at zero (everything else is written before it is read)
+    hipLaunchKernelGGL(clear_u32_kernel, dim3((nq + 1 + 255) / 256), dim3(256), 0, st, ws.tb + nq, nq + 1);
     index->last_nq = nq;
     index->last_scanned = ws.scanned;
     return enqueue_search(index, ws, false, queries_dev, nq, nullptr, nprobe, k, out_dist_dev, out_ids_dev, st);
@@ -1805,7 +1812,7 @@ int piperag_ivf_coarse(const piperag_index *index, const float *queries_dev, int
     const SearchWs &ws = ix->ws;
     const int rc = launch_coarse(ix, ws, queries_dev, nq, st);
     if (rc != PIPERAG_OK) return rc;
-    const int rc2 = launch_select(ix, ws, queries_dev, nq, nprobe, kTargetScanWGs, std::max(kTargetScanWGs, (int)nq), st);
+    const int rc2 = launch_select(ix, ws, queries_dev, nq, nprobe, kTargetScanWGs, std::max(kTargetScanWGs, (int)nq), kMaxScanWGs, st);
     if (rc2 != PIPERAG_OK) return rc2;
     PR_CHECK_HIP(hipMemcpy2DAsync(out_lists_dev, sizeof(int32_t) * nprobe, ws.probe, sizeof(int32_t) * ws.max_nprobe,
                                   sizeof(int32_t) * nprobe, nq, hipMemcpyDeviceToDevice, st));
@@ -1862,6 +1869,16 @@ int piperag_set_graph_replay(piperag_index *index, int enable) {
     PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
     index->replay = enable != 0;
     if (!index->replay) drop_graphs(index);
+    return PIPERAG_OK;
+}
+
+int piperag_set_compute_units(piperag_index *index, int32_t ncu) {
+    PR_REQUIRE(index != nullptr, PIPERAG_ERR_ARG, "index is NULL");
+    int total = 0;
+    PR_CHECK_HIP(hipDeviceGetAttribute(&total, hipDeviceAttributeMultiprocessorCount, index->device));
+    PR_REQUIRE(ncu <= total, PIPERAG_ERR_ARG, "ncu = %d exceeds the device's %d compute units", ncu, total);
+    index->ncu = ncu <= 0 ? total : ncu;
+    drop_graphs(index);              // a captured search holds the launch shapes of the time it was captured
     return PIPERAG_OK;
 }
 
