@@ -125,12 +125,29 @@ def _grid_of(row):
     return 0
 
 
+def duration_populations(v, gap=1.8):
+    """Launches of one kernel and grid, split into populations of durations: the sorted durations are cut wherever
+    one is more than `gap` times the one before it (the bench launches the scan on the timed batch, on smaller
+    batches and on single queries with the same grid).  Returns [(tag, durations)], longest population first; one
+    population has an empty tag."""
+    vs = sorted(v)
+    groups = [[vs[0]]]
+    for a, b in zip(vs, vs[1:]):
+        if b > gap * a:
+            groups.append([])
+        groups[-1].append(b)
+    if len(groups) == 1:
+        return [("", vs)]
+    groups.reverse()
+    return [(f" [population {i + 1} of {len(groups)}]", g) for i, g in enumerate(groups)]
+
+
 def summarize_rocprof(root, command):
     """Short text summary of rocprofv3 --output-format csv results: per-kernel totals from the kernel trace and
     per-kernel means of every counter collected.  Launches of one kernel are listed per grid size, because the
-    bench launches the search both on the full batch and on a single query; where the grid is the same for both
-    (the scan: spare workgroups exit at once) and the durations differ by more than 3x, the launches are split
-    at the geometric mean of the shortest and the longest into [long] and [short]."""
+    bench launches the search on the timed batch, on smaller batches and on a single query; where the grid is the
+    same for all (the scan: spare workgroups exit at once), the launches are split into populations of
+    durations (see duration_populations)."""
     import collections
     import csv
     lines = [f"command: {command}" if command else "command: (not given)"]
@@ -145,11 +162,7 @@ def summarize_rocprof(root, command):
                 lines.append(f"kernel trace ({f}): kernel, grid threads, calls, total us, average us, min us, max us, share")
                 for (name, grid), v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
                     short = shorten(name)
-                    groups = [("", v)]
-                    if max(v) > 3 * min(v):      # two populations in one grid (e.g. full batch and single query): split
-                        cut = (min(v) * max(v)) ** 0.5
-                        groups = [(" [long]", [t for t in v if t >= cut]), (" [short]", [t for t in v if t < cut])]
-                    for tag, g in groups:
+                    for tag, g in duration_populations(v):
                         lines.append(f"  {short + tag:50s} {grid:9d} {len(g):6d} {sum(g):12.1f} {sum(g)/len(g):10.2f} {min(g):10.2f} "
                                      f"{max(g):10.2f} {100*sum(g)/tot:6.2f}%")
             if f.endswith("counter_collection.csv"):
@@ -332,7 +345,7 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "paper"])
     ap.add_argument("--batches", type=int, default=8, help="different query batches the steps go round (default 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop (profiling runs)")
+    ap.add_argument("--no-latency", action="store_true", help="skip the single-query latency loop and the scans at other batch sizes (counter runs: every scan launch is then the timed batch)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB copy kernel three times (reference for the HBM traffic counters)")
     ap.add_argument("--residual", action="store_true",
@@ -409,7 +422,7 @@ def main():
     by_nq = {}
     ix.set_stage_timing(True)
     for nq_x in sorted({1, 16, cfg.nq} - {cfg.nq}):
-        if nq_x > cfg.nq:
+        if nq_x > cfg.nq or args.no_latency:
             continue
         fr = []
         for r in range(12):

@@ -134,7 +134,9 @@ void piperag_ivf_free(piperag_index *index);
  *   queries_dev f32 [nq*d];  out_dist_dev f32 [nq*k];  out_ids_dev i64 [nq*k].
  * Per query: ascending by (distance, id); distance = sum over m of the squared distance between the
  * query's m-th slice and the centre the code selects; when the probed lists hold fewer than k vectors
- * the remaining slots are id -1, distance +inf.  1 <= nq <= max_nq, 1 <= nprobe <= min(nlist,
+ * the remaining slots are id -1, distance +inf.  Which vectors are returned when more of them share the
+ * k-th distance, bit for bit, than there are places left: those stored first in the index (the scan
+ * selects by (distance, position), deterministically); only the order of the returned rows is by id.  1 <= nq <= max_nq, 1 <= nprobe <= min(nlist,
  * max_nprobe), 1 <= k <= max_k, else PIPERAG_ERR_LIMIT / PIPERAG_ERR_ARG.  nq == 0 is a no-op. */
 int piperag_ivfpq_search(const piperag_index *index, const float *queries_dev, int32_t nq, int32_t nprobe,
                          int32_t k, float *out_dist_dev, int64_t *out_ids_dev, void *stream);

@@ -172,13 +172,13 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(const float *__restrict_
 // of one vector in its own registers and walks them in ascending centre order (strict "<": lower index on equal
 // values); the two lanes that share a vector are combined with lane exchanges.
 // v orders the centres like the distance does up to its rounding errors, which are relative to |x_m||p| and not
-// to the distance, so the decision is made exact the way the list assignment's is: a lane keeps its two
-// smallest v, their centres and its third smallest v; with v1 the pair's smallest, every centre that could be
-// the nearest has v <= v1 + margin (margin = 4 (T + 2) 2^-24 (|x_m|^2 + |p1|^2): twice a bound on the error of a
-// v over T + 2 roundings).  One kept centre within the margin: it is the code.  Several: their direct-form fp32
-// distances sum_t (x_t - p_t)^2 decide, lower index on equal values.  A third smallest v within the margin as
-// well: the lane computes the direct form for all its 128 centres.  Codes are collected in LDS and written out
-// as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
+// to the distance, so the decision is made exact the way the list assignment's is: a lane keeps its smallest v
+// with its centre, and its second smallest v; with v1 and v2 the two smallest of the pair, every centre that
+// could be the nearest has v <= v1 + margin (margin = 4 (T + 2) 2^-24 (|x_m|^2 + |p1|^2): twice a bound on the
+// error of a v over T + 2 roundings).  v2 beyond the margin: v1's centre is the code.  Otherwise (a few (vector,
+// sub-quantiser) pairs in a thousand at the benchmark's mixtures) both lanes compute the direct form
+// sum_t (x_t - p_t)^2 for all their centres, lower index on equal values.  Codes are collected in LDS and written
+// out as one contiguous run.  T = pqe_rows(dsub) depth rows (even), dsub <= 32.
 __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__restrict__ x, int64_t n, int d,
                                                              const float *__restrict__ pqE, int M, int dsub, int T,
                                                              const int32_t *__restrict__ lists, const float *__restrict__ cent,
@@ -224,43 +224,31 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
 #pragma unroll
             for (int bi = 0; bi < 8; ++bi) acc[bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi * 32], bv, acc[bi], 0, 0, 0);
         }
-        float b1v = inf, b2v = inf, b3v = inf;
-        int b1c = 0, b2c = 0;
+        float b1v = inf, b2v = inf;                               // smallest v and its centre; second smallest v
+        int b1c = 0;
 #pragma unroll
         for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; ++r) {                        // ascending in bi, r = ascending centre; no branches
                 const float v = acc[bi][r];
-                if (v < b3v) {                                    // ascending in bi, r = ascending centre
-                    const int c = centre_of(bi, r);
-                    if (v < b2v) {
-                        b3v = b2v;
-                        if (v < b1v) { b2v = b1v; b2c = b1c; b1v = v; b1c = c; } else { b2v = v; b2c = c; }
-                    } else {
-                        b3v = v;
-                    }
-                }
+                const bool lt = v < b1v;
+                b2v = fminf(b2v, lt ? b1v : v);
+                b1c = lt ? centre_of(bi, r) : b1c;
+                b1v = lt ? v : b1v;
             }
         // the pair's smallest v, its centre and the margin
-        const float o1v = __shfl_xor(b1v, 32, 64), xn = 0.25f * (xq + __shfl_xor(xq, 32, 64));
+        const float o1v = __shfl_xor(b1v, 32, 64), o2v = __shfl_xor(b2v, 32, 64), xn = 0.25f * (xq + __shfl_xor(xq, 32, 64));
         const int o1c = __shfl_xor(b1c, 32, 64);
         const bool mine_first = b1v < o1v || (b1v == o1v && b1c < o1c);
         const float v1 = mine_first ? b1v : o1v;
         int code = mine_first ? b1c : o1c;
         const float limit = v1 + margin_scale * (xn + sA[dsub * kKsub + code]);
-        const bool more = (mine_first ? b2v : b1v) <= limit;      // a kept centre of mine, other than the pair's first, within the margin
-        const bool incomplete = b3v <= limit;                     // ... or one that was not kept
-        if (__any(more || incomplete)) {                          // seldom: direct-form distances decide
+        // the pair's second smallest v: the other lane's smallest, or the second smallest of either lane
+        const float v2 = fminf(fminf(b2v, o2v), mine_first ? o1v : b1v);
+        if (__any(v2 <= limit)) {                                 // seldom: direct-form distances decide
             float best_d = inf;
             int best_c = 256;
-            auto direct = [&](int c) {
-                float a2 = 0.f;
-                for (int t = 0; t < dsub; ++t) { const float e1 = x_at(m, t) - sA[t * kKsub + c]; a2 += e1 * e1; }
-                if (a2 < best_d || (a2 == best_d && c < best_c)) { best_d = a2; best_c = c; }
-            };
-            const bool pair_incomplete = __shfl_xor((int)incomplete, 32, 64) != 0 || incomplete;
-            const bool pair_more = __shfl_xor((int)more, 32, 64) != 0 || more;
-            if (pair_incomplete) {                                // every centre of this lane
+            if (v2 <= limit) {                                    // the same for both lanes of the pair: every centre of this lane
 #pragma unroll
                 for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
@@ -281,11 +269,6 @@ __global__ __launch_bounds__(256) void pq_encode_mfma_kernel(const float *__rest
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         if (acc[bi][r] < best_d) { best_d = acc[bi][r]; best_c = centre_of(bi, r); }
-            } else if (pair_more) {                               // the kept centres within the margin
-                if (b1v <= limit) direct(b1c);
-                if (b2v <= limit) direct(b2c);
-            }
-            if (pair_incomplete || pair_more) {
                 const float od = __shfl_xor(best_d, 32, 64);
                 const int oc = __shfl_xor(best_c, 32, 64);
                 code = (od < best_d || (od == best_d && oc < best_c)) ? oc : best_c;
@@ -443,7 +426,8 @@ __global__ void split_f16_kernel(const float *__restrict__ src, int64_t n, int d
 //   equal values.  If some source's third smallest v is also within the margin, a candidate may not have been
 //   kept: the vector goes to stage 3.
 // Stage 3 (assign_rows_direct_kernel + assign_rows_finish_kernel): the direct form against every centre for the
-//   vectors stage 2 could not settle (few, unless many centres lie within the rounding error of the nearest one).
+//   vectors stage 2 could not settle (a hundred or two per 262,144 at the benchmark's mixtures; most of them when
+//   many centres lie within the rounding error of the nearest one).
 constexpr float kAssignMargin = 4e-5f;
 constexpr int kAssignWords = 9;                // per (vector, centre range): 8 keys (value bits << 32 | centre) and the bound
 
@@ -741,7 +725,7 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
         const int nchunks = F16x3Tile::chunks_pad(d);
         const int64_t c_rp = F16x3Tile::rows_pad(K);
         // stage 3 splits the centres so that even a handful of rows keeps many compute units busy
-        const int per_split = std::max(TN, (K + 63) / 64 / TN * TN), splits = (K + per_split - 1) / per_split;
+        const int per_split = std::max(TN, (K + 255) / 256 / TN * TN), splits = (K + per_split - 1) / per_split;
         for (int64_t a = 0; a < n; a += slice) {
             const int64_t cnt = std::min(slice, n - a), rp = F16x3Tile::rows_pad(cnt);
             launch_split(x + a * ldx, cnt, d, ldx, x_amax, xs, xs + part, st);

@@ -8,7 +8,7 @@ sys.path.insert(0, ROOT)
 import bench  # noqa: E402
 
 
-def test_kernel_trace_summary_groups_by_kernel_and_grid_and_splits_two_populations(tmp_path):
+def test_kernel_trace_summary_groups_by_kernel_and_grid_and_splits_populations(tmp_path):
     d = tmp_path / "run" / "node"
     d.mkdir(parents=True)
     rows = ["Kernel_Name,Grid_Size,Start_Timestamp,End_Timestamp"]
@@ -16,19 +16,22 @@ def test_kernel_trace_summary_groups_by_kernel_and_grid_and_splits_two_populatio
         rows.append(f"void (anonymous namespace)::scan<4>(Args),131072,{1000 * i},{1000 * i + 100000}")   # 100 us
     for i in range(2):
         rows.append(f"void (anonymous namespace)::scan<4>(Args),131072,{9000 + i},{9000 + i + 10000}")    # 10 us
+    rows.append("void (anonymous namespace)::scan<4>(Args),131072,0,30000")                               # 30 us: a third population
     rows.append("void other(int),256,0,5000")                                                              # 5 us
     (d / "1_kernel_trace.csv").write_text("\n".join(rows) + "\n")
     text = bench.summarize_rocprof(str(tmp_path / "run"), "cmd --flag")
     lines = text.splitlines()
     assert lines[0] == "command: cmd --flag"
-    long_ = next(l for l in lines if "scan<4> [long]" in l).split()
-    short = next(l for l in lines if "scan<4> [short]" in l).split()
+    long_ = next(l for l in lines if "scan<4> [population 1 of 3]" in l).replace("[population 1 of 3]", "").split()
+    mid = next(l for l in lines if "scan<4> [population 2 of 3]" in l).replace("[population 2 of 3]", "").split()
+    short = next(l for l in lines if "scan<4> [population 3 of 3]" in l).replace("[population 3 of 3]", "").split()
+    assert mid[-7:-1] == ["131072", "1", "30.0", "30.00", "30.00", "30.00"]
     other = next(l for l in lines if l.strip().startswith("other")).split()
     # name [tag] grid calls total average min max share
     assert long_[-7:-1] == ["131072", "4", "400.0", "100.00", "100.00", "100.00"]
     assert short[-7:-1] == ["131072", "2", "20.0", "10.00", "10.00", "10.00"]
     assert other[-7:-1] == ["256", "1", "5.0", "5.00", "5.00", "5.00"]
-    assert abs(float(long_[-1].rstrip("%")) - 100 * 400 / 425) < 0.01
+    assert abs(float(long_[-1].rstrip("%")) - 100 * 400 / 455) < 0.01
 
 
 def test_counter_summary_gives_mean_min_max_per_dispatch(tmp_path):
