@@ -22,10 +22,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# The workload a plain `python bench.py` measures: a configuration the roofline target is stated on (the scan of
-# the two large indexes), whose whole run - building 268 M vectors included - stays well inside ten minutes.
-DEFAULT_WORKLOAD = "cfg3"
+# The workload a plain `python bench.py` measures: the largest single-GPU configuration, one of the two the roofline
+# target is stated on.  Its whole run takes about six minutes, 5.4 of them the build of 1.07 G vectors
+# (`--workload cfg3` is the other target configuration, 1.7 minutes).
+DEFAULT_WORKLOAD = "cfg4"
 PARITY_QUERIES = 32            # queries of the timed batch whose results are compared with the oracle
+LATENCY_CALLS = 200            # single-query searches the p50 latency is taken over, each with another query
 
 
 def log(*a):
@@ -337,6 +339,32 @@ def overlap_demo(args, pkg, cfg, torch):
     print(json.dumps({"workload": cfg.name, "tables": tables}), flush=True)
 
 
+def read_reference(torch):
+    """What a kernel that only reads reaches on this GPU, by launch shape: 8 GiB read with eight 16-byte loads in
+    flight per lane, ordinary and non-temporal, from 256 to 4,096 workgroups of 256 threads (the scan runs 512 to
+    2,048).  The reference the scan's fraction of the HBM peak is read against."""
+    from workload import gen_gpu
+    src = torch.empty(1 << 31, dtype=torch.float32, device="cuda").normal_()      # 8 GiB: far beyond every cache
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    nbytes = src.numel() * 4
+    print("| workgroups | ordinary loads GB/s | of 8 TB/s | non-temporal loads GB/s | of 8 TB/s |")
+    print("|---|---|---|---|---|")
+    rows = []
+    for wgs in (256, 512, 1024, 2048, 4096):
+        rates = []
+        for nt in (False, True):
+            ts = []
+            for r in range(7):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); gen_gpu.stream_read(src, wgs, nt, sink); e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            rates.append(nbytes / (float(np.median(ts[2:])) * 1e-3) / 1e9)
+        rows.append({"workgroups": wgs, "ordinary_GBps": rates[0], "nontemporal_GBps": rates[1]})
+        print(f"| {wgs} | {rates[0]:.0f} | {rates[0] / HBM_PEAK_GBS:.3f} | {rates[1]:.0f} | {rates[1] / HBM_PEAK_GBS:.3f} |")
+    print(json.dumps({"read_reference": rows, "bytes": nbytes}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -356,6 +384,8 @@ def main():
                     help="instead of the bench line: retrieval sized by the latency model, run beside a synthetic generation step")
     ap.add_argument("--overlap-cus", type=lambda t: [int(v) for v in t.split(",")], default=[0, 48, 64, 96],
                     help="with --overlap: compute units given to the search stream, one table per value (0 = no partition)")
+    ap.add_argument("--read-reference", action="store_true",
+                    help="instead of the bench line: the rate of a kernel that only reads, by launch shape (roofline reference)")
     ap.add_argument("--summarize", metavar="DIR", help="write a text summary of rocprofv3 CSV output found under DIR and exit")
     ap.add_argument("--command", default="", help="with --summarize: the command line that produced DIR")
     args = ap.parse_args()
@@ -373,6 +403,9 @@ def main():
     pkg.load_library()                      # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = gen.CONFIGS[args.workload]
+    if args.read_reference:
+        read_reference(torch)
+        return
     if args.nprobe_sweep:
         nprobe_sweep(args, pkg, cfg, torch)
         return
@@ -442,7 +475,8 @@ def main():
     q1 = q[:1].contiguous()                 # the caller's query buffer, refilled with another query before every call
     ix.set_graph_replay(True)               # a caller that waits for every search: repeated calls replay a captured graph
     lat = []
-    for r in range(0 if args.no_latency else args.warmup + args.steps):
+    # (its own number of calls, not the steps': single queries differ by a factor of ten in the vectors they scan)
+    for r in range(0 if args.no_latency else args.warmup + LATENCY_CALLS):
         q1.copy_(q_all[r % q_all.shape[0]][None])
         torch.cuda.synchronize()
         t1 = time.perf_counter()

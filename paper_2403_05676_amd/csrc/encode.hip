@@ -380,6 +380,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ s
     if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(out, m);
 }
 __global__ void zero_u32_kernel(uint32_t *p) { *p = 0u; }
+__global__ void zero_words_kernel(uint32_t *p, int n) { if ((int)threadIdx.x < n) p[threadIdx.x] = 0u; }
 
 // Power of two s with amax * s in [2^14, 2^15) (1 for a zero matrix), and the exponent of 1 / s.
 __device__ __forceinline__ int split_exponent(uint32_t amax_bits) {        // e with s = 2^e
@@ -423,10 +424,10 @@ __global__ void split_f16_kernel(const float *__restrict__ src, int64_t n, int d
 //   be the nearest has v <= v1 + margin (margin = kAssignMargin (|x|^2 + |c1|^2), a bound on twice the error of a
 //   v: a few 2^-24 per accumulation step of the product, the norms and the final subtraction).  The kept centres
 //   within the margin are compared by their direct-form fp32 distances sum_t (x_t - c_t)^2, lower index on
-//   equal values.  If some source's third smallest v is also within the margin, a candidate may not have been
-//   kept: the vector goes to stage 3.
-// Stage 3 (assign_rows_direct_kernel + assign_rows_finish_kernel): the direct form against every centre for the
-//   vectors stage 2 could not settle (a hundred or two per 262,144 at the benchmark's mixtures; most of them when
+//   equal values.  If the third smallest v of some source of a centre range is also within the margin, a
+//   candidate of that range may not have been kept: the vector goes to stage 3 for that range.
+// Stage 3 (assign_rows_direct_kernel + assign_rows_finish_kernel): the direct form against every centre of the
+//   range for the (vector, range) pairs stage 2 could not settle (a hundred or two per 262,144 at the benchmark's mixtures; most of them when
 //   many centres lie within the rounding error of the nearest one).
 constexpr float kAssignMargin = 4e-5f;
 constexpr int kAssignWords = 9;                // per (vector, centre range): 8 keys (value bits << 32 | centre) and the bound
@@ -523,14 +524,15 @@ __global__ __launch_bounds__(F16x3Tile::kThreads, 1) void assign_f16x3_kernel(in
     }
 }
 
-// One wavefront per vector (see the head of this section).  flist / nflag: rows handed to stage 3 and their
-// count; fkey[pos] is initialised for stage 3's atomic minimum.
+// One wavefront per vector (see the head of this section).  A centre range whose bound lies within the margin
+// may hold a nearer centre that was not kept: the vector joins that range's list for stage 3 (flist[range][..],
+// nflag[range]), and fkey[row] starts as the best found here, for stage 3's atomic minimum.
 __global__ __launch_bounds__(256) void assign_finish_kernel(const float *__restrict__ x, int64_t n, int d, int64_t ldx,
                                                             const float *__restrict__ cent, const float *__restrict__ cnorm, int K,
                                                             const uint64_t *__restrict__ cand, int R,
                                                             int32_t *__restrict__ out_idx, float *__restrict__ out_dist,
-                                                            uint32_t *__restrict__ flist, unsigned long long *__restrict__ fkey,
-                                                            uint32_t *__restrict__ nflag) {
+                                                            uint32_t *__restrict__ flist, int64_t flist_stride,
+                                                            unsigned long long *__restrict__ fkey, uint32_t *__restrict__ nflag) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n) return;
@@ -541,30 +543,27 @@ __global__ __launch_bounds__(256) void assign_finish_kernel(const float *__restr
     for (int off = 32; off > 0; off >>= 1) xn += __shfl_xor(xn, off, 64);
     // this lane's share of the words: entry e = range * kAssignWords + w
     constexpr int kPerLane = 3;                                // 64 * 3 >= kAssignWords * 16 ranges
-    uint64_t mine[kPerLane];
+    uint64_t mine[kPerLane];                                   // a key, or ~0
+    uint32_t bound[kPerLane];                                  // a range's bound (ordered bits), or ~0
     uint64_t k1 = ~0ull;
-    uint32_t t3 = 0xFFFFFFFFu;
 #pragma unroll
     for (int u = 0; u < kPerLane; ++u) {
         const int e = lane + 64 * u;
         mine[u] = ~0ull;
+        bound[u] = 0xFFFFFFFFu;
         if (e < R * kAssignWords) {
             const int r = e / kAssignWords, w = e - r * kAssignWords;
             const uint64_t word = cand[((size_t)r * n + row) * kAssignWords + w];
-            if (w == 8) t3 = min(t3, (uint32_t)word);
+            if (w == 8) bound[u] = (uint32_t)word;
             else if ((uint32_t)word < (uint32_t)K) { mine[u] = word; k1 = min(k1, word); }
         }
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        k1 = min(k1, (uint64_t)__shfl_xor((unsigned long long)k1, off, 64));
-        t3 = min(t3, (uint32_t)__shfl_xor(t3, off, 64));
-    }
+    for (int off = 32; off > 0; off >>= 1) k1 = min(k1, (uint64_t)__shfl_xor((unsigned long long)k1, off, 64));
     const bool any = k1 != ~0ull;                              // false only for values that are not numbers
     const float v1 = unordered_bits((uint32_t)(k1 >> 32));
     const float margin = kAssignMargin * (xn + (any ? cnorm[(uint32_t)k1] : 0.f));
     const float limit = v1 + margin;
-    const bool complete = any && !(unordered_bits(t3) <= limit);
     // direct-form distance to every kept centre within the margin, one after the other
     float best_d = __builtin_inff();
     int best_c = any ? (int)(uint32_t)k1 : 0;
@@ -584,32 +583,46 @@ __global__ __launch_bounds__(256) void assign_finish_kernel(const float *__restr
             if (a < best_d || (a == best_d && c < best_c)) { best_d = a; best_c = c; }
         }
     }
+    // ranges that may hold a nearer centre than the kept ones
+    bool handed_on = false;
+#pragma unroll
+    for (int u = 0; u < kPerLane; ++u) {
+        const int e = lane + 64 * u;
+        if (bound[u] != 0xFFFFFFFFu && (!any || unordered_bits(bound[u]) <= limit)) {
+            const int r = e / kAssignWords;
+            const uint32_t pos = atomicAdd(&nflag[r], 1u);
+            flist[(size_t)r * flist_stride + pos] = (uint32_t)row;
+            handed_on = true;
+        }
+    }
+    const bool some = __ballot(handed_on) != 0;
     if (lane == 0) {
         out_idx[row] = best_c;
         if (out_dist) out_dist[row] = best_d;
-        if (!complete) {
-            const uint32_t pos = atomicAdd(nflag, 1u);
-            flist[pos] = (uint32_t)row;
-            fkey[pos] = ~0ull;
-        }
+        if (some) fkey[row] = ((unsigned long long)__float_as_uint(best_d) << 32) | (unsigned)best_c;
     }
 }
 
-// Stage 3: direct-form distances of the listed rows to the centres of one split, 64 rows per workgroup at a time
-// (the tiling of assign_kernel); the nearest of a split meets the others' by an atomic minimum on
-// (distance bits << 32 | centre).  grid = (row groups, splits); workgroups beyond the list return at once.
+// Stage 3: direct-form distances of a range's listed rows to the centres of one split of that range, 64 rows per
+// workgroup at a time (the tiling of assign_kernel); the nearest of a split meets the others', and the best of
+// stage 2, by an atomic minimum on (distance bits << 32 | centre) in fkey[row].  grid = (row groups, splits per
+// range, ranges); workgroups beyond a list return at once.
 __global__ __launch_bounds__(256) void assign_rows_direct_kernel(const float *__restrict__ x, int d, int64_t ldx,
-                                                                 const uint32_t *__restrict__ flist, const uint32_t *__restrict__ nflag,
-                                                                 const float *__restrict__ cent, int K, int per_split,
+                                                                 const uint32_t *__restrict__ flist, int64_t flist_stride,
+                                                                 const uint32_t *__restrict__ nflag,
+                                                                 const float *__restrict__ cent, int K, int per_range, int per_split,
                                                                  unsigned long long *__restrict__ fkey) {
     __shared__ __align__(16) float xs[TK * LDT];
     __shared__ __align__(16) float cs[TK * LDT];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int lr = tid >> 2, lk = (tid & 3) * 4;
-    const int count = (int)*nflag;
-    const int jbeg = blockIdx.y * per_split, jend = min(K, jbeg + per_split);
+    const int range = blockIdx.z;
+    const int count = (int)nflag[range];
+    const uint32_t *list = flist + (size_t)range * flist_stride;
+    const int jbeg = range * per_range + blockIdx.y * per_split, jend = min(min(K, (range + 1) * per_range), jbeg + per_split);
+    if (jbeg >= jend) return;                                                  // uniform
     for (int p0 = blockIdx.x * TM; p0 < count; p0 += gridDim.x * TM) {          // uniform
-        const int64_t my_row = p0 + lr < count ? (int64_t)flist[p0 + lr] : -1;
+        const int64_t my_row = p0 + lr < count ? (int64_t)list[p0 + lr] : -1;
         float best_d[4];
         int best_j[4];
 #pragma unroll
@@ -662,18 +675,22 @@ __global__ __launch_bounds__(256) void assign_rows_direct_kernel(const float *__
         for (int i = 0; i < 4; ++i) {
             const int pos = p0 + ty * 4 + i;
             if (pos < count && best_j[i] != 0x7FFFFFFF)
-                atomicMin(&fkey[pos], ((unsigned long long)__float_as_uint(best_d[i]) << 32) | (unsigned)best_j[i]);
+                atomicMin(&fkey[list[pos]], ((unsigned long long)__float_as_uint(best_d[i]) << 32) | (unsigned)best_j[i]);
         }
     }
 }
-__global__ void assign_rows_finish_kernel(const uint32_t *__restrict__ flist, const uint32_t *__restrict__ nflag,
+// ... and what the minimum came to, for every listed row (grid.y = ranges; a row listed by several ranges is
+// written several times, with the same value).
+__global__ void assign_rows_finish_kernel(const uint32_t *__restrict__ flist, int64_t flist_stride, const uint32_t *__restrict__ nflag,
                                           const unsigned long long *__restrict__ fkey, int32_t *__restrict__ out_idx,
                                           float *__restrict__ out_dist) {
-    const uint32_t count = *nflag;
+    const uint32_t count = nflag[blockIdx.y];
+    const uint32_t *list = flist + (size_t)blockIdx.y * flist_stride;
     for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p < count; p += gridDim.x * blockDim.x) {
-        const unsigned long long key = fkey[p];
-        out_idx[flist[p]] = (int32_t)(uint32_t)key;
-        if (out_dist) out_dist[flist[p]] = __uint_as_float((uint32_t)(key >> 32));
+        const uint32_t row = list[p];
+        const unsigned long long key = fkey[row];
+        out_idx[row] = (int32_t)(uint32_t)key;
+        if (out_dist) out_dist[row] = __uint_as_float((uint32_t)(key >> 32));
     }
 }
 
@@ -712,7 +729,7 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
         const int Ruse = (K + per_range - 1) / per_range;
         const size_t split_bytes = (2 * part * sizeof(uint16_t) + 255) / 256 * 256;
         const size_t cand_bytes = sizeof(uint64_t) * kAssignWords * (size_t)Ruse * cap_rows;
-        const size_t flist_bytes = (sizeof(uint32_t) * (size_t)cap_rows + 255) / 256 * 256;
+        const size_t flist_bytes = (sizeof(uint32_t) * (size_t)Ruse * cap_rows + 255) / 256 * 256;
         const size_t fkey_bytes = sizeof(unsigned long long) * (size_t)cap_rows;
         unsigned char *scratch = nullptr;
         PR_CHECK_HIP(hipMallocAsync(reinterpret_cast<void **>(&scratch), split_bytes + cand_bytes + flist_bytes + fkey_bytes + 512, st));
@@ -721,25 +738,27 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
         uint32_t *flist = reinterpret_cast<uint32_t *>(scratch + split_bytes + cand_bytes);
         unsigned long long *fkey = reinterpret_cast<unsigned long long *>(scratch + split_bytes + cand_bytes + flist_bytes);
         uint32_t *x_amax = reinterpret_cast<uint32_t *>(scratch + split_bytes + cand_bytes + flist_bytes + fkey_bytes);
-        uint32_t *nflag = x_amax + 64;
+        uint32_t *nflag = x_amax + 64;                       // one count per centre range (at most 16)
         const int nchunks = F16x3Tile::chunks_pad(d);
         const int64_t c_rp = F16x3Tile::rows_pad(K);
-        // stage 3 splits the centres so that even a handful of rows keeps many compute units busy
-        const int per_split = std::max(TN, (K + 255) / 256 / TN * TN), splits = (K + per_split - 1) / per_split;
+        // stage 3 splits a range's centres so that even a handful of rows keeps many compute units busy
+        const int splits_target = std::max(1, 256 / Ruse);
+        const int per_split = std::max(TN, (per_range + splits_target - 1) / splits_target / TN * TN);
+        const int splits = (per_range + per_split - 1) / per_split;
         for (int64_t a = 0; a < n; a += slice) {
             const int64_t cnt = std::min(slice, n - a), rp = F16x3Tile::rows_pad(cnt);
             launch_split(x + a * ldx, cnt, d, ldx, x_amax, xs, xs + part, st);
-            hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, st, nflag);
+            hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st, nflag, 16);
             const int64_t tiles_v = (cnt + F16x3Tile::kRowsB - 1) / F16x3Tile::kRowsB;
             const unsigned grid = (unsigned)((tiles_v + 7) / 8 * 8 * Ruse);
             hipLaunchKernelGGL(assign_f16x3_kernel, dim3(grid), dim3(F16x3Tile::kThreads), kBfLds, st, cnt, nchunks, xs, xs + part, rp, chi, clo, c_rp,
                                x_amax, c_amax, cnorm, K, Ruse, per_range, cand);
             hipLaunchKernelGGL(assign_finish_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
-                               cnorm, K, cand, Ruse, out_idx + a, out_dist ? out_dist + a : nullptr, flist, fkey, nflag);
-            const unsigned row_groups = (unsigned)std::min<int64_t>((cnt + TM - 1) / TM, 256);
-            hipLaunchKernelGGL(assign_rows_direct_kernel, dim3(row_groups, splits), dim3(256), 0, st, x + a * ldx, d, ldx, flist, nflag,
-                               cent, K, per_split, fkey);
-            hipLaunchKernelGGL(assign_rows_finish_kernel, dim3(64), dim3(256), 0, st, flist, nflag, fkey, out_idx + a,
+                               cnorm, K, cand, Ruse, out_idx + a, out_dist ? out_dist + a : nullptr, flist, cap_rows, fkey, nflag);
+            const unsigned row_groups = (unsigned)std::min<int64_t>((cnt + TM - 1) / TM, 64);
+            hipLaunchKernelGGL(assign_rows_direct_kernel, dim3(row_groups, splits, Ruse), dim3(256), 0, st, x + a * ldx, d, ldx, flist,
+                               cap_rows, nflag, cent, K, per_range, per_split, fkey);
+            hipLaunchKernelGGL(assign_rows_finish_kernel, dim3(16, Ruse), dim3(256), 0, st, flist, cap_rows, nflag, fkey, out_idx + a,
                                out_dist ? out_dist + a : nullptr);
         }
         PR_CHECK_HIP(hipFreeAsync(scratch, st));

@@ -36,6 +36,8 @@ def _load():
         _lib.workload_gen_rows.restype = C.c_int
         _lib.workload_plain_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib.workload_plain_copy.restype = C.c_int
+        _lib.workload_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        _lib.workload_stream_read.restype = C.c_int
     return _lib
 
 
@@ -73,3 +75,12 @@ def plain_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     rc = _load().workload_plain_copy(src.data_ptr(), dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError(f"workload_plain_copy failed with hipError {rc}")
+
+
+def stream_read(src: torch.Tensor, workgroups: int, nontemporal: bool, sink: torch.Tensor) -> None:
+    """Launches the read-only reference kernel over src (roofline reference: nothing is computed or written)."""
+    nbytes = src.numel() * src.element_size()
+    rc = _load().workload_stream_read(src.data_ptr(), nbytes, int(workgroups), int(nontemporal), sink.data_ptr(),
+                                      torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"workload_stream_read failed with hipError {rc}")

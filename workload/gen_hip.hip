@@ -83,3 +83,42 @@ extern "C" int workload_plain_copy(const void *src_dev, void *dst_dev, size_t by
                        bytes / 16);
     return (int)hipGetLastError();
 }
+
+// ---- reference for the roofline: a kernel that only reads (no part of any workload) ----------------
+// Every workgroup walks its share of the buffer with eight 16-byte loads in flight per lane, ordinary or
+// non-temporal, and folds what it reads into one word, written only if it has a value it cannot have (so that the
+// loads are kept and nothing is written).  What this reaches is what a kernel of the same launch shape that
+// also computes can hope for.
+namespace {
+template <bool NT>
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16, uint32_t *__restrict__ sink) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(src + i + u * stride);
+            v[u] = NT ? __builtin_nontemporal_load(p) : *p;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) { const uint4 v = src[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+    if (acc == 0x9E3779B9u && sink) *sink = acc;
+}
+}  // namespace
+
+extern "C" int workload_stream_read(const void *src_dev, size_t bytes, int32_t workgroups, int32_t nontemporal, void *sink_dev,
+                                    void *stream) {
+    if (workgroups < 1 || bytes < 16) return (int)hipErrorInvalidValue;
+    if (nontemporal)
+        hipLaunchKernelGGL(stream_read_kernel<true>, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src_dev,
+                           bytes / 16, (uint32_t *)sink_dev);
+    else
+        hipLaunchKernelGGL(stream_read_kernel<false>, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src_dev,
+                           bytes / 16, (uint32_t *)sink_dev);
+    return (int)hipGetLastError();
+}
