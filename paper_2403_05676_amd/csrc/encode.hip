@@ -471,12 +471,22 @@ __global__ __launch_bounds__(F16x3Tile::kThreads, 1) void assign_f16x3_kernel(in
     const float inf = __builtin_inff();
     float b1v[2] = {inf, inf}, b2v[2] = {inf, inf}, b3v[2] = {inf, inf};
     int b1c[2] = {K, K}, b2c[2] = {K, K};                      // K: no centre
-    int tile = 0;
-    for (int j0 = jbeg; j0 < jend; j0 += F16x3Tile::kRowsA, ++tile) {
-        float *cn = s_cn + (tile & 1) * F16x3Tile::kRowsA;     // read after the barriers inside run(); rewritten two tiles later
-        if (tid < F16x3Tile::kRowsA) cn[tid] = j0 + tid < jend ? cnorm[j0 + tid] : inf;
-        acc16_t acc[4][2];
-        F16x3Tile::run(chi, clo, c_rp, j0, xhi, xlo, x_rp, row0, nchunks, bsmem, acc);
+    const int ntiles = (jend - jbeg + F16x3Tile::kRowsA - 1) / F16x3Tile::kRowsA;
+    // the squared norms of a tile's centres travel beside the stream: asked for at the tile's first step (straight
+    // into LDS, buffer t % 2: read when the tile is complete, rewritten two tiles later), and places beyond the
+    // range's last centre set to +inf two steps later
+    const uint32_t cn_lds = __builtin_amdgcn_readfirstlane(F16x3Tile::lds_address(s_cn) + (uint32_t)(tid >> 6) * 256u);
+    auto hook = [&](int t, int s) {
+        if (s != 0 && s != 2) return;                           // uniform
+        if (tid < F16x3Tile::kRowsA) {                          // whole waves
+            const int c = jbeg + t * F16x3Tile::kRowsA + tid;
+            if (s == 0) F16x3Tile::load_to_lds_f32(cnorm, (uint32_t)min(c, K - 1) * 4u, cn_lds + (uint32_t)(t & 1) * 1024u);
+            else if (c >= jend) s_cn[(t & 1) * F16x3Tile::kRowsA + tid] = inf;
+        }
+    };
+    auto tile_done = [&](int t, const acc16_t (&acc)[4][2]) {
+        const float *cn = s_cn + (t & 1) * F16x3Tile::kRowsA;
+        const int j0 = jbeg + t * F16x3Tile::kRowsA;
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
@@ -485,12 +495,12 @@ __global__ __launch_bounds__(F16x3Tile::kThreads, 1) void assign_f16x3_kernel(in
                 const float4 nn = *reinterpret_cast<const float4 *>(cn + r0);
                 const float nv[4] = {nn.x, nn.y, nn.z, nn.w};
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
                     for (int bj = 0; bj < 2; ++bj) {
-                        const float v = nv[t] + m2 * acc[bi][bj][4 * gq + t];
+                        const float v = nv[t4] + m2 * acc[bi][bj][4 * gq + t4];
                         if (v < b3v[bj]) {                     // seldom true once the running values have settled
-                            const int c = j0 + r0 + t;
+                            const int c = j0 + r0 + t4;
                             if (v < b2v[bj]) {
                                 b3v[bj] = b2v[bj];
                                 if (v < b1v[bj]) { b2v[bj] = b1v[bj]; b2c[bj] = b1c[bj]; b1v[bj] = v; b1c[bj] = c; }
@@ -501,7 +511,8 @@ __global__ __launch_bounds__(F16x3Tile::kThreads, 1) void assign_f16x3_kernel(in
                         }
                     }
             }
-    }
+    };
+    F16x3Tile::run_tiles(chi, clo, c_rp, jbeg, ntiles, xhi, xlo, x_rp, row0, nchunks, bsmem, hook, tile_done);
     __syncthreads();                                           // the tile buffers are free
     uint64_t *s_key = reinterpret_cast<uint64_t *>(bsmem);     // [256 columns][8 keys + 4 bounds]
 #pragma unroll

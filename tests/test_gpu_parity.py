@@ -381,6 +381,24 @@ def test_list_assignment_on_tight_clusters():
     assert nl <= 8                       # all excused as ties by check_encoding, and few
 
 
+@pytest.mark.parametrize("N,d,nlist,M", [
+    (6000, 72, 300, 9),              # two centre tiles, the second ragged; depth padded from 9 to 12 chunks of 8
+    (5000, 100, 129, 25),            # one centre beyond a full tile; d not a multiple of 8
+    (3000, 776, 513, 97),            # three tiles, one centre in the last; 97 chunks padded to 100
+    (2000, 64, 1024, 8),             # the smallest depth the matrix-core path takes, whole tiles
+])
+def test_list_assignment_with_ragged_centre_tiles(N, d, nlist, M):
+    # the matrix-core assignment walks the centres 256 at a time and the depth 16 at a time: places beyond the
+    # last centre and beyond the last coordinate must not win or change a distance
+    pkg = P()
+    cfg, x, q, coarse, pq = make_problem(N, d, nlist, M, seed=N + d + nlist, iters=2, nq=1)
+    ix = pkg.Index.ivf_create(coarse, pq, N)
+    gl, gc = ix.ivf_encode(dev(x))
+    torch.cuda.synchronize()
+    assert int(gl.min()) >= 0 and int(gl.max()) < nlist
+    parity.check_encoding(gl.cpu().numpy(), gc.cpu().numpy(), x, coarse, pq)
+
+
 def test_cross_workgroup_merge_is_repeatable():
     # One query spread over several hundred workgroups, merged in two levels (groups of workgroups, then the
     # groups): the keys cross workgroups through device-scope stores ordered by a counter.  200 identical searches
