@@ -473,7 +473,6 @@ def main():
 
     # ---- single-query latency (host call -> stream synchronised), p50 --------------------------
     q1 = q[:1].contiguous()                 # the caller's query buffer, refilled with another query before every call
-    ix.set_graph_replay(True)               # a caller that waits for every search: repeated calls replay a captured graph
     lat = []
     # (its own number of calls, not the steps': single queries differ by a factor of ten in the vectors they scan)
     for r in range(0 if args.no_latency else args.warmup + LATENCY_CALLS):
@@ -485,7 +484,6 @@ def main():
         if r >= args.warmup:
             lat.append((time.perf_counter() - t1) * 1e3)
     p50_1q = float(np.median(lat)) if lat else None
-    ix.set_graph_replay(False)
 
     traffic, traffic_src = stored_traffic(cfg.name)
     result = {

@@ -145,8 +145,7 @@ int piperag_ivfpq_search(const piperag_index *index, const float *queries_dev, i
  * tight serving loops, harnesses that forbid it): the same search as piperag_ivfpq_search, same kernels, same
  * results, but every intermediate (coarse distances, probe tables, lookup tables, partial results, counters)
  * lives in a static device array of PIPERAG_STATIC_SCRATCH_BYTES that the library's code object brings with it
- * (each GPU the library runs on holds its own copy until the process ends), and all work goes to `stream`
- * itself (the tables are not built on a side stream).  The call allocates nothing and ignores the index's
+ * (each GPU the library runs on holds its own copy until the process ends).  The call allocates nothing and ignores the index's
  * max_nq / max_nprobe / max_k: it is limited by the array instead - the scratch needed grows with nq * nlist,
  * nq * 256 * M and (512 + 10 * nq) * (k + 64); a call that needs more returns PIPERAG_ERR_LIMIT (e.g. nq = 16,
  * nprobe = 128, k = 100 on 65,536 lists with 64-byte codes needs 7 MiB).  The index must have been created in
@@ -197,8 +196,7 @@ int piperag_project_latency(const float *inference_ms_host, const float *retriev
  * at the default priority.  The paper hides the retrieval behind the generation of the next tokens by running it
  * on a server of its own (Section 3.2, S1); on one GPU the same is had by giving the search such a stream and the
  * generation a stream on the remaining compute units: every call of this library that takes a stream then runs
- * in that slice (the lookup tables of piperag_ivfpq_search are built on a side stream of the index, outside it;
- * piperag_ivfpq_search_static keeps everything on the given stream).  piperag_latency_profile on the same stream
+ * in that slice (a search is launched on the given stream only).  piperag_latency_profile on the same stream
  * gives the latency line of the slice.  *out_stream is a hipStream_t; destroy it with piperag_stream_destroy. */
 int piperag_stream_create_cu_slice(int32_t first_cu, int32_t ncu, void **out_stream);
 int piperag_stream_destroy(void *stream);
@@ -242,8 +240,8 @@ int piperag_search_stats(const piperag_index *index, int64_t *scanned_vectors, i
 /* Per-stage timing of the retrieval latency model's terms (Section 3.2, S3: index scan + vector scan).
  * When enabled, every search call records HIP events around its stages on its stream;
  * piperag_stage_times synchronises on them and writes the most recent call's milliseconds:
- * [0] coarse quantiser, [1] top-nprobe selection, scan plan and work sharing, [2] wait for the lookup
- * tables (built on a side stream beside the selection), [3] list scan with k-selection, merge of
+ * [0] coarse quantiser, [1] top-nprobe selection, scan plan and work sharing, [2] lookup
+ * tables, [3] list scan with k-selection, merge of
  * the query's partial results and id gather (one kernel).  Stages [0]+[1] are the index-scan term,
  * [2]+[3] the vector-scan term. */
 #define PIPERAG_NSTAGES 4

@@ -157,10 +157,6 @@ struct piperag_index {
     // stage timing
     bool timing;
     hipEvent_t ev[PIPERAG_NSTAGES + 1];
-    // the table build depends only on the queries: it runs on a stream of the index's own, beside the coarse
-    // quantiser, forked from and joined to the caller's stream with these two events
-    hipStream_t side;
-    hipEvent_t ev_fork, ev_join;
     hipStream_t cap_stream;       // capture stream for the search graphs
     bool replay;                  // graph replay of repeated calls is enabled
     int streaming;                // scan loads: < 0 by index size, 0 ordinary, > 0 non-temporal

@@ -316,11 +316,8 @@ int create_impl(const piperag_params *params, const float *cent_host, const floa
     }
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (hipEventCreate(&ix->ev[e]) != hipSuccess) { set_error("hipEventCreate failed"); return fail(PIPERAG_ERR_HIP); }
-    if (hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking) != hipSuccess ||
-        hipStreamCreateWithFlags(&ix->cap_stream, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming) != hipSuccess) {
-        set_error("creating the side stream failed");
+    if (hipStreamCreateWithFlags(&ix->cap_stream, hipStreamNonBlocking) != hipSuccess) {
+        set_error("creating the capture stream failed");
         return fail(PIPERAG_ERR_HIP);
     }
     *out = ix;
@@ -416,9 +413,6 @@ void piperag_ivf_free(piperag_index *ix) {
     for (void *p : ptrs) (void)hipFree(p);
     for (int e = 0; e <= PIPERAG_NSTAGES; ++e)
         if (ix->ev[e]) (void)hipEventDestroy(ix->ev[e]);
-    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
-    if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
-    if (ix->side) (void)hipStreamDestroy(ix->side);
     if (ix->cap_stream) (void)hipStreamDestroy(ix->cap_stream);
     for (SearchGraph &g : ix->graphs)
         if (g.exec) (void)hipGraphExecDestroy(g.exec);

@@ -41,7 +41,6 @@ namespace piperag {
 
 typedef float acc16_t __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 struct F16x3Tile {
     static constexpr int kRowsA = 256, kRowsB = 256, kTileK = 16, kRowPad = 256, kThreads = 512;

@@ -1545,27 +1545,22 @@ int check_search_limits(const piperag_index *ix, int32_t nq, int32_t nprobe, int
 // piperag_set_compute_units says otherwise), or for large batches about 8 per query.
 int scan_target_wgs(int nq, int ncu) { return std::min(kMaxScanWGs, std::max(std::min(kTargetScanWGs, 2 * ncu), 8 * nq)); }
 
-// Enqueues one search on st, with `ws` as its scratch (kernel launches and event operations only: it can be
-// captured into a graph).  fork: the tables are built on the index's side stream beside the selection;
-// otherwise on st itself (no events of the index are touched, and stage timing is not recorded).
-int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool fork, const float *q, int32_t nq, const int32_t *probes,
+// Enqueues one search on st, with `ws` as its scratch (kernel launches and event records only: it can be captured
+// into a graph).  stages: record the index's stage events (not for searches that use a workspace other than the
+// index's own).  Everything runs on st, in the order coarse quantiser, selection, tables, scan.  (The tables need
+// only the queries and were once built on a side stream beside the first two stages; the two cross-stream waits
+// cost more than the overlap gave: a waited-for single query took 111 instead of 90 us, 16 queries 158 instead
+// of 139, and back-to-back batches of 64 or 256 ran no faster.  Building them by workgroups appended to the coarse
+// quantiser's grid instead of a launch of their own was measured too: 1 us less for one query, 4 us for four -
+// launches queued on one stream follow each other within a microsecond or two - and was not kept.)
+int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool stages, const float *q, int32_t nq, const int32_t *probes,
                    int32_t nprobe, int32_t k, float *out_d, int64_t *out_i, hipStream_t st) {
     int rc = PIPERAG_OK;
     const int pstride = ws.max_nprobe;
-    const bool tm = ix->timing && fork;
+    const bool tm = ix->timing && stages;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[0], st));
-    // The tables need only the queries: with the fork they are built on the side stream beside the coarse
-    // quantiser and the selection, and joined before the scan.
-    if (fork) PR_CHECK_HIP(hipEventRecord(ix->ev_fork, st));                 // the fork point: before the coarse quantiser ...
     if (!probes && (rc = launch_coarse(ix, ws, q, nq, st)) != PIPERAG_OK) return rc;
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[1], st));
-    if (fork) {                                                              // ... which is submitted first all the same
-        PR_CHECK_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
-        launch_lut_build(ix, q, nq, ws.lut, ix->side);
-        PR_CHECK_HIP(hipEventRecord(ix->ev_join, ix->side));
-    } else {
-        launch_lut_build(ix, q, nq, ws.lut, st);
-    }
     const int target_wgs = scan_target_wgs(nq, ix->ncu);
     const int G = std::max(target_wgs, nq);                 // upper bound of the workgroups the plan hands out
     const int KW = k + kKeepSlack;                          // key slots per scan workgroup in the partial buffer
@@ -1597,7 +1592,7 @@ int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool fork, const
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[2], st));
     ScanArgs a{ix->codes, ws.lut, ws.pfx, ws.pblk, ws.plen, ix->p.residual ? ws.pcst : nullptr,
                ix->p.residual ? ix->tx : nullptr, ws.part, ws.thr, ws.desc, ws.ctr, nprobe, pstride, k, KW};
-    if (fork) PR_CHECK_HIP(hipStreamWaitEvent(st, ix->ev_join, 0));    // join: the tables are ready
+    launch_lut_build(ix, q, nq, ws.lut, st);
     if (tm) PR_CHECK_HIP(hipEventRecord(ix->ev[3], st));
     a.cap = cap;
     a.qdone = ws.done;
@@ -1622,12 +1617,12 @@ int enqueue_search(const piperag_index *ix, const SearchWs &ws, bool fork, const
     return PIPERAG_OK;
 }
 
-// A search is four launches and four event operations; enqueueing them one by one costs the host tens of
-// microseconds, a large part of a single query's latency.  With replay enabled (piperag_set_graph_replay), a call
-// that repeats an earlier one (same buffers, same sizes: a serving loop that refills its query buffer) is
-// captured into a graph the second time it is seen and replayed with one launch from then on (measured: 8 us
-// less per waited-for call, but 10 us more per call in a back-to-back loop, hence opt-in).  The graph holds
-// only kernel nodes and the fork / join of the table build.  Stage timing keeps the plain path.
+// A search is four launches on one stream.  With replay enabled (piperag_set_graph_replay), a call that repeats an
+// earlier one (same buffers, same sizes: a serving loop that refills its query buffer) is captured into a graph
+// the second time it is seen and replayed with one launch from then on: one host call per search instead of four.
+// It does not shorten a search (measured on this GPU: a waited-for single query takes 93 us replayed against 89 us
+// launched plainly, and back-to-back calls lose 10 us each), so it is opt-in, for callers whose host thread is the
+// scarce resource.  The graph holds only kernel nodes.  Stage timing keeps the plain path.
 // The index is const for the caller: what a search changes is its workspace in device memory and the members
 // declared mutable (statistics, event state, graph cache).
 int search_impl(const piperag_index *ix, const float *q, int32_t nq, const int32_t *probes, int32_t nprobe, int32_t k,
