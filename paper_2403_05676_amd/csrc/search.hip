@@ -33,6 +33,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // Workgroup-wide selection: returns a threshold T such that exactly kth of the given keys are <= T.
 // Keys equal to kSentinel are ignored; the others must be distinct and at least kth of them must exist
 // (if fewer exist, kSentinel - 1 is returned: "keep all").  blockDim is a multiple of 64, >= 64.
+// slack > 0: any T with between kth and kth + slack keys <= T will do (it is found in fewer rounds, mostly one).
 // Method: bucket counting over the value range that still contains the kth key - 256 equal-width buckets
 // over [lo, hi], starting from the actual minimum and maximum, narrowed to one bucket per round - so the
 // histogram is spread over the buckets from the first round on, whatever bits the keys have in common.
@@ -40,7 +41,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // together cover every key exactly once); it is run once per round, so keys may live in registers, LDS or
 // global memory.  s_hist: 256 words, s_state: 8 words of LDS.
 template <class ForEach>
-__device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigned *s_hist, unsigned long long *s_state) {
+__device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigned *s_hist, unsigned long long *s_state, int slack = 0) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     // first pass: minimum, maximum and number of valid keys
     uint64_t lo = kSentinel, hi = 0;
@@ -103,18 +104,18 @@ __device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigne
         lo = lo + ((uint64_t)bucket << sh);
         const uint64_t bhi = lo + ((sh > 0 ? (1ull << sh) : 1ull) - 1ull);
         hi = bhi < hi ? bhi : hi;
-        if (inb == need) return hi;         // every key of this bucket is wanted: T = its upper end
+        if (inb - need <= (unsigned)slack) return hi;   // every key of this bucket is wanted, or few enough are not: T = its upper end
         // sh == 0 means one key value per bucket, so inb == 1 == need there: the loop ends at the latest then
     }
 }
 
 // The same for keys addressed by index: key_at(i), i = 0..n-1.
 template <class KeyFn>
-__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state) {
+__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state, int slack = 0) {
     auto each = [&](auto f) {
         for (int i = threadIdx.x; i < n; i += blockDim.x) f(key_at(i));
     };
-    return block_select_kth_each(each, kth, s_hist, s_state);
+    return block_select_kth_each(each, kth, s_hist, s_state, slack);
 }
 
 // In-place ascending sort of n <= 64 keys in LDS by one wavefront (all 64 lanes call it): one key per lane, bitonic
@@ -1027,8 +1028,12 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
 // sweep over global memory per round.
 // FINAL = true: ids are looked up and the results written to out_d / out_i, sorted by (distance, id) and padded
 // with (+inf, -1); s_d / s_id: power-of-two >= k slots.
-// FINAL = false: the selected keys are written to dst[0..KW), unsorted and padded with kSentinel.
+// FINAL = false: the k smallest keys and up to KW - k more are written to dst[0..KW), unsorted and padded with
+// kSentinel (whoever reads them selects again).
 // Slots of `list` that hold kSentinel are skipped.
+constexpr int kRankMaxK = 256;        // results up to this many are placed by counting (see below)
+constexpr int kRankSlack = 128;       // ... among at most this many candidates more than k
+
 template <bool FINAL>
 __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int room, int k, uint32_t bound, uint64_t *s_keys,
                                  unsigned *s_hist, unsigned long long *s_state, unsigned *s_count,
@@ -1043,12 +1048,12 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
     const bool in_lds = n <= room;                               // uniform
     int found = n;
     if (in_lds) {
-        for (int i0 = tid; i0 < n; i0 += 8 * nt) {               // 8 loads in flight per thread, then the appends
-            uint64_t key[8];
+        for (int i0 = tid; i0 < n; i0 += 16 * nt) {              // 16 loads in flight per thread, then the appends
+            uint64_t key[16];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) key[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
+            for (int j = 0; j < 16; ++j) key[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {                        // one counter update per wave and round
+            for (int j = 0; j < 16; ++j) {                       // one counter update per wave and round
                 const bool pass = key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound;
                 const uint64_t mask = __ballot(pass);
                 unsigned at = 0;
@@ -1062,13 +1067,80 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         __syncthreads();
     }
     auto key_at = [&](int i) { return in_lds ? s_keys[i] : load_key(list + i); };
+    // Results by counting.  An exact k-th key takes the bucket counting up to eight rounds of four barriers (1 to 7
+    // were seen, 3 us each on a few thousand keys), and the results then still have to be ordered.  Instead: a bound
+    // T with between k and k + kRankSlack keys below it (one round, seldom two), those candidates side by side in
+    // LDS, and for each the number of candidates with a smaller key: that is its rank by (distance, slot) - ranks
+    // below k are the results, and the rank is the place in the output unless results share a distance (then the ids
+    // of that run decide, as the order is by (distance, id)).
+    const int ncand_max = k + kRankSlack;
+    if (FINAL && k <= kRankMaxK && nt >= kRankMaxK && (in_lds ? found + ncand_max <= room || found <= ncand_max : ncand_max <= room)) {   // uniform
+        const uint64_t *c_keys = s_keys;                         // the candidates
+        int m = found;
+        if (found > ncand_max || !in_lds) {
+            uint64_t T = kSentinel - 1;
+            if (found > ncand_max) T = block_select_kth(key_at, found, k, s_hist, s_state, kRankSlack);
+            uint64_t *c_out = in_lds ? s_keys + found : s_keys;
+            if (tid == 0) *s_count = 0;
+            __syncthreads();
+            for (int i = tid; i < found; i += nt) {
+                const uint64_t key = key_at(i);
+                if (key <= T) c_out[atomicAdd(s_count, 1u)] = key;   // kSentinel > T
+            }
+            __syncthreads();
+            m = (int)*s_count;
+            c_keys = c_out;
+        }
+        const int cnt = min(m, k);
+        for (int j = tid; j < m; j += nt) {
+            const uint64_t mine = c_keys[j];
+            int rank = 0;
+            int i = 0;
+            for (; i + 8 <= m; i += 8) {                         // reads that all lanes make at the same address
+                uint64_t o[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) o[u] = c_keys[i + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += o[u] < mine ? 1 : 0;
+            }
+            for (; i < m; ++i) rank += c_keys[i] < mine ? 1 : 0;
+            if (rank < k) { s_d[rank] = (uint32_t)(mine >> 32); s_id[rank] = ids[(uint32_t)mine]; }
+        }
+        __syncthreads();
+        for (int r = tid; r < cnt; r += nt) {
+            const uint32_t d = s_d[r];
+            const int64_t id = s_id[r];
+            int place = r;
+            if ((r > 0 && s_d[r - 1] == d) || (r + 1 < cnt && s_d[r + 1] == d)) {   // a run of equal distances: by id
+                // the run's ends by bisection (s_d is ascending), then the ids of the run, eight reads at a time
+                int b = 0, bh = r;                               // first place of the run: first i in [0, r] with s_d[i] >= d
+                while (b < bh) { const int mid = (b + bh) >> 1; if (s_d[mid] < d) b = mid + 1; else bh = mid; }
+                int e = r + 1, eh = cnt;                         // its end: first i in (r, cnt] with s_d[i] > d (cnt if none)
+                while (e < eh) { const int mid = (e + eh) >> 1; if (s_d[mid] > d) eh = mid; else e = mid + 1; }
+                place = b;
+                int i = b;
+                for (; i + 8 <= e; i += 8) {
+                    int64_t o[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) o[u] = s_id[i + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) place += (o[u] < id || (o[u] == id && i + u < r)) ? 1 : 0;
+                }
+                for (; i < e; ++i) place += (s_id[i] < id || (s_id[i] == id && i < r)) ? 1 : 0;
+            }
+            out_d[place] = __uint_as_float(d);
+            out_i[place] = id;
+        }
+        for (int i = cnt + tid; i < k; i += nt) { out_d[i] = __builtin_inff(); out_i[i] = -1; }
+        return;
+    }
     uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
-    if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state);
+    if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state, FINAL ? 0 : KW - k);
     if (tid == 0) *s_count = 0;
     __syncthreads();
     for (int i = tid; i < found; i += nt) {
         const uint64_t key = key_at(i);
-        if (key <= T) {                                          // at most k keys qualify (keys are distinct; kSentinel > T)
+        if (key <= T) {                                          // at most k (FINAL) or KW keys qualify (keys are distinct; kSentinel > T)
             const unsigned slot = atomicAdd(s_count, 1u);
             if (FINAL) { s_d[slot] = (uint32_t)(key >> 32); s_id[slot] = ids[(uint32_t)key]; }
             else store_key(dst + slot, key);
