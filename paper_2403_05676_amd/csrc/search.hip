@@ -1032,7 +1032,8 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
 // kSentinel (whoever reads them selects again).
 // Slots of `list` that hold kSentinel are skipped.
 constexpr int kRankMaxK = 256;        // results up to this many are placed by counting (see below)
-constexpr int kRankSlack = 128;       // ... among at most this many candidates more than k
+constexpr int kRankSlack = 128;       // ... among at most this many candidates more than k (more slack ends the counting
+                                      // earlier but leaves more candidates to rank: 384 cost batches a quarter more)
 
 template <bool FINAL>
 __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int room, int k, uint32_t bound, uint64_t *s_keys,
@@ -1048,18 +1049,37 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
     const bool in_lds = n <= room;                               // uniform
     int found = n;
     if (in_lds) {
-        for (int i0 = tid; i0 < n; i0 += 16 * nt) {              // 16 loads in flight per thread, then the appends
-            uint64_t key[16];
+        // 16 keys per thread at a time; the loads of the next 16 are issued before these are looked at, and a wave
+        // adds its passing keys of all 16 to the counter at once (one LDS round trip per wave and turn, not 16)
+        constexpr int kPer = 16;
+        uint64_t key[kPer], nxt[kPer];
+        auto fetch = [&](uint64_t (&dst)[kPer], int i0) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) key[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
+            for (int j = 0; j < kPer; ++j) dst[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
+        };
+        fetch(key, tid);
+        for (int i0 = tid; i0 < n + tid; i0 += kPer * nt) {      // i0 - tid < n: the same number of turns for every thread
+            const bool more = i0 - tid + kPer * nt < n;          // uniform
+            if (more) fetch(nxt, i0 + kPer * nt);
+            uint64_t mask[kPer];
+            unsigned total = 0;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {                       // one counter update per wave and round
-                const bool pass = key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound;
-                const uint64_t mask = __ballot(pass);
-                unsigned at = 0;
-                if ((tid & 63) == 0 && mask != 0) at = atomicAdd(s_count, (unsigned)__popcll(mask));
-                at = __builtin_amdgcn_readfirstlane(at);
-                if (pass) s_keys[at + (unsigned)__popcll(mask & ((1ull << (tid & 63)) - 1ull))] = key[j];
+            for (int j = 0; j < kPer; ++j) {
+                mask[j] = __ballot(key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound);
+                total += (unsigned)__popcll(mask[j]);
+            }
+            unsigned at = 0;
+            if ((tid & 63) == 0 && total != 0) at = atomicAdd(s_count, total);
+            at = __builtin_amdgcn_readfirstlane(at);
+            const uint64_t below = (1ull << (tid & 63)) - 1ull;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                if ((mask[j] >> (tid & 63)) & 1ull) s_keys[at + (unsigned)__popcll(mask[j] & below)] = key[j];
+                at += (unsigned)__popcll(mask[j]);
+            }
+            if (more) {
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) key[j] = nxt[j];
             }
         }
         __syncthreads();
