@@ -1033,7 +1033,9 @@ __global__ __launch_bounds__(256) void lut_build_kernel(const float *__restrict_
 // Slots of `list` that hold kSentinel are skipped.
 constexpr int kRankMaxK = 256;        // results up to this many are placed by counting (see below)
 constexpr int kRankSlack = 128;       // ... among at most this many candidates more than k (more slack ends the counting
-                                      // earlier but leaves more candidates to rank: 384 cost batches a quarter more)
+                                      // earlier but leaves more candidates to rank: 384 cost batches a quarter more, 64 made
+                                      // no difference; the same scheme in the probe selection gained nothing at 32 probes
+                                      // and lost 4 us at 256, where ranking 384 candidates costs more than the rounds saved)
 
 template <bool FINAL>
 __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int room, int k, uint32_t bound, uint64_t *s_keys,
