@@ -752,8 +752,11 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
         uint32_t *nflag = x_amax + 64;                       // one count per centre range (at most 16)
         const int nchunks = F16x3Tile::chunks_pad(d);
         const int64_t c_rp = F16x3Tile::rows_pad(K);
-        // stage 3 splits a range's centres so that even a handful of rows keeps many compute units busy
-        const int splits_target = std::max(1, 256 / Ruse);
+        // stage 3 splits a range's centres finely, one 64-centre tile per workgroup where the range allows it: its
+        // workgroups are bound by the latency of their loads (a tile takes about 100 us whatever else runs), so a
+        // handful of rows is done soonest by as many of them as there are tiles (3.3 ms per launch with 256 centres
+        // each); the rows of a long list are walked by a few row groups in turn
+        const int splits_target = std::max(1, 1024 / Ruse);
         const int per_split = std::max(TN, (per_range + splits_target - 1) / splits_target / TN * TN);
         const int splits = (per_range + per_split - 1) / per_split;
         for (int64_t a = 0; a < n; a += slice) {
@@ -766,7 +769,7 @@ int launch_assign(const float *x, int64_t n, int d, int64_t ldx, const float *ce
                                x_amax, c_amax, cnorm, K, Ruse, per_range, cand);
             hipLaunchKernelGGL(assign_finish_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, st, x + a * ldx, cnt, d, ldx, cent,
                                cnorm, K, cand, Ruse, out_idx + a, out_dist ? out_dist + a : nullptr, flist, cap_rows, fkey, nflag);
-            const unsigned row_groups = (unsigned)std::min<int64_t>((cnt + TM - 1) / TM, 64);
+            const unsigned row_groups = (unsigned)std::min<int64_t>((cnt + TM - 1) / TM, 16);
             hipLaunchKernelGGL(assign_rows_direct_kernel, dim3(row_groups, splits, Ruse), dim3(256), 0, st, x + a * ldx, d, ldx, flist,
                                cap_rows, nflag, cent, K, per_range, per_split, fkey);
             hipLaunchKernelGGL(assign_rows_finish_kernel, dim3(16, Ruse), dim3(256), 0, st, flist, cap_rows, nflag, fkey, out_idx + a,
