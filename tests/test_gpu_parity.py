@@ -443,6 +443,11 @@ def test_many_vectors_with_identical_codes_tie_at_the_kth_distance():
     od, oi = ix.ivfpq_search(dev(q), 4, 100)
     od2, oi2 = ix.ivfpq_search(dev(q), 4, 100)
     assert torch.equal(od, od2) and torch.equal(oi, oi2)   # and the choice is deterministic
+    # results are ordered by (distance, id): inside a run of equal distances (here up to all 100 places) ids ascend
+    dn, idn = od.cpu().numpy(), oi.cpu().numpy()
+    assert (np.diff(dn, axis=1) >= 0).all()
+    same = dn[:, 1:] == dn[:, :-1]
+    assert same.sum() > 500 and (idn[:, 1:][same] > idn[:, :-1][same]).all()
 
 
 def test_repeated_calls_replay_a_captured_graph_with_fresh_inputs(cfg0):
