@@ -23,8 +23,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # The workload a plain `python bench.py` measures: the largest single-GPU configuration, one of the two the roofline
-# target is stated on.  Its whole run takes about six minutes, 5.4 of them the build of 1.07 G vectors
-# (`--workload cfg3` is the other target configuration, 1.7 minutes).
+# target is stated on.  Its whole run takes about five and a half minutes, 4.8 of them the build of 1.07 G vectors
+# (`--workload cfg3` is the other target configuration, 1.6 minutes).
 DEFAULT_WORKLOAD = "cfg4"
 PARITY_QUERIES = 32            # queries of the timed batch whose results are compared with the oracle
 LATENCY_CALLS = 200            # single-query searches the p50 latency is taken over, each with another query

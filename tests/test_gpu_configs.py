@@ -39,7 +39,7 @@ def record(name, what):
             f.write(json.dumps(what, default=float) + "\n")
 
 
-def run_config(name, slice_rows, batches, max_check=64, plain_rows=4096):
+def run_config(name, slice_rows, batches, max_check=64, plain_rows=4096, capsys=None):
     import paper_2403_05676_amd as pkg
     import bench
     pkg.load_library()
@@ -47,7 +47,11 @@ def run_config(name, slice_rows, batches, max_check=64, plain_rows=4096):
     t0 = time.time()
     max_nq = max(nq for nq, _ in batches)
     max_np = max(npr for _, npr in batches)
-    ix, g, info = bench.build_index(pkg, cfg, torch, max_nq=max_nq, max_nprobe=max_np, max_k=cfg.k)
+    # the build of the large configurations takes minutes: its progress lines (one every 20 s) go to the terminal even
+    # when pytest captures output, so that whoever runs the suite sees that it is alive
+    import contextlib
+    with (capsys.disabled() if capsys is not None else contextlib.nullcontext()):
+        ix, g, info = bench.build_index(pkg, cfg, torch, max_nq=max_nq, max_nprobe=max_np, max_k=cfg.k)
     print(f"\n[{name}] built in {time.time() - t0:.1f}s (train {info['train_s']:.1f} encode {info['encode_s']:.1f} "
           f"finalize {info['finalize_s']:.1f})", flush=True)
     coarse, pq = info["coarse"].cpu().numpy(), info["pq"].cpu().numpy()
@@ -153,16 +157,16 @@ def test_cfg2_full_size():
     run_config("cfg2", 65536, [(1, 1), (1, 32), (1, 256), (8, 1), (8, 64), (8, 256)])
 
 
-def test_cfg3_full_size():
+def test_cfg3_full_size(capsys):
     skip_if_asked("cfg3")
-    run_config("cfg3", 1 << 20, [(64, 64), (16, 64), (1, 64)], max_check=32)
+    run_config("cfg3", 1 << 20, [(64, 64), (16, 64), (1, 64)], max_check=32, capsys=capsys)
 
 
-def test_cfg4_full_size():
+def test_cfg4_full_size(capsys):
     skip_if_asked("cfg4")
-    run_config("cfg4", 1 << 20, [(1, 128), (16, 128), (256, 128)], max_check=32)
+    run_config("cfg4", 1 << 20, [(1, 128), (16, 128), (256, 128)], max_check=32, capsys=capsys)
 
 
 @pytest.mark.skipif("paper" not in LARGE, reason="set PIPERAG_LARGE=paper (builds 3 G vectors in two passes, 230 GB of HBM)")
-def test_paper_shaped_index():
-    run_config("paper", 1 << 20, [(1, 64), (64, 64)], max_check=16)
+def test_paper_shaped_index(capsys):
+    run_config("paper", 1 << 20, [(1, 64), (64, 64)], max_check=16, capsys=capsys)
