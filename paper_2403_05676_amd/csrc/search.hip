@@ -383,7 +383,15 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
         // workgroups do not all queue up at one address.  Every wave starts on the chunk of its own number;
         // counter p then hands out P * v + p for v = the number of starting chunks it covers, and up.
         const int W = S * kScanWaves, P = min(kCtrPerQuery, max(1, S / 4));
-        o.desc[w] = int4{lo, seg, S, P};
+        // Length of the query's chunks, 4 << lg blocks: a chunk must outlast the round trip of the counter addition
+        // that fetches the next one (8 blocks do, 4 do not: 16 queries at 4,096 lists scanned 30 % faster with 8), and
+        // longer chunks read longer runs of memory (32 blocks, 128 KiB with 64-byte codes: +6 % at 64 queries on
+        // 16 GiB of codes) - as long as every wave still gets several of them, or the last chunks decide when the
+        // query ends (one query over 512 workgroups: 8 blocks best, 32 blocks 13 % slower), and none when a wave has
+        // fewer than 8 blocks to scan in all.
+        const long long per_wave = blocks_of(lo) / W;
+        const int lg = per_wave < 8 ? 0 : (per_wave < 64 ? 1 : (per_wave < 128 ? 2 : 3));
+        o.desc[w] = int4{lo, seg, S, P | (lg << 8)};
         if (seg == 0)
             for (int c = 0; c < P; ++c) o.ctr[((size_t)lo * kCtrPerQuery + c) * kCtrStride] = (uint32_t)((W - c + P - 1) / P);
     }
@@ -677,7 +685,7 @@ constexpr int kKeepSlack = 64;                        // pruning keeps between k
 constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack, at most
 constexpr int kCandRoomMin = 512;                     // and at least (the scan needs more than kScanThreads)
 constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
-constexpr int kChunkBlocks = 4;                       // consecutive blocks a scan wave takes at a time
+constexpr int kChunkBlocks = 4;                       // blocks a scan wave works through per turn of its loop; a chunk is 1, 2, 4 or 8 turns
 
 // LDS carve-up of the scan kernel (all dynamic, so that the table starts at address 0)
 struct ScanLds {
@@ -1252,7 +1260,7 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // Stage 3: scan of the probed lists with candidate selection.
 // The probed lists of a query, concatenated in probe order, form a sequence of 64-vector blocks; the plan
 // gives every workgroup a query, and the waves of a query's workgroups take that sequence in chunks of
-// kChunkBlocks blocks from shared counters.  A lane owns one vector of the block: it reads its Mp code bytes
+// 4 to 32 blocks (the plan fixes the length per query) from shared counters.  A lane owns one vector of the block: it reads its Mp code bytes
 // with Mp/16 16-byte loads (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.
 // Because of the rotated code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp,
 // so with the table stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
@@ -1302,7 +1310,7 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     uint32_t off4[16];
     make_off4(off4, lane);
 
-    // The query's blocks (numbered along its probed lists) are handed out in chunks of kChunkBlocks to the
+    // The query's blocks (numbered along its probed lists) are handed out in chunks of chunk_len blocks to the
     // waves of all its workgroups: the first chunk of a wave is the one of its own number, later ones come from
     // the query's counter, asked for one chunk ahead so that the answer is there when it is needed.  A slow
     // workgroup (pruning, a busy memory channel) simply takes fewer chunks.
@@ -1310,7 +1318,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // (the zero below is lane-dependent as far as the compiler can tell: an address it knows to be the same in
     // all lanes makes it combine the lanes' additions and fetch the answer at once, which would wait for every
     // load in flight)
-    const int wave_of_query = desc.y * kScanWaves + wave, nctr = desc.w, my_ctr = wave_of_query % nctr;
+    const int wave_of_query = desc.y * kScanWaves + wave, nctr = desc.w & 0xFF, my_ctr = wave_of_query % nctr;
+    const int tpc = 1 << (desc.w >> 8), chunk_len = kChunkBlocks * tpc;   // a chunk is tpc turns of kChunkBlocks blocks
     uint32_t *ctr = a.ctr + ((size_t)qi * kCtrPerQuery + my_ctr) * kCtrStride + __builtin_amdgcn_mbcnt_lo(0u, 0u);
     int pi = 0;                     // probe whose list holds the block looked up last (chunks only move forward)
     auto ask_chunk = [&]() -> uint32_t {
@@ -1373,7 +1382,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 
     uint4 w[NSETS][C];
     Meta meta[NSETS];
-    int cb = wave_of_query * kChunkBlocks;                   // first block of the chunk being requested
+    int cb = wave_of_query * chunk_len;                      // first block of the turn being requested (of the wave's own first chunk)
+    int turn = 0;                                            // which turn of its chunk that is
     uint32_t pending = ask_chunk();
     // the query's bound is polled once per chunk, with the chunk request, and used one turn later
     uint32_t tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1399,7 +1409,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         return ndone;
     };
     // One turn of the loop works through kChunkBlocks blocks; request number NSETS + j (counted from the wave's
-    // first) is made at step j, so the step at which the next chunk begins is the same in every turn.
+    // first) is made at step j, so the step at which the next turn's blocks begin - and, every tpc turns, the next
+    // chunk - is the same in every turn.
     static_assert(kChunkBlocks % NSETS == 0, "a chunk is a whole number of rounds over the register sets");
     for (;;) {
         bool any = false;           // this wave still holds a requested block
@@ -1410,11 +1421,16 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         for (int j = 0; j < kChunkBlocks; ++j) {
             const int i = j % NSETS, pos = (NSETS + j) % kChunkBlocks;   // position of the request within its chunk
             if (pos == 0) {
-                const uint32_t v = min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / (kChunkBlocks * kCtrPerQuery) - 1u);
-                cb = (int)(v * nctr + my_ctr) * kChunkBlocks;
-                pending = ask_chunk();
-                thr = min(thr, ((uint64_t)tg << 32) | 0xFFFFFFFFull);
-                tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (++turn == tpc) {                         // uniform: the chunk is used up, on to the one asked for
+                    turn = 0;
+                    const uint32_t v = min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / (kChunkBlocks * 8 * kCtrPerQuery) - 1u);
+                    cb = (int)(v * nctr + my_ctr) * chunk_len;
+                    pending = ask_chunk();
+                    thr = min(thr, ((uint64_t)tg << 32) | 0xFFFFFFFFull);
+                    tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    cb += kChunkBlocks;                      // the chunk's next turn
+                }
             }
             if (meta[i].nvalid > 0) {
                 // the count is looked at before every block; a wave appends at most 64 keys per block
