@@ -252,10 +252,12 @@ int piperag_stage_times(const piperag_index *index, float *out_ms_host /* [PIPER
  * and wait for it (the paper's serving loop retrieves for one sequence between generation steps, Section
  * 3.1): when enabled, a search call whose arguments (query, probe and output pointers, nq, nprobe, k)
  * repeat an earlier call's is captured into a HIP graph the second time it is seen and replayed with a
- * single launch from then on, which shortens the host side of the call.  The buffers' contents may change
- * between calls; their addresses must stay valid while replay is enabled.  Up to 8 distinct calls are
- * remembered (least recently used is dropped).  Back-to-back calls that are not waited for run faster
- * without it.  Disabling destroys the cached graphs.  Stage timing bypasses replay. */
+ * single launch from then on: one host call per search instead of four, for callers whose host thread is
+ * the scarce resource.  It does not shorten the search itself (on an MI355X a waited-for single query took
+ * 93 us replayed against 89 us launched plainly, and back-to-back calls lose about 10 us each).  The buffers'
+ * contents may change between calls; their addresses must stay valid while replay is enabled.  Up to 8
+ * distinct calls are remembered (least recently used is dropped).  Disabling destroys the cached graphs.
+ * Stage timing bypasses replay. */
 int piperag_set_graph_replay(piperag_index *index, int enable);
 
 /* How the scan reads the code blocks (Section 3.2, S3: the vector-scan term of the latency).  mode < 0
