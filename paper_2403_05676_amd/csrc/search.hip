@@ -30,6 +30,26 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Work areas in LDS, for functions that are compiled on their own (not inlined into a kernel): there nothing says
+// that a plain pointer argument points to LDS, so every access through it is a flat one - slower than an LDS
+// instruction, and its completion is counted together with the global loads in flight.  Such a function converts its
+// arguments to these types once.  lds_add / lds_min / lds_max take plain or LDS pointers.
+typedef __attribute__((address_space(3))) uint64_t lds_u64;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) unsigned long long lds_ull;
+typedef __attribute__((address_space(3))) int64_t lds_i64;
+// The same for arguments in global memory: a flat load counts as an LDS access too, so waiting for an LDS result
+// would wait for every such load in flight (the gather of the keys prefetches while it writes to LDS).
+typedef __attribute__((address_space(1))) uint64_t glb_u64;
+typedef __attribute__((address_space(1))) int64_t glb_i64;
+typedef __attribute__((address_space(1))) float glb_f32;
+template <class P, class V>
+__device__ __forceinline__ V lds_add(P p, V v) { return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+template <class P, class V>
+__device__ __forceinline__ V lds_min(P p, V v) { return __hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+template <class P, class V>
+__device__ __forceinline__ V lds_max(P p, V v) { return __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
 // Workgroup-wide selection: returns a threshold T such that exactly kth of the given keys are <= T.
 // Keys equal to kSentinel are ignored; the others must be distinct and at least kth of them must exist
 // (if fewer exist, kSentinel - 1 is returned: "keep all").  blockDim is a multiple of 64, >= 64.
@@ -39,33 +59,41 @@ __device__ __forceinline__ float wave_sum(float v) {
 // histogram is spread over the buckets from the first round on, whatever bits the keys have in common.
 // for_each_key(f) calls f(key) for every key this thread is responsible for (the threads of the workgroup
 // together cover every key exactly once); it is run once per round, so keys may live in registers, LDS or
-// global memory.  s_hist: 256 words, s_state: 8 words of LDS.
-template <class ForEach>
-__device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigned *s_hist, unsigned long long *s_state, int slack = 0) {
+// global memory.  s_hist: 256 words, s_state: 8 words of LDS (plain or LDS pointers).
+// A caller that has looked at every key already passes what the first pass would find (KeyRange: a range that
+// contains all valid keys, and their number; the same values in all threads) and saves that pass.
+struct KeyRange { bool known; uint64_t lo, hi; unsigned total; };
+template <class ForEach, class HistPtr, class StatePtr>
+__device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, HistPtr s_hist, StatePtr s_state, int slack = 0,
+                                         KeyRange range = KeyRange{false, 0, 0, 0}) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
-    // first pass: minimum, maximum and number of valid keys
-    uint64_t lo = kSentinel, hi = 0;
-    unsigned cnt = 0;
-    for_each_key([&](uint64_t key) {
-        if (key != kSentinel) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; ++cnt; }
-    });
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t ol = __shfl_xor(lo, off, 64), oh = __shfl_xor(hi, off, 64);
-        lo = ol < lo ? ol : lo; hi = oh > hi ? oh : hi;
-        cnt += __shfl_xor(cnt, off, 64);
-    }
-    if (tid == 0) { s_state[0] = kSentinel; s_state[1] = 0; s_state[2] = 0; }
+    uint64_t lo = range.lo, hi = range.hi;
+    unsigned total = range.total;
     for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
-    __syncthreads();
-    if (lane == 0) {
-        atomicMin(&s_state[0], (unsigned long long)lo);
-        atomicMax(&s_state[1], (unsigned long long)hi);
-        atomicAdd(&s_state[2], (unsigned long long)cnt);
+    if (!range.known) {                                          // uniform
+        // first pass: minimum, maximum and number of valid keys
+        lo = kSentinel; hi = 0;
+        unsigned cnt = 0;
+        for_each_key([&](uint64_t key) {
+            if (key != kSentinel) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; ++cnt; }
+        });
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint64_t ol = __shfl_xor(lo, off, 64), oh = __shfl_xor(hi, off, 64);
+            lo = ol < lo ? ol : lo; hi = oh > hi ? oh : hi;
+            cnt += __shfl_xor(cnt, off, 64);
+        }
+        if (tid == 0) { s_state[0] = kSentinel; s_state[1] = 0; s_state[2] = 0; }
+        __syncthreads();
+        if (lane == 0) {
+            lds_min(&s_state[0], (unsigned long long)lo);
+            lds_max(&s_state[1], (unsigned long long)hi);
+            lds_add(&s_state[2], (unsigned long long)cnt);
+        }
+        __syncthreads();
+        lo = s_state[0]; hi = s_state[1];
+        total = (unsigned)s_state[2];
     }
-    __syncthreads();
-    lo = s_state[0]; hi = s_state[1];
-    const unsigned total = (unsigned)s_state[2];
     __syncthreads();
     if (total < (unsigned)kth) return kSentinel - 1;
     unsigned need = (unsigned)kth;          // rank of the wanted key among the keys in [lo, hi]
@@ -73,7 +101,7 @@ __device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigne
         const uint64_t width = hi - lo;
         const int sh = width < 256 ? 0 : (56 - __clzll((long long)width));     // (width >> sh) <= 255
         for_each_key([&](uint64_t key) {
-            if (key != kSentinel && key >= lo && key <= hi) atomicAdd(&s_hist[(unsigned)((key - lo) >> sh)], 1u);
+            if (key != kSentinel && key >= lo && key <= hi) lds_add(&s_hist[(unsigned)((key - lo) >> sh)], 1u);
         });
         __syncthreads();
         if (tid < 64) {                     // wave 0: prefix sums over the 256 buckets, 4 per lane, and reset
@@ -109,13 +137,27 @@ __device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, unsigne
     }
 }
 
+// f(key) for the keys key_at(i), i = 0..n-1, shared out over the workgroup's threads; a thread reads eight of its keys
+// at a time, so that the reads (LDS or global memory) overlap: one key per turn costs a full read latency per key,
+// 3.3 us for a pass over 8,000 keys in LDS.  Places beyond n give kSentinel, which f must ignore.
+template <class KeyFn, class F>
+__device__ __forceinline__ void for_each_key_of(KeyFn key_at, int n, F f) {
+    const int nt = blockDim.x;
+    for (int i = threadIdx.x; i < n; i += 8 * nt) {
+        uint64_t key[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) key[u] = i + u * nt < n ? key_at(i + u * nt) : kSentinel;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) f(key[u]);
+    }
+}
+
 // The same for keys addressed by index: key_at(i), i = 0..n-1.
-template <class KeyFn>
-__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, unsigned *s_hist, unsigned long long *s_state, int slack = 0) {
-    auto each = [&](auto f) {
-        for (int i = threadIdx.x; i < n; i += blockDim.x) f(key_at(i));
-    };
-    return block_select_kth_each(each, kth, s_hist, s_state, slack);
+template <class KeyFn, class HistPtr, class StatePtr>
+__device__ uint64_t block_select_kth(KeyFn key_at, int n, int kth, HistPtr s_hist, StatePtr s_state, int slack = 0,
+                                    KeyRange range = KeyRange{false, 0, 0, 0}) {
+    auto each = [&](auto f) { for_each_key_of(key_at, n, f); };
+    return block_select_kth_each(each, kth, s_hist, s_state, slack, range);
 }
 
 // In-place ascending sort of n <= 64 keys in LDS by one wavefront (all 64 lanes call it): one key per lane, bitonic
@@ -366,7 +408,12 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
     }
     if (tid == 0) { o.seg0[nq] = s_carry; if (seg_in_lds) s_seg0[nq] = s_carry; }
     __syncthreads();
-    auto seg_at = [&](int i) { return seg_in_lds ? s_seg0[i] : o.seg0[i]; };
+    // (typed pointers: a choice between two plain pointers would be made first and the load through it be a flat one)
+    typedef __attribute__((address_space(3))) const int32_t lds_ci32;
+    typedef __attribute__((address_space(1))) const int32_t glb_ci32;
+    lds_ci32 *const seg_lds = (lds_ci32 *)s_seg0;
+    glb_ci32 *const seg_glb = (glb_ci32 *)o.seg0;
+    auto seg_at = [&](int i) { return seg_in_lds ? seg_lds[i] : seg_glb[i]; };
     const int total_wg = s_carry;
     if (!act) return;
     for (int w = tid; w < max_wg; w += 256) o.gdone[w] = 0;
@@ -409,8 +456,11 @@ __global__ __launch_bounds__(256) void share_kernel(const int32_t *__restrict__ 
 // publish_keys(): wait until this thread's stores are acknowledged, then meet the workgroup; a counter
 // increment after that tells the others.  No cache-wide write-back or invalidation is involved (a full fence
 // by every finishing workgroup costs far more than the merge itself).
-__device__ __forceinline__ void store_key(uint64_t *p, uint64_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ uint64_t load_key(const uint64_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// (plain pointers, or pointers that name the global address space: see glb_u64)
+template <class P>
+__device__ __forceinline__ void store_key(P p, uint64_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <class P>
+__device__ __forceinline__ uint64_t load_key(P p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void publish_keys() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): loads and stores of this thread are complete
@@ -615,7 +665,16 @@ __global__ __launch_bounds__(NT) void select_probes_kernel(const float *__restri
     // The workgroup that finishes the last query shares the scan workgroups out over the queries (saves a launch):
     // every query's workgroup publishes its number of blocks with a device-scope store, waits for it to complete
     // and adds itself to a counter; the last one reads all the numbers and resets the counter for the next search.
+    // A single query has nobody to wait for (two round trips to memory less).
     __syncthreads();
+    if (nq == 1) {                                           // uniform
+        if (tid == 0) s_ticket = (unsigned)mine.pfx[nprobe];
+        __syncthreads();
+        const long long my_blocks = s_ticket;
+        auto blocks_of = [&](int) { return my_blocks; };
+        share_plan(blocks_of, 1, target, max_wg, share);
+        return;
+    }
     if (tid == 0) {
         __hip_atomic_store(&tb[qi], (uint32_t)mine.pfx[nprobe], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
@@ -1046,18 +1105,28 @@ constexpr int kRankSlack = 128;       // ... among at most this many candidates 
                                       // and lost 4 us at 256, where ranking 384 candidates costs more than the rounds saved)
 
 template <bool FINAL>
-__device__ void select_from_list(const uint64_t *__restrict__ list, int n, int room, int k, uint32_t bound, uint64_t *s_keys,
-                                 unsigned *s_hist, unsigned long long *s_state, unsigned *s_count,
-                                 const int64_t *__restrict__ ids, uint32_t *s_d, int64_t *s_id, float *__restrict__ out_d,
-                                 int64_t *__restrict__ out_i, uint64_t *__restrict__ dst, int KW) {
+__device__ void select_from_list(const uint64_t *list_in_global, int n, int room, int k, uint32_t bound, uint64_t *keys_in_lds,
+                                 unsigned *hist_in_lds, unsigned long long *state_in_lds, unsigned *count_in_lds,
+                                 const int64_t *ids_in_global, uint32_t *d_in_lds, int64_t *id_in_lds, float *out_d_in_global,
+                                 int64_t *out_i_in_global, uint64_t *dst_in_global, int KW) {
+    const glb_u64 *const list = (const glb_u64 *)list_in_global;
+    const glb_i64 *const ids = (const glb_i64 *)ids_in_global;
+    glb_f32 *const out_d = (glb_f32 *)out_d_in_global;
+    glb_i64 *const out_i = (glb_i64 *)out_i_in_global;
+    glb_u64 *const dst = (glb_u64 *)dst_in_global;
+    lds_u64 *const s_keys = (lds_u64 *)keys_in_lds;              // see the comment at lds_u64
+    lds_u32 *const s_hist = (lds_u32 *)hist_in_lds, *const s_count = (lds_u32 *)count_in_lds, *const s_d = (lds_u32 *)d_in_lds;
+    lds_ull *const s_state = (lds_ull *)state_in_lds;
+    lds_i64 *const s_id = (lds_i64 *)id_in_lds;
     const int tid = threadIdx.x, nt = blockDim.x;
     const int k2 = max(2, 1 << (32 - __clz(k - 1)));
     if (FINAL)
         for (int i = tid; i < k2; i += nt) { s_d[i] = 0xFFFFFFFFu; s_id[i] = 0x7FFFFFFFFFFFFFFFll; }
-    if (tid == 0) *s_count = 0;
+    if (tid == 0) { *s_count = 0; s_state[5] = 0xFFFFFFFFull; s_state[6] = 0; }
     __syncthreads();
     const bool in_lds = n <= room;                               // uniform
     int found = n;
+    KeyRange range{false, 0, 0, 0};
     if (in_lds) {
         // 16 keys per thread at a time; the loads of the next 16 are issued before these are looked at, and a wave
         // adds its passing keys of all 16 to the counter at once (one LDS round trip per wave and turn, not 16)
@@ -1067,6 +1136,9 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
 #pragma unroll
             for (int j = 0; j < kPer; ++j) dst[j] = i0 + j * nt < n ? load_key(list + i0 + j * nt) : kSentinel;
         };
+        // (the smallest and the largest distance among the keys gathered are noted on the way: the selection below
+        // then starts from their range without a pass of its own over the keys)
+        uint32_t dmin = 0xFFFFFFFFu, dmax = 0;
         fetch(key, tid);
         for (int i0 = tid; i0 < n + tid; i0 += kPer * nt) {      // i0 - tid < n: the same number of turns for every thread
             const bool more = i0 - tid + kPer * nt < n;          // uniform
@@ -1075,11 +1147,15 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
             unsigned total = 0;
 #pragma unroll
             for (int j = 0; j < kPer; ++j) {
-                mask[j] = __ballot(key[j] != kSentinel && (uint32_t)(key[j] >> 32) <= bound);
+                const uint32_t dj = (uint32_t)(key[j] >> 32);
+                const bool ok = key[j] != kSentinel && dj <= bound;
+                mask[j] = __ballot(ok);
                 total += (unsigned)__popcll(mask[j]);
+                dmin = ok ? min(dmin, dj) : dmin;
+                dmax = ok ? max(dmax, dj) : dmax;
             }
             unsigned at = 0;
-            if ((tid & 63) == 0 && total != 0) at = atomicAdd(s_count, total);
+            if ((tid & 63) == 0 && total != 0) at = lds_add(s_count, total);
             at = __builtin_amdgcn_readfirstlane(at);
             const uint64_t below = (1ull << (tid & 63)) - 1ull;
 #pragma unroll
@@ -1092,8 +1168,15 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
                 for (int j = 0; j < kPer; ++j) key[j] = nxt[j];
             }
         }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            dmin = min(dmin, (uint32_t)__shfl_xor(dmin, off, 64));
+            dmax = max(dmax, (uint32_t)__shfl_xor(dmax, off, 64));
+        }
+        if ((tid & 63) == 0) { lds_min(&s_state[5], (unsigned long long)dmin); lds_max(&s_state[6], (unsigned long long)dmax); }
         __syncthreads();
         found = (int)*s_count;
+        range = KeyRange{true, (uint64_t)s_state[5] << 32, ((uint64_t)s_state[6] << 32) | 0xFFFFFFFFull, (unsigned)found};
         __syncthreads();
     }
     auto key_at = [&](int i) { return in_lds ? s_keys[i] : load_key(list + i); };
@@ -1105,18 +1188,17 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
     // of that run decide, as the order is by (distance, id)).
     const int ncand_max = k + kRankSlack;
     if (FINAL && k <= kRankMaxK && nt >= kRankMaxK && (in_lds ? found + ncand_max <= room || found <= ncand_max : ncand_max <= room)) {   // uniform
-        const uint64_t *c_keys = s_keys;                         // the candidates
+        const lds_u64 *c_keys = s_keys;                          // the candidates
         int m = found;
         if (found > ncand_max || !in_lds) {
             uint64_t T = kSentinel - 1;
-            if (found > ncand_max) T = block_select_kth(key_at, found, k, s_hist, s_state, kRankSlack);
-            uint64_t *c_out = in_lds ? s_keys + found : s_keys;
+            if (found > ncand_max) T = block_select_kth(key_at, found, k, s_hist, s_state, kRankSlack, range);
+            lds_u64 *c_out = in_lds ? s_keys + found : s_keys;
             if (tid == 0) *s_count = 0;
             __syncthreads();
-            for (int i = tid; i < found; i += nt) {
-                const uint64_t key = key_at(i);
-                if (key <= T) c_out[atomicAdd(s_count, 1u)] = key;   // kSentinel > T
-            }
+            for_each_key_of(key_at, found, [&](uint64_t key) {
+                if (key <= T) c_out[lds_add(s_count, 1u)] = key;     // kSentinel > T
+            });
             __syncthreads();
             m = (int)*s_count;
             c_keys = c_out;
@@ -1124,6 +1206,7 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         const int cnt = min(m, k);
         for (int j = tid; j < m; j += nt) {
             const uint64_t mine = c_keys[j];
+            const int64_t id = ids[(uint32_t)mine];              // asked for before the rank is known: the counting covers the wait
             int rank = 0;
             int i = 0;
             for (; i + 8 <= m; i += 8) {                         // reads that all lanes make at the same address
@@ -1134,7 +1217,7 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
                 for (int u = 0; u < 8; ++u) rank += o[u] < mine ? 1 : 0;
             }
             for (; i < m; ++i) rank += c_keys[i] < mine ? 1 : 0;
-            if (rank < k) { s_d[rank] = (uint32_t)(mine >> 32); s_id[rank] = ids[(uint32_t)mine]; }
+            if (rank < k) { s_d[rank] = (uint32_t)(mine >> 32); s_id[rank] = id; }
         }
         __syncthreads();
         for (int r = tid; r < cnt; r += nt) {
@@ -1165,17 +1248,16 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
         return;
     }
     uint64_t T = kSentinel - 1;                                  // no more than k candidates: keep them all
-    if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state, FINAL ? 0 : KW - k);
+    if (found > k) T = block_select_kth(key_at, found, k, s_hist, s_state, FINAL ? 0 : KW - k, range);
     if (tid == 0) *s_count = 0;
     __syncthreads();
-    for (int i = tid; i < found; i += nt) {
-        const uint64_t key = key_at(i);
+    for_each_key_of(key_at, found, [&](uint64_t key) {
         if (key <= T) {                                          // at most k (FINAL) or KW keys qualify (keys are distinct; kSentinel > T)
-            const unsigned slot = atomicAdd(s_count, 1u);
+            const unsigned slot = lds_add(s_count, 1u);
             if (FINAL) { s_d[slot] = (uint32_t)(key >> 32); s_id[slot] = ids[(uint32_t)key]; }
             else store_key(dst + slot, key);
         }
-    }
+    });
     __syncthreads();
     const int cnt = (int)*s_count;
     if (!FINAL) {
@@ -1217,7 +1299,7 @@ __device__ void select_from_list(const uint64_t *__restrict__ list, int n, int r
                 const int64_t id_mine = s_id[mine];
                 for (int jj = j0; jj < j0 + span; ++jj) before += (s_d[jj] == d_mine && s_id[jj] < id_mine) ? 1 : 0;
             }
-            if (before) atomicAdd(&s_hist[mine], (unsigned)before);
+            if (before) lds_add(&s_hist[mine], (unsigned)before);
         }
         __syncthreads();
         if (tid < cnt) {
@@ -1457,7 +1539,18 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // workgroup, without groups) selects the results.  (With local bounds only, a query spread over S workgroups
     // ends with about k keys per workgroup that none of them can rule out; that is what the two levels are for.)
     const int seg = desc.y, S = desc.z, wg0 = wg - seg;          // the query's workgroups: wg0 .. wg0 + S - 1
-    const int fan = a.fan, R = (S + fan - 1) / fan;              // R groups (R = 1: no groups)
+    // Groups: none if one selection takes the keys of all S workgroups (a.fan of them fit its LDS); else groups of about
+    // sqrt(S) workgroups, so that the two levels see about as many keys each - a selection is the work of one compute
+    // unit, a few us per pass over 8,000 keys, and the groups' selections run side by side (512 workgroups in 9 groups
+    // of 58: 20 to 30 us for the first level and 15 for the second; in 23 groups of 23: see the measurements with the
+    // plan) - but no smaller than it takes for the groups' own keys to fit the second selection.
+    int fan = a.fan;
+    if (S > fan) {                                               // uniform; a.fan * a.fan >= S (the host sees to that)
+        int f = 1;
+        while (f * f < S) ++f;
+        fan = min(fan, max(f, (S + fan - 1) / fan));
+    }
+    const int R = (S + fan - 1) / fan;                           // R groups (R = 1: no groups)
     const int r = R == 1 ? 0 : seg / fan, gsize = R == 1 ? S : min(fan, S - r * fan);
     uint64_t *list = a.part + (size_t)(wg0 + r * fan) * KW;      // of the group (of the query, without groups)
     uint32_t *ldone = R == 1 ? &a.qdone[qi] : &a.gdone[wg0 + r];
