@@ -337,13 +337,15 @@ __global__ __launch_bounds__(64) void probe_const_kernel(const float *__restrict
 
 // Shares the scan workgroups out over the queries (one workgroup): query q gets
 // S_q = clamp(ceil(TB_q / per), 1, kMaxSegments) segments, TB_q = its number of blocks and
-// per = ceil(sum of TB / target), so that every workgroup scans about the same number of blocks whatever
+// per = the smallest number of blocks for which these fit the budget of workgroups (found by bisection; about
+// sum of TB / target), so that every workgroup scans about the same number of blocks whatever
 // the lengths of the lists a query probes.  seg0[q] = first workgroup of query q (seg0[nq] = workgroups in
 // use, at most max(target, nq)); desc[w] = (query, number of the workgroup among the query's, their count,
 // chunk counters in use) of workgroup w; desc of spare workgroups has query -1.  A workgroup gets at least
 // kMinBlocksPerWG blocks on average (unless its query has fewer), so that small searches are not spread over
 // needlessly many workgroups.
 constexpr int kShareLdsQueries = 1024;
+constexpr int kChunkBlocks = 4;                       // blocks a scan wave works through per turn of its loop; a chunk is 1, 2, 4 or 8 turns
 struct ShareOut {
     int32_t *seg0;
     int4 *desc;
@@ -374,18 +376,51 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
     for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
     if (act && (tid & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&s_total), (unsigned long long)mine);
     __syncthreads();
+    // Workgroups of a query with tb blocks when a workgroup is to take `per` blocks.
+    auto segments = [&](long long tb, long long per) -> int32_t {
+        int32_t sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
+        // a small scan spread over a few more workgroups than one selection merges would pay a second merge
+        // level for nothing
+        if (sq > o.fan && tb <= (long long)o.fan * kSoftBlocksPerWG) sq = o.fan;
+        return sq;
+    };
     // sum of ceil(TB_q / per) <= total / per + nq, so dividing by (target - nq) keeps the sum within target
     const long long denom = max(1, target - nq);
-    const long long per = max((long long)kMinBlocksPerWG, (s_total + denom - 1) / denom);
+    long long per = max((long long)kMinBlocksPerWG, (s_total + denom - 1) / denom);
+    // That bound leaves up to nq workgroups unused and the queries' shares uneven (a query just above a multiple of
+    // `per` has workgroups with little to do; the launch lasts as long as the fullest workgroup: at 64 queries on 480 of
+    // 512 workgroups the fullest had 14 % more than an even share).  The smallest `per` whose segments still fit the
+    // budget is found by bisection between the even share and that bound, to 1/64 (at most a dozen counts).
+    if (seg_in_lds) {
+        const long long budget = max(target, nq);
+        if (act)
+            for (int q = tid; q < nq; q += 256) s_seg0[q] = (int32_t)min(0x7FFFFFFFll, q < 256 ? first_tb : blocks_of(q));
+        long long lo = max((long long)kMinBlocksPerWG, (s_total + budget - 1) / budget), hi = per;
+        while (hi - lo > (hi >> 6)) {                          // uniform; hi always fits the budget
+            const long long mid = (lo + hi) >> 1;
+            __syncthreads();                                   // s_seg0 written; the last count read
+            if (tid == 0) s_carry = 0;
+            __syncthreads();
+            int32_t c = 0;
+            if (act)
+                for (int q = tid; q < nq; q += 256) c += segments(s_seg0[q], mid);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+            if (act && (tid & 63) == 0) atomicAdd(&s_carry, c);
+            __syncthreads();
+            if (s_carry <= budget) hi = mid; else lo = mid + 1;
+        }
+        per = hi;
+        __syncthreads();
+        if (tid == 0) s_carry = 0;
+        __syncthreads();
+    }
     for (int q0 = 0; q0 < nq; q0 += 256) {
         const int q = q0 + tid;
         int32_t sq = 0;
         if (act && q < nq) {
             const long long tb = q0 == 0 ? first_tb : blocks_of(q);
-            sq = (int32_t)min((long long)kMaxSegments, max(1ll, (tb + per - 1) / per));
-            // a small scan spread over a few more workgroups than one selection merges would pay a second merge
-            // level for nothing
-            if (sq > o.fan && tb <= (long long)o.fan * kSoftBlocksPerWG) sq = o.fan;
+            sq = segments(tb, per);
         }
         int32_t incl = sq;                                 // inclusive scan: within the wave, then over the four waves
 #pragma unroll
@@ -436,9 +471,17 @@ __device__ void share_plan(BlocksOf blocks_of, int nq, int target, int max_wg, S
         // 16 GiB of codes) - as long as every wave still gets several of them, or the last chunks decide when the
         // query ends (one query over 512 workgroups: 8 blocks best, 32 blocks 13 % slower), and none when a wave has
         // fewer than 8 blocks to scan in all.
-        const long long per_wave = blocks_of(lo) / W;
+        const long long tbq = blocks_of(lo), per_wave = tbq / W;
         const int lg = per_wave < 8 ? 0 : (per_wave < 64 ? 1 : (per_wave < 128 ? 2 : 3));
-        o.desc[w] = int4{lo, seg, S, P | (lg << 8)};
+        // The query's last W chunks' worth of blocks are handed out in chunks of kChunkBlocks instead: the query is over
+        // when the wave that took the last chunk is through with it, and with whole chunks to the end the other waves
+        // waited for it about a chunk's time (8 blocks: 10 to 14 us of a 64-query scan that takes 100; afterwards 3 to
+        // 5).  full = number of chunks of full length, counted from the front.  Only where a wave gets four full chunks
+        // at least: 16 queries at 4,096 lists, 15 blocks per wave, took 79 instead of 63 us with half of their blocks
+        // in short chunks.
+        const long long len = (long long)kChunkBlocks << lg;
+        const int full = per_wave < 32 ? 0x3FFFFFFF : (int)min(0x3FFFFFFFll, max(0ll, tbq / len - W));
+        o.desc[w] = int4{lo, seg | (S << 16), full, P | (lg << 8)};
         if (seg == 0)
             for (int c = 0; c < P; ++c) o.ctr[((size_t)lo * kCtrPerQuery + c) * kCtrStride] = (uint32_t)((W - c + P - 1) / P);
     }
@@ -744,7 +787,6 @@ constexpr int kKeepSlack = 64;                        // pruning keeps between k
 constexpr int kCandRoom = 1472;                       // candidate slots beyond k + kKeepSlack, at most
 constexpr int kCandRoomMin = 512;                     // and at least (the scan needs more than kScanThreads)
 constexpr int kCandPerThread = (kMaxK + kKeepSlack + kCandRoom + kScanThreads - 1) / kScanThreads;
-constexpr int kChunkBlocks = 4;                       // blocks a scan wave works through per turn of its loop; a chunk is 1, 2, 4 or 8 turns
 
 // LDS carve-up of the scan kernel (all dynamic, so that the table starts at address 0)
 struct ScanLds {
@@ -1371,7 +1413,7 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // one L2 rather than eight, was measured: 6 % faster at 32 queries, 3 % slower at 64 queries x 256 probes, equal
     // elsewhere - not kept.)
     const int wg = blockIdx.x;
-    const int4 desc = a.desc[wg];                            // (query, number among its workgroups, their count, counters)
+    const int4 desc = a.desc[wg];            // (query, number among its workgroups | their count << 16, full-length chunks, counters and chunk length)
     if (desc.x < 0) return;                                  // spare workgroup (uniform exit)
     const int qi = desc.x;
     const bool lut_at_zero =
@@ -1400,8 +1442,14 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // (the zero below is lane-dependent as far as the compiler can tell: an address it knows to be the same in
     // all lanes makes it combine the lanes' additions and fetch the answer at once, which would wait for every
     // load in flight)
-    const int wave_of_query = desc.y * kScanWaves + wave, nctr = desc.w & 0xFF, my_ctr = wave_of_query % nctr;
-    const int tpc = 1 << (desc.w >> 8), chunk_len = kChunkBlocks * tpc;   // a chunk is tpc turns of kChunkBlocks blocks
+    const int wave_of_query = (desc.y & 0xFFFF) * kScanWaves + wave, nctr = desc.w & 0xFF, my_ctr = wave_of_query % nctr;
+    const int tpc = 1 << (desc.w >> 8), chunk_len = kChunkBlocks * tpc;   // a chunk is tpc turns of kChunkBlocks blocks ...
+    const int full = desc.z;                                 // ... up to chunk number `full`; from there on, one turn
+    // first block of chunk c, and its number of turns
+    auto chunk_at = [&](int c, int &turns) -> int {
+        turns = c < full ? tpc : 1;
+        return c < full ? c * chunk_len : (int)((unsigned)full * (unsigned)chunk_len + (unsigned)(c - full) * kChunkBlocks);
+    };
     uint32_t *ctr = a.ctr + ((size_t)qi * kCtrPerQuery + my_ctr) * kCtrStride + __builtin_amdgcn_mbcnt_lo(0u, 0u);
     int pi = 0;                     // probe whose list holds the block looked up last (chunks only move forward)
     auto ask_chunk = [&]() -> uint32_t {
@@ -1464,7 +1512,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
 
     uint4 w[NSETS][C];
     Meta meta[NSETS];
-    int cb = wave_of_query * chunk_len;                      // first block of the turn being requested (of the wave's own first chunk)
+    int turns;                                               // turns of the chunk being requested (the wave's own first chunk to begin with)
+    int cb = chunk_at(wave_of_query, turns);                 // first block of the turn being requested
     int turn = 0;                                            // which turn of its chunk that is
     uint32_t pending = ask_chunk();
     // the query's bound is polled once per chunk, with the chunk request, and used one turn later
@@ -1503,10 +1552,10 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
         for (int j = 0; j < kChunkBlocks; ++j) {
             const int i = j % NSETS, pos = (NSETS + j) % kChunkBlocks;   // position of the request within its chunk
             if (pos == 0) {
-                if (++turn == tpc) {                         // uniform: the chunk is used up, on to the one asked for
+                if (++turn == turns) {                       // uniform: the chunk is used up, on to the one asked for
                     turn = 0;
                     const uint32_t v = min(__builtin_amdgcn_readfirstlane(pending), 0x7FFFFFFFu / (kChunkBlocks * 8 * kCtrPerQuery) - 1u);
-                    cb = (int)(v * nctr + my_ctr) * chunk_len;
+                    cb = chunk_at((int)(v * nctr + my_ctr), turns);
                     pending = ask_chunk();
                     thr = min(thr, ((uint64_t)tg << 32) | 0xFFFFFFFFull);
                     tg = __hip_atomic_load(&a.thr[qi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1538,7 +1587,7 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // the group's k best on to the query's list in the same way, and the last group of the query (or its last
     // workgroup, without groups) selects the results.  (With local bounds only, a query spread over S workgroups
     // ends with about k keys per workgroup that none of them can rule out; that is what the two levels are for.)
-    const int seg = desc.y, S = desc.z, wg0 = wg - seg;          // the query's workgroups: wg0 .. wg0 + S - 1
+    const int seg = desc.y & 0xFFFF, S = desc.y >> 16, wg0 = wg - seg;   // the query's workgroups: wg0 .. wg0 + S - 1
     // Groups: none if one selection takes the keys of all S workgroups (a.fan of them fit its LDS); else groups of about
     // sqrt(S) workgroups, so that the two levels see about as many keys each - a selection is the work of one compute
     // unit, a few us per pass over 8,000 keys, and the groups' selections run side by side (512 workgroups in 9 groups
