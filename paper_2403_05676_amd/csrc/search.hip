@@ -138,8 +138,9 @@ __device__ uint64_t block_select_kth_each(ForEach for_each_key, int kth, HistPtr
 }
 
 // f(key) for the keys key_at(i), i = 0..n-1, shared out over the workgroup's threads; a thread reads eight of its keys
-// at a time, so that the reads (LDS or global memory) overlap: one key per turn costs a full read latency per key,
-// 3.3 us for a pass over 8,000 keys in LDS.  Places beyond n give kSentinel, which f must ignore.
+// at a time, so that the reads (LDS or global memory) overlap.  (A pass over 8,000 keys in LDS by 256 threads takes
+// about 3 us either way: four wavefronts that issue one instruction per four cycles each; it is the reads from
+// global memory that gain.)  Places beyond n give kSentinel, which f must ignore.
 template <class KeyFn, class F>
 __device__ __forceinline__ void for_each_key_of(KeyFn key_at, int n, F f) {
     const int nt = blockDim.x;
@@ -1384,7 +1385,7 @@ __host__ __device__ inline int reduce_room_keys(int Mp, int cap, int k) {
 // Stage 3: scan of the probed lists with candidate selection.
 // The probed lists of a query, concatenated in probe order, form a sequence of 64-vector blocks; the plan
 // gives every workgroup a query, and the waves of a query's workgroups take that sequence in chunks of
-// 4 to 32 blocks (the plan fixes the length per query) from shared counters.  A lane owns one vector of the block: it reads its Mp code bytes
+// 4 to 32 blocks (the plan fixes the length per query, and how many chunks have it: the last ones are 4 blocks) from shared counters.  A lane owns one vector of the block: it reads its Mp code bytes
 // with Mp/16 16-byte loads (NSETS blocks are kept in flight per wave) and adds Mp table entries from LDS.
 // Because of the rotated code layout (see common.h), at step t lane l looks up sub-quantiser (l + t) mod Mp,
 // so with the table stored [j][Mp] the lanes of a half-wave hit different LDS banks when Mp is 32 or 64.
@@ -1591,8 +1592,8 @@ __global__ __launch_bounds__(kScanThreads, 2) void adc_scan_kernel(ScanArgs a) {
     // Groups: none if one selection takes the keys of all S workgroups (a.fan of them fit its LDS); else groups of about
     // sqrt(S) workgroups, so that the two levels see about as many keys each - a selection is the work of one compute
     // unit, a few us per pass over 8,000 keys, and the groups' selections run side by side (512 workgroups in 9 groups
-    // of 58: 20 to 30 us for the first level and 15 for the second; in 23 groups of 23: see the measurements with the
-    // plan) - but no smaller than it takes for the groups' own keys to fit the second selection.
+    // of 58: 20 to 30 us for the first level and 15 for the second; in 23 groups of 23: 10 to 13 and 16 to 21) - but no
+    // smaller than it takes for the groups' own keys to fit the second selection.
     int fan = a.fan;
     if (S > fan) {                                               // uniform; a.fan * a.fan >= S (the host sees to that)
         int f = 1;
